@@ -1,0 +1,203 @@
+"""CPU float64 oracle of the token-importance pass (test infrastructure).
+
+Thin ctypes wrapper over ``sp_oracle.c``: the arithmetic lives in the C file,
+this module only marshals numpy arrays. Only tests, the smoke check and the
+benchmark's CPU-baseline leg may import it; the GPU library never does, and
+this module imports nothing from the GPU package.
+
+Citations (paper sections) are given per function in ``sp_oracle.c``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "sp_oracle.c")
+_LIB = os.path.join(_DIR, "libsp_oracle.so")
+
+LAYER_MEAN = 0
+LAYER_MAX = 1
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (``-O2``, OpenMP over rows, no hand vectorisation)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11",
+                               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB):
+        build(force=True)
+    lib = ctypes.CDLL(_LIB)
+    c = ctypes
+    P = c.c_void_p
+    lib.sp_oracle_max_threads.restype = c.c_int
+    lib.sp_oracle_set_threads.argtypes = [c.c_int]
+    lib.sp_oracle_logits_layer.argtypes = [P, P, c.c_int64, c.c_int64, c.c_int, c.c_int, c.c_int,
+                                           c.c_int, c.c_int64, c.c_double, P]
+    lib.sp_oracle_softmax_rows.argtypes = [P, c.c_int64, c.c_int64, P, P]
+    lib.sp_oracle_score.argtypes = [P, P, c.c_int64, c.c_int64, c.c_int, c.c_int, c.c_int, c.c_int,
+                                    c.c_int, c.c_int64, c.c_double, c.c_int, P]
+    lib.sp_oracle_pool.argtypes = [P, c.c_int64, c.c_int, P]
+    lib.sp_oracle_chunk_mean.argtypes = [P, c.c_int64, c.c_int, P]
+    lib.sp_oracle_keep_count.argtypes = [c.c_int64, c.c_int64, c.c_int64]
+    lib.sp_oracle_keep_count.restype = c.c_int64
+    lib.sp_oracle_topk.argtypes = [P, c.c_int64, c.c_int64, P]
+    lib.sp_oracle_merge.argtypes = [P, c.c_int64, c.c_int, c.c_int64, P]
+    lib.sp_oracle_merge.restype = c.c_int64
+    lib.sp_oracle_project.argtypes = [P, c.c_int64, P, c.c_int64, P, c.c_int64, P, P, P, P]
+    _lib = lib
+    return lib
+
+
+def _ptr(a: np.ndarray):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"oracle {what}: invalid arguments (code {rc})")
+
+
+def max_threads() -> int:
+    return int(_load().sp_oracle_max_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().sp_oracle_set_threads(int(n))
+
+
+def _k_strides(k_layer: np.ndarray, layout: str) -> Tuple[int, int, int, int, int]:
+    """(stride_token, stride_head, Hkv, L, d) in elements for a contiguous layer array."""
+    if layout == "HND":
+        hkv, L, d = k_layer.shape
+        return d, L * d, hkv, L, d
+    if layout == "NHD":
+        L, hkv, d = k_layer.shape
+        return hkv * d, d, hkv, L, d
+    raise ValueError("layout must be 'HND' or 'NHD'")
+
+
+def logits_layer(q_layer: np.ndarray, k_layer: np.ndarray, scale: float, layout: str = "HND") -> np.ndarray:
+    """Scaled logits of one layer, float64 [H][n_q][L]. q_layer: uint16 [H][n_q][d]."""
+    q_layer = np.ascontiguousarray(q_layer, dtype=np.uint16)
+    k_layer = np.ascontiguousarray(k_layer, dtype=np.uint16)
+    H, n_q, d = q_layer.shape
+    st, sh, hkv, L, dk = _k_strides(k_layer, layout)
+    if dk != d:
+        raise ValueError("head_dim mismatch")
+    s = np.empty((H, n_q, L), dtype=np.float64)
+    _check(_load().sp_oracle_logits_layer(_ptr(q_layer), _ptr(k_layer), st, sh, H, hkv, n_q, d, L,
+                                          float(scale), _ptr(s)), "logits_layer")
+    return s
+
+
+def softmax_rows(s: np.ndarray, return_stats: bool = False):
+    """Row softmax over the last axis (copy). Optionally also (row_max, row_sum)."""
+    p = np.array(s, dtype=np.float64, order="C", copy=True)
+    L = p.shape[-1]
+    rows = p.size // L
+    m = np.empty(rows, dtype=np.float64)
+    l = np.empty(rows, dtype=np.float64)
+    _check(_load().sp_oracle_softmax_rows(_ptr(p), rows, L, _ptr(m), _ptr(l)), "softmax_rows")
+    if return_stats:
+        return p, m.reshape(p.shape[:-1]), l.reshape(p.shape[:-1])
+    return p
+
+
+def score(q: np.ndarray, k_layers: Sequence[np.ndarray], scale: float, layer_agg: int = LAYER_MEAN,
+          layout: str = "HND") -> np.ndarray:
+    """Token importance I[L] (float64). q: uint16 [Lyr][H][n_q][d]; k_layers: list of uint16 layer arrays."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    Lyr, H, n_q, d = q.shape
+    if len(k_layers) != Lyr:
+        raise ValueError("need one K array per layer")
+    ks = [np.ascontiguousarray(k, dtype=np.uint16) for k in k_layers]
+    st, sh, hkv, L, dk = _k_strides(ks[0], layout)
+    for k in ks:
+        if k.shape != ks[0].shape:
+            raise ValueError("K layers must share a shape")
+    if dk != d:
+        raise ValueError("head_dim mismatch")
+    ptrs = (ctypes.c_void_p * Lyr)(*[k.ctypes.data for k in ks])
+    out = np.empty(L, dtype=np.float64)
+    _check(_load().sp_oracle_score(_ptr(q), ctypes.cast(ptrs, ctypes.c_void_p), st, sh, Lyr, H, hkv, n_q,
+                                   d, L, float(scale), int(layer_agg), _ptr(out)), "score")
+    return out
+
+
+def pool(I: np.ndarray, w: int) -> np.ndarray:
+    I = np.ascontiguousarray(I, dtype=np.float64)
+    out = np.empty_like(I)
+    _check(_load().sp_oracle_pool(_ptr(I), I.size, int(w), _ptr(out)), "pool")
+    return out
+
+
+def chunk_mean(P: np.ndarray, c: int) -> np.ndarray:
+    P = np.ascontiguousarray(P, dtype=np.float64)
+    if int(c) < 1:
+        raise ValueError("oracle chunk_mean: chunk must be >= 1")
+    C = (P.size + c - 1) // c
+    out = np.empty(C, dtype=np.float64)
+    _check(_load().sp_oracle_chunk_mean(_ptr(P), P.size, int(c), _ptr(out)), "chunk_mean")
+    return out
+
+
+def keep_count(C: int, num: int, den: int) -> int:
+    k = int(_load().sp_oracle_keep_count(int(C), int(num), int(den)))
+    if k < 0:
+        raise ValueError("oracle keep_count: invalid arguments")
+    return k
+
+
+def topk(cs: np.ndarray, k: int) -> np.ndarray:
+    cs = np.ascontiguousarray(cs, dtype=np.float64)
+    if not (1 <= int(k) <= cs.size):
+        raise ValueError("oracle topk: k out of range")
+    sel = np.empty(int(k), dtype=np.int64)
+    _check(_load().sp_oracle_topk(_ptr(cs), cs.size, int(k), _ptr(sel)), "topk")
+    return sel
+
+
+def merge(sel: np.ndarray, c: int, L: int) -> np.ndarray:
+    sel = np.ascontiguousarray(sel, dtype=np.int64)
+    spans = np.empty((max(sel.size, 1), 2), dtype=np.int64)
+    n = int(_load().sp_oracle_merge(_ptr(sel), sel.size, int(c), int(L), _ptr(spans)))
+    if n < 0:
+        raise ValueError("oracle merge: invalid arguments")
+    return spans[:n].copy()
+
+
+def project(draft_off: np.ndarray, target_off: np.ndarray, spans: np.ndarray):
+    """Returns (target_spans [n][2] int64, keep_mask [M] uint8, n_kept)."""
+    draft_off = np.ascontiguousarray(draft_off, dtype=np.int64)
+    target_off = np.ascontiguousarray(target_off, dtype=np.int64)
+    spans = np.ascontiguousarray(spans, dtype=np.int64).reshape(-1, 2)
+    L, M = draft_off.size - 1, target_off.size - 1
+    mask = np.zeros(max(M, 1), dtype=np.uint8)
+    tspans = np.empty((max(M, 1), 2), dtype=np.int64)
+    n_t = np.zeros(1, dtype=np.int64)
+    n_k = np.zeros(1, dtype=np.int64)
+    _check(_load().sp_oracle_project(_ptr(draft_off), L, _ptr(target_off), M, _ptr(spans), spans.shape[0],
+                                     _ptr(mask), _ptr(tspans), _ptr(n_t), _ptr(n_k)), "project")
+    return tspans[: int(n_t[0])].copy(), mask[:M], int(n_k[0])
+
+
+def select(I: np.ndarray, w: int, c: int, k: int):
+    """Pool -> chunk means -> top-k -> merge. Returns (sel, spans, chunk_scores)."""
+    cs = chunk_mean(pool(I, w), c)
+    sel = topk(cs, k)
+    return sel, merge(sel, c, I.size), cs

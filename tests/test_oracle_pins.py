@@ -1,0 +1,550 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+The paper prints no worked numerical example for the token-importance pass
+(Appendix A.1 describes it in words; Appendix A.3 gives only the
+hyper-parameters), so every function of the oracle is pinned here by closed
+forms, invariants, library routines (numpy / scipy) on special cases, and brute
+force on tiny inputs. Each test names the mistake it is meant to catch.
+"""
+from __future__ import annotations
+
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+
+import oracle
+import synth
+from synth import bf16_bits_to_f32, f32_to_bf16_bits
+
+
+def bits(x):
+    return f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def rand_small_ints(rng, shape, lo=-3, hi=3):
+    """Small integers: exactly representable in bf16, sums exact in float64."""
+    return rng.integers(lo, hi + 1, size=shape).astype(np.float32)
+
+
+def make_qk(rng, Lyr, H, Hkv, n_q, d, L, q_scale=0.25):
+    q = rand_small_ints(rng, (Lyr, H, n_q, d)) * np.float32(q_scale)
+    k = [rand_small_ints(rng, (Hkv, L, d)) for _ in range(Lyr)]
+    return q, k
+
+
+# --------------------------------------------------------------------------
+# softmax / logits  (Appendix A.1.1)
+# --------------------------------------------------------------------------
+
+def test_softmax_rows_sum_to_one_and_stats():
+    """O1: every probability row sums to 1; returned (max, sum) are the row's own."""
+    rng = np.random.default_rng(1)
+    s = rng.normal(size=(5, 7, 301)) * 6.0
+    p, m, l = oracle.softmax_rows(s, return_stats=True)
+    np.testing.assert_allclose(p.sum(-1), 1.0, rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(m, s.max(-1))
+    np.testing.assert_allclose(l, np.exp(s - m[..., None]).sum(-1), rtol=1e-13)
+    assert (p > 0).all()
+
+
+def test_single_row_equals_library_softmax_of_matmul():
+    """O8: with one layer, one head, one lookahead row the importance vector is a
+    softmax row; it must equal scipy's float64 softmax of numpy's matmul.
+    Catches a wrong scale, a transposed operand, a wrong stride."""
+    rng = np.random.default_rng(2)
+    d, L = 64, 257
+    qf = rng.standard_normal((1, 1, 1, d)).astype(np.float32)
+    kf = rng.standard_normal((1, L, d)).astype(np.float32)
+    qb, kb = bits(qf), bits(kf)
+    scale = 0.125
+    I = oracle.score(qb, [kb], scale, oracle.LAYER_MAX)
+    ref = scipy.special.softmax(scale * (bf16_bits_to_f32(kb[0]).astype(np.float64)
+                                         @ bf16_bits_to_f32(qb[0, 0, 0]).astype(np.float64)))
+    np.testing.assert_allclose(I, ref, rtol=1e-12, atol=0)
+    I2 = oracle.score(qb, [kb], scale, oracle.LAYER_MEAN)
+    np.testing.assert_allclose(I2, ref, rtol=1e-12, atol=0)
+    # token-major layout of the same keys gives the same result (stride handling)
+    k_nhd = np.ascontiguousarray(kb.transpose(1, 0, 2))
+    np.testing.assert_allclose(oracle.score(qb, [k_nhd], scale, 0, layout="NHD"), ref, rtol=1e-12)
+
+
+def test_logits_match_library_contraction_with_gqa_groups():
+    """Logits of a multi-head GQA layer against numpy einsum per kv group.
+    Catches a wrong head -> kv-head mapping and index mix-ups."""
+    rng = np.random.default_rng(3)
+    H, Hkv, n_q, d, L = 6, 3, 4, 32, 50
+    qf, kf = make_qk(rng, 1, H, Hkv, n_q, d, L)
+    s = oracle.logits_layer(bits(qf[0]), bits(kf[0]), 0.3)
+    G = H // Hkv
+    q64 = bf16_bits_to_f32(bits(qf[0])).astype(np.float64)
+    k64 = bf16_bits_to_f32(bits(kf[0])).astype(np.float64)
+    ref = np.stack([0.3 * np.einsum("ne,je->nj", q64[h], k64[h // G]) for h in range(H)])
+    np.testing.assert_allclose(s, ref, rtol=1e-13, atol=1e-13)
+
+
+def test_uniform_keys_give_uniform_scores_and_lowest_index_selection():
+    """O2: identical keys (or all-zero K) give I[j] = 1/L in both modes; the pooled
+    interior equals 1/L; tied chunk scores select the lowest indices."""
+    rng = np.random.default_rng(4)
+    Lyr, H, Hkv, n_q, d, L = 3, 4, 2, 5, 16, 416
+    qf, _ = make_qk(rng, Lyr, H, Hkv, n_q, d, L)
+    krow = rand_small_ints(rng, (Hkv, 1, d))
+    for kf in ([np.repeat(krow, L, axis=1)] * Lyr, [np.zeros((Hkv, L, d), np.float32)] * Lyr):
+        for mode in (oracle.LAYER_MEAN, oracle.LAYER_MAX):
+            I = oracle.score(bits(qf), [bits(k) for k in kf], 0.25, mode)
+            np.testing.assert_allclose(I, 1.0 / L, rtol=1e-12)
+    I = np.full(L, 1.0 / L)
+    P = oracle.pool(I, 13)
+    np.testing.assert_allclose(P[6:L - 6], 1.0 / L, rtol=1e-13)
+    # interior chunks (those not touching the 6-token edges) tie exactly when
+    # the input is a constant whose window sum is exact: use a power of two.
+    I2 = np.full(L, 2.0 ** -9)
+    sel, spans, cs = oracle.select(I2, 13, 32, 4)
+    C = L // 32
+    assert np.all(cs[1:C - 1] == cs[1])
+    assert cs[0] < cs[1] and cs[C - 1] < cs[1]
+    np.testing.assert_array_equal(sel, [1, 2, 3, 4])
+    np.testing.assert_array_equal(spans, [[32, 160]])
+
+
+def test_single_dominant_key_closed_form():
+    """O3: K = 0 except one position j*: p(j*) = e^a / (e^a + L - 1), others
+    1 / (e^a + L - 1), a = scale * q.k*. A large a lets the key capture the score."""
+    d, L, jstar = 16, 100, 37
+    q = np.zeros((1, 1, 1, d), np.float32)
+    q[..., :4] = [1.0, -2.0, 0.5, 3.0]
+    k = np.zeros((1, L, d), np.float32)
+    k[0, jstar, :4] = [2.0, -1.0, 4.0, 1.0]
+    scale = 0.5
+    a = scale * (2.0 + 2.0 + 2.0 + 3.0)
+    I = oracle.score(bits(q), [bits(k)], scale, oracle.LAYER_MAX)
+    den = np.exp(a) + L - 1
+    expect = np.full(L, 1.0 / den)
+    expect[jstar] = np.exp(a) / den
+    np.testing.assert_allclose(I, expect, rtol=1e-13)
+    k[0, jstar, :4] *= 16.0      # a -> 72: the key takes all the mass
+    I = oracle.score(bits(q), [bits(k)], scale, oracle.LAYER_MAX)
+    assert 1.0 - 1e-15 <= I[jstar] <= 1.0
+    assert np.delete(I, jstar).max() < 1e-29
+
+
+def test_two_level_keys_closed_form_with_head_max():
+    """O4: keys take two values; with two heads attending oppositely the max over
+    heads has a closed form. Catches a max taken before the normalisation."""
+    d, L, n1 = 8, 60, 20
+    q = np.zeros((1, 2, 1, d), np.float32)
+    q[0, 0, 0, 0] = 2.0       # head 0 likes key type A
+    q[0, 1, 0, 1] = 1.0       # head 1 likes key type B
+    k = np.zeros((1, L, d), np.float32)
+    k[0, :n1, 0] = 1.5        # type A: first n1 keys
+    k[0, n1:, 1] = 2.0        # type B
+    I = oracle.score(bits(q), [bits(k)], 1.0, oracle.LAYER_MAX)   # H=2, Hkv=1
+    a, b = 3.0, 2.0
+    pA0 = np.exp(a) / (n1 * np.exp(a) + (L - n1))      # head 0 on type A
+    pB0 = 1.0 / (n1 * np.exp(a) + (L - n1))
+    pA1 = 1.0 / (n1 + (L - n1) * np.exp(b))            # head 1 on type A
+    pB1 = np.exp(b) / (n1 + (L - n1) * np.exp(b))
+    expect = np.concatenate([np.full(n1, max(pA0, pA1)), np.full(L - n1, max(pB0, pB1))])
+    np.testing.assert_allclose(I, expect, rtol=1e-13)
+    assert pA0 > pA1 and pB1 > pB0      # the max really switches head
+
+
+def test_shift_invariance_large_offset():
+    """O5: adding one vector to every key shifts each row's logits by a constant
+    and must not change the scores, even when the shift is huge (max-subtraction)."""
+    rng = np.random.default_rng(5)
+    Lyr, H, Hkv, n_q, d, L = 2, 4, 2, 3, 16, 90
+    qf, kf = make_qk(rng, Lyr, H, Hkv, n_q, d, L, q_scale=1.0)
+    v = rng.choice([-64.0, 64.0], size=(1, 1, d)).astype(np.float32)   # |k+v| <= 67: exact in bf16
+    base = oracle.score(bits(qf), [bits(k) for k in kf], 1.0, oracle.LAYER_MEAN)
+    shifted = oracle.score(bits(qf), [bits(k + v) for k in kf], 1.0, oracle.LAYER_MEAN)
+    assert np.isfinite(shifted).all()
+    np.testing.assert_allclose(shifted, base, rtol=1e-10)
+
+
+def test_key_permutation_permutes_scores():
+    """O6."""
+    rng = np.random.default_rng(6)
+    Lyr, H, Hkv, n_q, d, L = 2, 4, 2, 3, 16, 77
+    qf, kf = make_qk(rng, Lyr, H, Hkv, n_q, d, L)
+    perm = rng.permutation(L)
+    for mode in (0, 1):
+        a = oracle.score(bits(qf), [bits(k) for k in kf], 0.25, mode)
+        b = oracle.score(bits(qf), [bits(k[:, perm]) for k in kf], 0.25, mode)
+        np.testing.assert_allclose(b, a[perm], rtol=1e-12)
+
+
+def test_gqa_equals_replicated_kv_heads():
+    """O7: query head h reads kv head h // G. Replicating each kv head G times and
+    running as multi-head attention gives the same scores."""
+    rng = np.random.default_rng(7)
+    Lyr, H, Hkv, n_q, d, L = 2, 8, 2, 3, 16, 64
+    G = H // Hkv
+    qf, kf = make_qk(rng, Lyr, H, Hkv, n_q, d, L)
+    rep = [np.repeat(k, G, axis=0) for k in kf]
+    for mode in (0, 1):
+        a = oracle.score(bits(qf), [bits(k) for k in kf], 0.25, mode)
+        b = oracle.score(bits(qf), [bits(k) for k in rep], 0.25, mode)
+        np.testing.assert_allclose(a, b, rtol=1e-13)
+    # and the mapping is not h % Hkv: interleaving the replicas must change it
+    wrong = [np.tile(k, (G, 1, 1)) for k in kf]
+    c = oracle.score(bits(qf), [bits(k) for k in wrong], 0.25, 0)
+    assert np.abs(c - a).max() > 1e-6
+
+
+def test_head_max_identity_via_logsumexp():
+    """O9: max_h softmax_h(s)[j] = exp(max_h (s_h[j] - lse_h)); checked through the
+    oracle's own logits and row statistics against its aggregated score."""
+    rng = np.random.default_rng(8)
+    H, Hkv, n_q, d, L = 4, 2, 3, 16, 120
+    qf, kf = make_qk(rng, 1, H, Hkv, n_q, d, L)
+    s = oracle.logits_layer(bits(qf[0]), bits(kf[0]), 0.25)
+    lse = scipy.special.logsumexp(s, axis=-1)
+    via_lse = np.exp((s - lse[..., None]).max(axis=0)).mean(axis=0)
+    I = oracle.score(bits(qf), [bits(kf[0])], 0.25, oracle.LAYER_MAX)
+    np.testing.assert_allclose(I, via_lse, rtol=1e-12)
+
+
+def test_aggregation_modes_definition_and_bounds():
+    """O10 and the two aggregation modes written out with numpy on the oracle's
+    probabilities: mean mode averages the per-layer head-max over layers and
+    lookahead rows; max mode takes the max over layers too. Bounds: 0 < I <= 1,
+    1 <= sum I <= H (mean) or H*Lyr (max), I_max >= I_mean, and duplicating a
+    layer changes neither mode."""
+    rng = np.random.default_rng(9)
+    Lyr, H, Hkv, n_q, d, L = 3, 4, 2, 5, 16, 150
+    qf, kf = make_qk(rng, Lyr, H, Hkv, n_q, d, L)
+    qb, kb = bits(qf), [bits(k) for k in kf]
+    p = np.stack([oracle.softmax_rows(oracle.logits_layer(qb[l], kb[l], 0.25)) for l in range(Lyr)])
+    head_max = p.max(axis=1)                     # p is [Lyr][H][n_q][L] -> [Lyr][n_q][L]
+    mean_ref = head_max.mean(axis=(0, 1))
+    max_ref = head_max.max(axis=0).mean(axis=0)
+    I_mean = oracle.score(qb, kb, 0.25, oracle.LAYER_MEAN)
+    I_max = oracle.score(qb, kb, 0.25, oracle.LAYER_MAX)
+    np.testing.assert_allclose(I_mean, mean_ref, rtol=1e-13)
+    np.testing.assert_allclose(I_max, max_ref, rtol=1e-13)
+    assert (I_mean > 0).all() and (I_max <= 1).all()
+    assert 1 - 1e-12 <= I_mean.sum() <= H + 1e-12
+    assert 1 - 1e-12 <= I_max.sum() <= H * Lyr + 1e-12
+    assert (I_max >= I_mean - 1e-15).all()
+    q2 = np.concatenate([qb, qb[-1:]], axis=0)
+    k2 = kb + [kb[-1]]
+    np.testing.assert_allclose(oracle.score(q2, k2, 0.25, 1), I_max, rtol=1e-13)
+    # duplicating a layer leaves the max mode alone and re-weights the mean mode
+    dup_mean = (head_max.sum(axis=0) + head_max[-1]).mean(axis=0) / (Lyr + 1)
+    np.testing.assert_allclose(oracle.score(q2, k2, 0.25, 0), dup_mean, rtol=1e-13)
+    # duplicating every layer changes neither mode
+    q3, k3 = np.concatenate([qb, qb], axis=0), kb + kb
+    np.testing.assert_allclose(oracle.score(q3, k3, 0.25, 0), I_mean, rtol=1e-13)
+    np.testing.assert_allclose(oracle.score(q3, k3, 0.25, 1), I_max, rtol=1e-13)
+
+
+def test_split_row_statistics_merge_by_logsumexp():
+    """O11: statistics (m, l) of two halves of a row merged by log-sum-exp equal
+    those of the whole row: the identity a split-L streaming pass relies on."""
+    rng = np.random.default_rng(10)
+    s = rng.normal(size=(6, 400)) * 8
+    _, m, l = oracle.softmax_rows(s, return_stats=True)
+    _, m1, l1 = oracle.softmax_rows(s[:, :123], return_stats=True)
+    _, m2, l2 = oracle.softmax_rows(s[:, 123:], return_stats=True)
+    M = np.maximum(m1, m2)
+    np.testing.assert_array_equal(M, m)
+    np.testing.assert_allclose(l1 * np.exp(m1 - M) + l2 * np.exp(m2 - M), l, rtol=1e-13)
+
+
+def test_scale_is_applied_inside_the_exponent():
+    """Doubling the scale equals doubling the queries (a power of two is exact in
+    bf16). Catches a scale applied after the softmax or dropped."""
+    rng = np.random.default_rng(11)
+    qf, kf = make_qk(rng, 2, 4, 2, 3, 16, 70)
+    a = oracle.score(bits(qf * 2), [bits(k) for k in kf], 0.125, 0)
+    b = oracle.score(bits(qf), [bits(k) for k in kf], 0.25, 0)
+    np.testing.assert_allclose(a, b, rtol=1e-13)
+    c = oracle.score(bits(qf), [bits(k) for k in kf], 0.125, 0)
+    assert np.abs(c - b).max() > 1e-6
+
+
+# --------------------------------------------------------------------------
+# pooling and chunk means  (Algorithm 1, Appendix A.1.2, Appendix A.3)
+# --------------------------------------------------------------------------
+
+def test_pool_impulse_and_textbook_convolution():
+    """O12: an interior unit impulse spreads to w entries of 1/w; near the edge it
+    is truncated; the pool equals numpy's 'same' convolution with ones(w)/w."""
+    L, w = 50, 13
+    x = np.zeros(L)
+    x[20] = 1.0
+    P = oracle.pool(x, w)
+    expect = np.zeros(L)
+    expect[14:27] = 1.0 / 13
+    np.testing.assert_allclose(P, expect, rtol=1e-15, atol=0)
+    x = np.zeros(L)
+    x[2] = 1.0
+    P = oracle.pool(x, w)
+    expect = np.zeros(L)
+    expect[0:9] = 1.0 / 13
+    np.testing.assert_allclose(P, expect, rtol=1e-15, atol=0)
+    rng = np.random.default_rng(12)
+    for L, w in ((50, 13), (7, 13), (1, 13), (33, 1), (40, 5)):
+        x = rng.random(L)
+        np.testing.assert_allclose(oracle.pool(x, w), np.convolve(x, np.ones(w) / w, mode="same")[:L]
+                                   if L >= w else
+                                   np.array([x[max(0, j - w // 2): j + w // 2 + 1].sum() / w for j in range(L)]),
+                                   rtol=1e-13)
+    a, b = rng.random(64), rng.random(64)
+    np.testing.assert_allclose(oracle.pool(2 * a - 3 * b, 13), 2 * oracle.pool(a, 13) - 3 * oracle.pool(b, 13),
+                               rtol=1e-12, atol=1e-15)
+    with pytest.raises(ValueError):
+        oracle.pool(a, 12)
+
+
+def test_pool_mass_closed_form():
+    """O13: the divisor is always w, so sum(pool) = (1/w) sum_j cnt(j) I[j] with
+    cnt(j) the number of windows covering j; the mean is preserved exactly when
+    the outer (w-1)/2 entries on each side are zero."""
+    rng = np.random.default_rng(13)
+    L, w = 200, 13
+    h = (w - 1) // 2
+    x = rng.random(L)
+    j = np.arange(L)
+    cnt = np.minimum(j + h, L - 1) - np.maximum(j - h, 0) + 1
+    np.testing.assert_allclose(oracle.pool(x, w).sum(), (cnt * x).sum() / w, rtol=1e-13)
+    x[:h] = 0
+    x[L - h:] = 0
+    np.testing.assert_allclose(oracle.pool(x, w).mean(), x.mean(), rtol=1e-13)
+    c = np.full(L, 0.37)
+    np.testing.assert_allclose(oracle.pool(c, w)[h:L - h], 0.37, rtol=1e-14)
+
+
+def test_chunk_mean_mass_and_short_last_chunk():
+    """O14: sum_i size_i * cs[i] = sum_j P[j]; the short last chunk divides by its
+    own size; matches numpy's reshape-mean when c divides L."""
+    rng = np.random.default_rng(14)
+    P = rng.random(100)
+    cs = oracle.chunk_mean(P, 32)
+    assert cs.size == 4
+    sizes = np.array([32, 32, 32, 4])
+    np.testing.assert_allclose((sizes * cs).sum(), P.sum(), rtol=1e-13)
+    np.testing.assert_allclose(cs[3], P[96:].mean(), rtol=1e-14)
+    np.testing.assert_allclose(oracle.chunk_mean(P[:96], 32), P[:96].reshape(3, 32).mean(1), rtol=1e-14)
+    np.testing.assert_allclose(oracle.chunk_mean(P, 1), P, rtol=0)
+    np.testing.assert_allclose(oracle.chunk_mean(P, 1000), [P.mean()], rtol=1e-14)
+
+
+def test_pool_then_chunk_exact_rationals():
+    """A hand-checkable case in exact rational arithmetic: I = 0..11, w = 3, c = 5."""
+    I = [Fraction(v) for v in range(12)]
+    pooled = []
+    for j in range(12):
+        lo, hi = max(0, j - 1), min(11, j + 1)
+        pooled.append(sum(I[lo:hi + 1]) / 3)
+    cs = [sum(pooled[0:5]) / 5, sum(pooled[5:10]) / 5, sum(pooled[10:12]) / 2]
+    got_p = oracle.pool(np.arange(12.0), 3)
+    got_c = oracle.chunk_mean(got_p, 5)
+    np.testing.assert_allclose(got_p, [float(v) for v in pooled], rtol=1e-15)
+    np.testing.assert_allclose(got_c, [float(v) for v in cs], rtol=1e-15)
+    assert pooled[0] == Fraction(1, 3) and pooled[11] == Fraction(21, 3) and pooled[5] == 5
+
+
+# --------------------------------------------------------------------------
+# top-k, merge, keep count  (Algorithm 1; Sections 3.1, 3.2)
+# --------------------------------------------------------------------------
+
+def brute_force_topk(cs, k):
+    """The k-subset with the largest total; among equal totals the one whose sorted
+    index tuple is lexicographically smallest (lower index wins a tie)."""
+    best, best_sum = None, None
+    for comb in itertools.combinations(range(len(cs)), k):
+        tot = sum(Fraction(float(cs[i])) for i in comb)
+        if best is None or tot > best_sum:          # combinations come in lexicographic order
+            best, best_sum = comb, tot
+    return np.array(best, dtype=np.int64)
+
+
+def test_topk_equals_brute_force_on_tiny_inputs():
+    """O15, O16."""
+    rng = np.random.default_rng(15)
+    for trial in range(40):
+        C = int(rng.integers(1, 11))
+        if trial % 2:
+            cs = rng.integers(0, 4, size=C).astype(np.float64)      # many exact ties
+        else:
+            cs = rng.random(C)
+        for k in range(1, C + 1):
+            np.testing.assert_array_equal(oracle.topk(cs, k), brute_force_topk(cs, k))
+    cs = np.array([1.0, 5.0, 5.0, 2.0, 5.0])
+    np.testing.assert_array_equal(oracle.topk(cs, 1), [1])
+    np.testing.assert_array_equal(oracle.topk(cs, 2), [1, 2])
+    np.testing.assert_array_equal(oracle.topk(cs, 5), [0, 1, 2, 3, 4])
+    with pytest.raises(ValueError):
+        oracle.topk(cs, 0)
+    with pytest.raises(ValueError):
+        oracle.topk(cs, 6)
+
+
+def test_merge_spans_invariants():
+    """O17: spans sorted, disjoint, non-adjacent, total length = kept chunk sizes,
+    boundaries multiples of c or L."""
+    rng = np.random.default_rng(16)
+    for _ in range(50):
+        L = int(rng.integers(1, 400))
+        c = int(rng.integers(1, 40))
+        C = (L + c - 1) // c
+        k = int(rng.integers(1, C + 1))
+        sel = np.sort(rng.choice(C, size=k, replace=False)).astype(np.int64)
+        spans = oracle.merge(sel, c, L)
+        assert (spans[:, 0] < spans[:, 1]).all()
+        assert (spans[1:, 0] > spans[:-1, 1]).all()
+        sizes = np.minimum((sel + 1) * c, L) - sel * c
+        assert (spans[:, 1] - spans[:, 0]).sum() == sizes.sum()
+        assert all(b % c == 0 for b in spans[:, 0])
+        assert all(e % c == 0 or e == L for e in spans[:, 1])
+        covered = np.zeros(L, bool)
+        for b, e in spans:
+            covered[b:e] = True
+        expect = np.zeros(L, bool)
+        for i in sel:
+            expect[i * c:min((i + 1) * c, L)] = True
+        np.testing.assert_array_equal(covered, expect)
+    np.testing.assert_array_equal(oracle.merge(np.array([0, 1, 3, 4, 5, 9]), 4, 38),
+                                  [[0, 8], [12, 24], [36, 38]])
+
+
+def test_keep_count_table():
+    """O22: K = clamp(ceil(C * rho), 1, C) at the five workloads' (C, rho)."""
+    table = [(32, 25, 100, 8), (256, 20, 100, 52), (1024, 15, 100, 154), (2048, 10, 100, 205),
+             (10, 0, 100, 1), (10, 100, 100, 10), (10, 250, 100, 10), (3, 1, 3, 1), (1, 1, 2, 1)]
+    for C, num, den, k in table:
+        assert oracle.keep_count(C, num, den) == k
+
+
+# --------------------------------------------------------------------------
+# projection onto the target tokenisation  (Algorithm 1; Section 3.1)
+# --------------------------------------------------------------------------
+
+def random_offsets(rng, n, max_len):
+    return np.concatenate([[0], np.cumsum(rng.integers(1, max_len + 1, size=n))]).astype(np.int64)
+
+
+def split_same_text(rng, total, max_len):
+    cuts = [0]
+    while cuts[-1] < total:
+        cuts.append(min(total, cuts[-1] + int(rng.integers(1, max_len + 1))))
+    return np.array(cuts, dtype=np.int64)
+
+
+def random_spans(rng, L):
+    n_cut = int(rng.integers(1, 6)) * 2
+    pts = np.sort(rng.choice(L + 1, size=min(n_cut, L + 1) // 2 * 2, replace=False))
+    return pts.reshape(-1, 2).astype(np.int64)
+
+
+def test_projection_identity_tokenisation():
+    """O18: target tokenisation = draft tokenisation gives target spans = draft spans."""
+    rng = np.random.default_rng(17)
+    doff = random_offsets(rng, 120, 8)
+    spans = np.array([[0, 5], [9, 10], [50, 120]], dtype=np.int64)
+    ts, mask, n = oracle.project(doff, doff, spans)
+    np.testing.assert_array_equal(ts, spans)
+    assert n == 5 + 1 + 70 == mask.sum()
+
+
+def test_projection_char_level_and_single_token_targets():
+    """O19: all-length-1 target tokens keep exactly the kept characters; a single
+    target token is kept iff any span exists."""
+    rng = np.random.default_rng(18)
+    doff = random_offsets(rng, 60, 8)
+    total = int(doff[-1])
+    chars = np.arange(total + 1, dtype=np.int64)
+    spans = np.array([[3, 7], [20, 33]], dtype=np.int64)
+    ts, mask, n = oracle.project(doff, chars, spans)
+    kept_chars = (doff[7] - doff[3]) + (doff[33] - doff[20])
+    assert n == kept_chars
+    np.testing.assert_array_equal(ts, [[doff[3], doff[7]], [doff[20], doff[33]]])
+    one = np.array([0, total], dtype=np.int64)
+    ts, mask, n = oracle.project(doff, one, spans)
+    assert n == 1 and ts.tolist() == [[0, 1]]
+    ts, mask, n = oracle.project(doff, one, np.zeros((0, 2), np.int64))
+    assert n == 0 and ts.shape == (0, 2)
+
+
+def test_projection_keep_all_and_monotone():
+    """O20."""
+    rng = np.random.default_rng(19)
+    doff = random_offsets(rng, 90, 8)
+    toff = split_same_text(rng, int(doff[-1]), 7)
+    M = toff.size - 1
+    ts, mask, n = oracle.project(doff, toff, np.array([[0, 90]]))
+    assert ts.tolist() == [[0, M]] and n == M
+    few = np.array([[10, 20]], dtype=np.int64)
+    more = np.array([[10, 20], [40, 45]], dtype=np.int64)
+    _, m1, _ = oracle.project(doff, toff, few)
+    _, m2, _ = oracle.project(doff, toff, more)
+    assert ((m2 >= m1).all()) and m2.sum() > m1.sum()
+
+
+def test_projection_covers_exactly_the_overlapping_tokens():
+    """O21: on tiny random splits, the kept set equals the set of target tokens that
+    share at least one character with a kept draft token (computed through an
+    explicit per-character ownership table, a different route than interval tests),
+    and target spans are sorted, disjoint, non-adjacent with total = n_kept."""
+    rng = np.random.default_rng(20)
+    for _ in range(60):
+        L = int(rng.integers(1, 40))
+        doff = random_offsets(rng, L, 8)
+        total = int(doff[-1])
+        toff = split_same_text(rng, total, 7)
+        M = toff.size - 1
+        spans = random_spans(rng, L)
+        spans = spans[spans[:, 0] < spans[:, 1]]
+        char_kept = np.zeros(total, bool)
+        for a, b in spans:
+            char_kept[doff[a]:doff[b]] = True
+        owner = np.repeat(np.arange(M), np.diff(toff))        # target token of each char
+        expect = np.zeros(M, np.uint8)
+        expect[np.unique(owner[char_kept])] = 1
+        ts, mask, n = oracle.project(doff, toff, spans)
+        np.testing.assert_array_equal(mask, expect)
+        assert n == expect.sum() == (ts[:, 1] - ts[:, 0]).sum()
+        assert (ts[1:, 0] > ts[:-1, 1]).all()
+        rebuilt = np.zeros(M, np.uint8)
+        for a, b in ts:
+            rebuilt[a:b] = 1
+        np.testing.assert_array_equal(rebuilt, expect)
+
+
+def test_projection_boundary_token_is_kept_once():
+    """A target token straddling the gap between two kept spans is kept and bridges
+    the two target ranges into one span."""
+    doff = np.array([0, 2, 4, 6, 8, 10], dtype=np.int64)
+    toff = np.array([0, 3, 7, 10], dtype=np.int64)
+    ts, mask, n = oracle.project(doff, toff, np.array([[0, 2], [3, 5]]))  # chars [0,4) and [6,10)
+    assert mask.tolist() == [1, 1, 1] and ts.tolist() == [[0, 3]] and n == 3
+    ts, mask, n = oracle.project(doff, toff, np.array([[0, 1], [4, 5]]))  # chars [0,2) and [8,10)
+    assert mask.tolist() == [1, 0, 1] and ts.tolist() == [[0, 1], [2, 3]] and n == 2
+    # touching but not overlapping: span ends exactly at a target boundary
+    toff2 = np.array([0, 4, 10], dtype=np.int64)
+    ts, mask, n = oracle.project(doff, toff2, np.array([[0, 2]]))         # chars [0,4)
+    assert mask.tolist() == [1, 0] and n == 1
+
+
+# --------------------------------------------------------------------------
+# generator sanity (no arithmetic of the method involved)
+# --------------------------------------------------------------------------
+
+def test_generator_shapes_and_heavy_hitters_show_up():
+    w = synth.get_config("tiny")
+    inp = synth.make_score_inputs(w)
+    assert inp["q"].shape == (1, 2, 4, 8, 64) and inp["k"][0].shape == (2, 1024, 64)
+    assert inp["hh_pos"][0].size == 11
+    I = oracle.score(inp["q"][0], inp["k"], w.scale, oracle.LAYER_MEAN)
+    top = np.argsort(-I)[:11]
+    assert set(top.tolist()) == set(inp["hh_pos"][0].tolist())
+    doff, toff = synth.gen_char_offsets(w, w.L)
+    assert doff.size == w.L + 1 and doff[-1] == toff[-1] and (np.diff(toff) >= 1).all()
+    assert (np.diff(doff) >= 1).all() and np.diff(doff).max() <= 8 and np.diff(toff).max() <= 7
+    x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 0.0], np.float32)   # RNE ties and exact values
+    assert bf16_bits_to_f32(f32_to_bf16_bits(x)).tolist() == [1.0, 1.0, 1.015625, -2.5, 0.0]
