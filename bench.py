@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the token-importance hot path on one MI355X.
+
+One "step" is one pass of the whole path -- sp_score, sp_select, sp_project --
+over one synthetic prompt already resident in HBM. The default workload is the
+128K-token long-context configuration (16 layers, 32 query / 8 kv heads,
+head_dim 64, 16 lookahead rows): the one the bandwidth target is quoted on.
+
+Prints ONE JSON line with the throughput (prompt tokens scored per second
+through all layers), the HBM roofline of sp_score (algorithmic K bytes read
+once / measured duration, against the 8 TB/s peak) and the CPU oracle timed on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(msg: str) -> None:
+    print(msg, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="long-128k")
+    ap.add_argument("--layer-agg", default="mean", choices=["mean", "max"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-layers", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import synth
+    import paper_2603_02631_amd as sp
+
+    sp.load_library()            # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = "cuda:0"
+    w = synth.get_config(args.workload)
+    if w.batch > 0:
+        print("bench.py: the ragged batch is a parity-test case, not a bench workload", file=sys.stderr)
+        return 2
+    mode = sp.SP_LAYER_MEAN if args.layer_agg == "mean" else sp.SP_LAYER_MAX
+    L = w.L
+
+    # ---- inputs: generated on the host by the seeded generator, uploaded once ----
+    t0 = time.time()
+    lengths = synth.gen_prompt_lengths(w)
+    hh = synth.heavy_hitter_positions(w, lengths)
+    q_bits = synth.gen_q(w, 1)
+    qd = torch.from_numpy(q_bits[0].view(np.int16)).to(dev)
+    k_dev = []
+    k_sample = []                # host copies of the layers the CPU baseline uses
+    for l in range(w.n_layers):
+        k = synth.gen_k_layer(w, l, q_bits, lengths, hh)
+        if l < args.cpu_sample_layers and not args.no_cpu_baseline:
+            k_sample.append(k)
+        k_dev.append(torch.from_numpy(k.view(np.int16)).to(dev))
+    doff, toff = synth.gen_char_offsets(w, L)
+    M = toff.size - 1
+    log(f"[bench] inputs for {w.name} ready in {time.time() - t0:.1f}s "
+        f"(K = {w.k_bytes_per_token * L / 2**30:.2f} GiB, M = {M} target tokens)")
+
+    C = (L + w.chunk - 1) // w.chunk
+    k_keep = sp.sp_keep_count(C, w.keep_num, w.keep_den)
+    desc = sp.ScoreDesc(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_q, w.scale, mode,
+                        w.head_dim, L * w.head_dim)
+    ws1 = torch.empty(sp.sp_score_workspace(desc, L, 1), dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(sp.sp_select_workspace(L, w.chunk), dtype=torch.uint8, device=dev)
+    scores = torch.empty(L, dtype=torch.float32, device=dev)
+    sel = torch.empty(k_keep, dtype=torch.int32, device=dev)
+    spans = torch.empty((k_keep, 2), dtype=torch.int64, device=dev)
+    n_spans = torch.zeros(1, dtype=torch.int32, device=dev)
+    dd = torch.from_numpy(doff).to(dev)
+    td = torch.from_numpy(toff).to(dev)
+    tsp = torch.empty((k_keep, 2), dtype=torch.int64, device=dev)
+    n_t = torch.zeros(1, dtype=torch.int32, device=dev)
+    mask = torch.empty(M, dtype=torch.uint8, device=dev)
+    n_kept = torch.zeros(1, dtype=torch.int64, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        if ev is not None:
+            ev[0].record(stream)
+        sp.sp_score(desc, qd, k_dev, L, scores, ws1, stream=stream)
+        if ev is not None:
+            ev[1].record(stream)
+        sp.sp_select(scores, L, w.pool, w.chunk, k_keep, sel, spans, n_spans, None, ws2, stream=stream)
+        sp.sp_project(dd, L, td, M, spans, n_spans, k_keep, tsp, n_t, mask, n_kept, stream=stream)
+        if ev is not None:
+            ev[2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    score_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    rest_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    k_bytes = float(w.k_bytes_per_token) * L
+    achieved = k_bytes / (score_ms * 1e-3) / 1e9
+    log(f"[bench] {args.steps} steps: {ms_per_step:.3f} ms/step; sp_score {score_ms:.3f} ms "
+        f"({achieved:.0f} GB/s algorithmic), select+project {rest_ms:.3f} ms; kept {int(n_kept.item())} of {M}")
+
+    out = {
+        "metric": "prompt tokens scored/sec (all layers)",
+        "value": L / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n_layers": w.n_layers, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "n_q": w.n_q, "L": L,
+                   "pool": w.pool, "chunk": w.chunk, "keep": f"{w.keep_num}/{w.keep_den}",
+                   "layer_agg": args.layer_agg, "k_layout": "HND"},
+        "stage_ms": {"sp_score": score_ms, "sp_select+sp_project": rest_ms},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "sp_score (all its launches)", "algorithmic_bytes": k_bytes},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        n_s = min(args.cpu_sample_layers, w.n_layers)
+        t0 = time.perf_counter()
+        I = oracle.score(q_bits[0, :n_s], k_sample, w.scale, mode)
+        t_score = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        o_sel, o_spans, _ = oracle.select(I, w.pool, w.chunk, k_keep)
+        oracle.project(doff, toff, o_spans)
+        t_rest = time.perf_counter() - t0
+        t_full = t_score * w.n_layers / n_s + t_rest
+        out["cpu_baseline"] = {
+            "value": L / t_full, "unit": "tokens/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": f"score pass on {n_s} of {w.n_layers} layers at full L={L} ({t_score:.1f}s, scaled "
+                      f"linearly to all layers) + full select/project ({t_rest:.2f}s)",
+        }
+        log(f"[bench] oracle: {t_score:.1f}s for {n_s} layer(s) on {oracle.max_threads()} threads")
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,178 @@
+/*
+ * sp.h -- C ABI of the MI355X (gfx950) token-importance library for
+ * cross-family speculative prefill.
+ *
+ * The library computes, on one GPU, the draft-model token-importance pass of
+ * the paper "Cross-Family Speculative Prefill": attention of the lookahead
+ * queries over the prompt's keys in every draft layer, max/mean aggregation to
+ * one score per prompt token, average pooling, chunk means, top-k chunk
+ * selection, merging into spans, and projection of those spans through
+ * character offsets onto another tokenisation (Algorithm 1; Appendix A.1).
+ *
+ * Conventions shared by every call
+ *  - Pointers named *_dev point to device memory of the current HIP device and
+ *    are owned by the caller; pointers named *_host point to host memory that
+ *    is read during the call only. The library never allocates or frees device
+ *    memory; scratch space comes from the caller's workspace (`ws_dev`), whose
+ *    size the *_workspace functions report. Workspaces must be 256-byte aligned.
+ *  - All device work is enqueued on `hip_stream` (a hipStream_t passed as
+ *    void*; NULL is the default stream). No call synchronises with the host;
+ *    outputs, including the n_*_dev counters, are valid once the stream has
+ *    been synchronised. Two calls sharing a workspace must be ordered by the
+ *    stream.
+ *  - Every call returns an sp_status and never aborts. Host-visible arguments
+ *    are validated before anything is launched; on an error nothing is
+ *    launched and no output is written. sp_last_error() returns a thread-local
+ *    description of the last failure.
+ *  - Contents of device buffers (offsets non-decreasing, finite scores, the
+ *    host and device copies of the batch offsets agreeing) are the caller's
+ *    contract and are not checked.
+ */
+#ifndef SP_H_
+#define SP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SP_OK = 0,
+    SP_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, inconsistent sizes */
+    SP_ERR_UNSUPPORTED = 2,   /* valid request outside the supported set */
+    SP_ERR_WORKSPACE = 3,     /* workspace missing, misaligned or too small */
+    SP_ERR_DEVICE = 4         /* a HIP call failed */
+} sp_status;
+
+/* How per-layer head maxima are combined (Appendix A.1.1; Algorithm 1
+ * "AggregateMaxMean"). SP_LAYER_MAX is the paper's statement: maximum over
+ * layers and heads, then mean over the lookahead rows. SP_LAYER_MEAN takes the
+ * maximum over heads only and averages over lookahead rows and layers. */
+typedef enum { SP_LAYER_MEAN = 0, SP_LAYER_MAX = 1 } sp_layer_agg;
+
+/* Shape of the draft model's attention and of its K cache.
+ * Q is dense bf16 [n_layers][n_q_heads][n_q][head_dim] (per prompt).
+ * K of one layer is bf16 with head_dim contiguous; element (kv head, token j,
+ * e) sits at  kv * k_stride_head + j * k_stride_token + e  (strides in
+ * elements, multiples of 8; layer base pointers 16-byte aligned). Query head h
+ * reads kv head h / (n_q_heads / n_kv_heads).
+ * Supported: head_dim 64 or 128; 1 <= n_q <= 16; n_q_heads a multiple of
+ * n_kv_heads with ratio <= 16; n_layers <= 128; scale finite and > 0. */
+typedef struct {
+    int32_t n_layers;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t n_q;              /* lookahead query rows (the paper's N) */
+    float   scale;            /* logit scale, normally 1/sqrt(head_dim) */
+    int32_t layer_agg;        /* sp_layer_agg */
+    int64_t k_stride_token;
+    int64_t k_stride_head;
+} sp_score_desc;
+
+/* Bytes of workspace sp_score / sp_score_batch need for `total_tokens` prompt
+ * tokens in `n_prompts` prompts (upper bound; 1 prompt for sp_score). */
+sp_status sp_score_workspace(const sp_score_desc *desc, int64_t total_tokens,
+                             int32_t n_prompts, size_t *bytes);
+
+/*
+ * Token importance of one prompt (Appendix A.1.1; Algorithm 1, the
+ * ForwardWithAttn loop's attention and AggregateMaxMean).
+ * For every layer l, query head h and lookahead row n the row
+ *   p[l,h,n,j] = softmax_j( scale * <Q[l,h,n,:], K[l,h/G,j,:]> ),  j in [0,L)
+ * is formed over exactly the L prompt keys (no mask: lookahead rows follow the
+ * prompt), and scores_dev[j] receives
+ *   SP_LAYER_MAX :  (1/n_q)          sum_n max_{l,h} p[l,h,n,j]
+ *   SP_LAYER_MEAN:  (1/(n_q*Lyr))    sum_l sum_n max_h p[l,h,n,j].
+ * q_dev: bf16 Q as described above. k_layers_host: host array of n_layers
+ * device pointers. scores_dev: float[L]. L == 0 is a no-op returning SP_OK.
+ * The softmax is exact (row maximum and sum over all L keys, fp32); the result
+ * is deterministic: the same inputs give bit-identical scores.
+ */
+sp_status sp_score(const sp_score_desc *desc, const void *q_dev,
+                   const void *const *k_layers_host, int64_t L,
+                   float *scores_dev, void *ws_dev, size_t ws_bytes,
+                   void *hip_stream);
+
+/*
+ * The same for a ragged batch of B prompts whose keys are packed back to back
+ * along the token axis: prompt b owns tokens [offsets[b], offsets[b+1]) of each
+ * layer's K and of scores_dev; its queries are q_dev + b * (one prompt's Q).
+ * offsets_host and offsets_dev hold the same B+1 non-decreasing values with
+ * offsets[0] == 0; empty prompts are allowed. Each prompt is softmaxed over
+ * its own keys only. 1 <= B <= 4096.
+ */
+sp_status sp_score_batch(const sp_score_desc *desc, const void *q_dev,
+                         const void *const *k_layers_host,
+                         const int64_t *offsets_host, const int64_t *offsets_dev,
+                         int32_t B, float *scores_dev, void *ws_dev,
+                         size_t ws_bytes, void *hip_stream);
+
+/* Number of chunks to keep for a keep rate keep_num/keep_den (Section 3.1: the
+ * top-K chunks make up a fraction rho of the draft sequence):
+ * clamp(ceil(n_chunks * keep_num / keep_den), 1, n_chunks) in integer
+ * arithmetic. Returns -1 on invalid arguments (n_chunks < 1, keep_den < 1,
+ * keep_num < 0). Host-only. */
+int64_t sp_keep_count(int64_t n_chunks, int64_t keep_num, int64_t keep_den);
+
+/* Bytes of workspace sp_select needs for a prompt of L tokens and this chunk size. */
+sp_status sp_select_workspace(int64_t L, int32_t chunk, size_t *bytes);
+
+/*
+ * Chunk selection (Algorithm 1: AvgPool1D, PartitionIntoChunks, TopKChunks,
+ * MergeAdjacentChunks; Appendix A.1.2; Appendix A.3 for pool 13, chunk 32/128).
+ *  - pooled[j] = (1/pool_w) * sum of scores over the pool_w-wide window centred
+ *    on j, zeros outside [0,L), divisor always pool_w (pool_w odd, >= 1);
+ *  - chunk i covers tokens [i*chunk, min((i+1)*chunk, L)); its score is the
+ *    mean of pooled over its true size; C = ceil(L/chunk);
+ *  - the k chunks with the largest scores are kept, equal scores resolved in
+ *    favour of the lower chunk index (compared as fp32, -0 == +0);
+ *  - sel_chunks_dev[k]: kept chunk indices, ascending;
+ *  - spans_dev[k][2]: maximal runs of adjacent kept chunks as draft-token
+ *    ranges [begin, end), ascending; *n_spans_dev of them are written;
+ *  - chunk_scores_dev: optional float[C] copy of the chunk scores (may be NULL).
+ * Requires 1 <= k <= C, 1 <= chunk, L >= 1. Scores must not be NaN.
+ */
+sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_w,
+                    int32_t chunk, int64_t k, int32_t *sel_chunks_dev,
+                    int64_t *spans_dev, int32_t *n_spans_dev,
+                    float *chunk_scores_dev, void *ws_dev, size_t ws_bytes,
+                    void *hip_stream);
+
+/*
+ * Projection of kept draft-token spans onto the target model's tokenisation
+ * (Algorithm 1: MapDraftChunksToTextSpans and the target tokenisation of the
+ * kept text; Section 3.1), in character-offset form. Both tokenisations are
+ * given as non-decreasing character offsets into the same text:
+ * draft_off_dev[L+1] and target_off_dev[M+1]. Draft span [a,b) covers
+ * characters [draft_off[a], draft_off[b]); target token t is kept iff
+ *      target_off[t] < draft_off[b]  and  target_off[t+1] > draft_off[a]
+ * for some span. spans_dev holds *n_spans_dev ascending, disjoint spans (as
+ * written by sp_select), at most max_spans.
+ *  - tspans_dev[max_spans][2]: kept target tokens as maximal ranges
+ *    [begin, end), ascending, disjoint and non-adjacent (ranges that overlap or
+ *    touch are merged); *n_tspans_dev of them are written;
+ *  - keep_mask_dev: optional uint8[M], 1 for kept target tokens (may be NULL);
+ *  - *n_kept_dev: number of kept target tokens.
+ * Requires L >= 1, M >= 1, 1 <= max_spans <= 2^24.
+ */
+sp_status sp_project(const int64_t *draft_off_dev, int64_t L,
+                     const int64_t *target_off_dev, int64_t M,
+                     const int64_t *spans_dev, const int32_t *n_spans_dev,
+                     int32_t max_spans, int64_t *tspans_dev,
+                     int32_t *n_tspans_dev, uint8_t *keep_mask_dev,
+                     int64_t *n_kept_dev, void *hip_stream);
+
+/* Description of the last error raised on the calling thread ("" if none).
+ * The string lives in thread-local storage owned by the library. */
+const char *sp_last_error(void);
+
+/* Library version string (static storage). */
+const char *sp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SP_H_ */

@@ -1,0 +1,24 @@
+"""MI355X-native token-importance pass for cross-family speculative prefill.
+
+The package is a thin ctypes binding over ``libsp_amd.so`` (hand-written HIP
+kernels for gfx950 behind the C ABI declared in ``include/sp.h``). Importing
+the package does not load the library; the first call does, and it raises if
+the library has not been built.
+"""
+from .binding import (  # noqa: F401
+    SP_LAYER_MAX,
+    SP_LAYER_MEAN,
+    SpError,
+    ScoreDesc,
+    library_path,
+    load_library,
+    sp_keep_count,
+    sp_last_error,
+    sp_project,
+    sp_score,
+    sp_score_batch,
+    sp_score_workspace,
+    sp_select,
+    sp_select_workspace,
+    sp_version,
+)

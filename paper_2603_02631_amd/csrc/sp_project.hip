@@ -1,0 +1,189 @@
+// sp_project: kept draft-token spans -> kept target tokens through character
+// offsets (paper: Algorithm 1 "MapDraftChunksToTextSpans" and the target
+// tokenisation of the kept text; Section 3.1).
+//
+// Target token t overlaps the character interval [cs, ce) of a draft span iff
+//     target_off[t] < ce  and  target_off[t+1] > cs.
+// With non-decreasing offsets the first condition holds on a prefix of t and
+// the second on a suffix, so the overlapping tokens form the range
+//     [ first t with target_off[t+1] > cs ,  first t with target_off[t] >= ce )
+// found by two binary searches per span. Ranges of ascending spans are monotone,
+// so ranges that overlap or touch are merged with an exclusive running maximum
+// of the range ends and a prefix sum of "starts a new range" flags.
+//
+//   sp_project_spans_kernel  one workgroup: searches, scans, merged target
+//                            ranges, their count and the kept-token total.
+//   sp_project_mask_kernel   one thread per target token: binary search of the
+//                            merged ranges, writes the 0/1 keep mask.
+#include "sp_common.hpp"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / 64;
+
+// first index i in [0, n) with a[i] > v   (n if none)
+__device__ __forceinline__ int64_t upper_bound(const int64_t *a, int64_t n, int64_t v)
+{
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (a[mid] > v) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
+// first index i in [0, n) with a[i] >= v   (n if none)
+__device__ __forceinline__ int64_t lower_bound(const int64_t *a, int64_t n, int64_t v)
+{
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (a[mid] >= v) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
+struct ScanSmem {
+    int64_t wave_max[kWavesPerBlock];
+    int wave_sum[kWavesPerBlock];
+};
+
+// Inclusive block scans: running maximum of an int64 and running sum of an int.
+__device__ __forceinline__ void block_scan(int64_t &mx, int &sum, ScanSmem &sm, int64_t &tot_max, int &tot_sum)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int64_t m2 = __shfl_up(mx, off);
+        const int s2 = __shfl_up(sum, off);
+        if (lane >= off) { mx = mx > m2 ? mx : m2; sum += s2; }
+    }
+    __syncthreads();
+    if (lane == 63) { sm.wave_max[wave] = mx; sm.wave_sum[wave] = sum; }
+    __syncthreads();
+    int64_t bm = -1; int bs = 0;
+    tot_max = -1; tot_sum = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+        const int64_t wm = sm.wave_max[w];
+        const int ws = sm.wave_sum[w];
+        if (w < wave) { bm = bm > wm ? bm : wm; bs += ws; }
+        tot_max = tot_max > wm ? tot_max : wm;
+        tot_sum += ws;
+    }
+    mx = mx > bm ? mx : bm;
+    sum += bs;
+}
+
+__global__ __launch_bounds__(kThreads) void sp_project_spans_kernel(
+    const int64_t *__restrict__ draft_off, int64_t L, const int64_t *__restrict__ target_off, int64_t M,
+    const int64_t *__restrict__ spans, const int32_t *__restrict__ n_spans_p, int max_spans, int64_t *tspans,
+    int32_t *n_tspans, int64_t *n_kept)
+{
+    __shared__ ScanSmem sm;
+    __shared__ int64_t red[kWavesPerBlock];
+    const int tid = threadIdx.x;
+    int n_spans = *n_spans_p;
+    if (n_spans > max_spans) n_spans = max_spans;
+    if (n_spans < 0) n_spans = 0;
+
+    int64_t carry_hi = -1;      // largest range end seen in earlier segments (-1: none)
+    int carry_n = 0;            // merged ranges opened in earlier segments
+    for (int base = 0; base < n_spans; base += kThreads) {
+        const int s = base + tid;
+        int64_t lo = 0, hi = 0;
+        bool nonempty = false;
+        if (s < n_spans) {
+            int64_t a = spans[2 * s], b = spans[2 * s + 1];
+            a = a < 0 ? 0 : (a > L ? L : a);
+            b = b < 0 ? 0 : (b > L ? L : b);
+            const int64_t cs = draft_off[a], ce = draft_off[b];
+            lo = upper_bound(target_off + 1, M, cs);      // first t with target_off[t+1] > cs
+            hi = lower_bound(target_off, M, ce);          // first t with target_off[t] >= ce  (M if none)
+            nonempty = lo < hi;
+        }
+        // exclusive running maximum of the ends of earlier non-empty ranges
+        int64_t incl_max = nonempty ? hi : -1;
+        int dummy = 0;
+        int64_t tot_max; int tot_dummy;
+        block_scan(incl_max, dummy, sm, tot_max, tot_dummy);
+        int64_t prev_hi = __shfl_up(incl_max, 1);
+        if ((tid & 63) == 0) {
+            prev_hi = -1;
+            for (int w = 0; w < (tid >> 6); ++w) prev_hi = prev_hi > sm.wave_max[w] ? prev_hi : sm.wave_max[w];
+        }
+        prev_hi = prev_hi > carry_hi ? prev_hi : carry_hi;
+        const int start = nonempty && (prev_hi < 0 || lo > prev_hi);
+        int id = start;
+        int64_t dm = -1; int64_t tm; int tot_start;
+        block_scan(dm, id, sm, tm, tot_start);
+        if (start) {
+            const int r = carry_n + id - 1;
+            tspans[2 * r] = lo;
+            if (r > 0) tspans[2 * (r - 1) + 1] = prev_hi;   // closes the previous merged range
+        }
+        carry_hi = carry_hi > tot_max ? carry_hi : tot_max;
+        carry_n += tot_start;
+    }
+    if (tid == 0) {
+        if (carry_n > 0) tspans[2 * (carry_n - 1) + 1] = carry_hi;
+        *n_tspans = carry_n;
+    }
+    __syncthreads();
+    // kept-token total = sum of merged range lengths
+    int64_t part = 0;
+    for (int r = tid; r < carry_n; r += kThreads) part += tspans[2 * r + 1] - tspans[2 * r];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off);
+    if ((tid & 63) == 0) red[tid >> 6] = part;
+    __syncthreads();
+    if (tid == 0) {
+        int64_t t = 0;
+        for (int w = 0; w < kWavesPerBlock; ++w) t += red[w];
+        *n_kept = t;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void sp_project_mask_kernel(const int64_t *__restrict__ tspans,
+                                                                   const int32_t *__restrict__ n_tspans, int64_t M,
+                                                                   uint8_t *__restrict__ mask)
+{
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= M) return;
+    const int n = *n_tspans;
+    // last merged range whose begin is <= t
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = lo + ((hi - lo) >> 1);
+        if (tspans[2 * mid] <= t) lo = mid + 1; else hi = mid;
+    }
+    uint8_t keep = 0;
+    if (lo > 0 && t < tspans[2 * (lo - 1) + 1]) keep = 1;
+    mask[t] = keep;
+}
+
+}  // namespace
+
+extern "C" sp_status sp_project(const int64_t *draft_off_dev, int64_t L, const int64_t *target_off_dev, int64_t M,
+                                const int64_t *spans_dev, const int32_t *n_spans_dev, int32_t max_spans,
+                                int64_t *tspans_dev, int32_t *n_tspans_dev, uint8_t *keep_mask_dev,
+                                int64_t *n_kept_dev, void *hip_stream)
+{
+    if (!draft_off_dev || !target_off_dev || !spans_dev || !n_spans_dev || !tspans_dev || !n_tspans_dev || !n_kept_dev)
+        return sp::fail(SP_ERR_INVALID_ARG, "only keep_mask_dev may be null");
+    if (L < 1 || M < 1) return sp::fail(SP_ERR_INVALID_ARG, "L = %lld and M = %lld must be >= 1", (long long)L, (long long)M);
+    if (max_spans < 1 || max_spans > (1 << 24))
+        return sp::fail(SP_ERR_INVALID_ARG, "max_spans = %d outside 1..2^24", max_spans);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(sp_project_spans_kernel, dim3(1), dim3(kThreads), 0, st, draft_off_dev, L, target_off_dev, M,
+                       spans_dev, n_spans_dev, (int)max_spans, tspans_dev, n_tspans_dev, n_kept_dev);
+    SP_HIP_CHECK(hipGetLastError());
+    if (keep_mask_dev) {
+        const unsigned grid = (unsigned)((M + kThreads - 1) / kThreads);
+        hipLaunchKernelGGL(sp_project_mask_kernel, dim3(grid), dim3(kThreads), 0, st, (const int64_t *)tspans_dev,
+                           (const int32_t *)n_tspans_dev, M, keep_mask_dev);
+        SP_HIP_CHECK(hipGetLastError());
+    }
+    return SP_OK;
+}

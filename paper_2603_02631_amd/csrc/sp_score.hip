@@ -1,0 +1,593 @@
+// sp_score / sp_score_batch: token importance from the lookahead queries'
+// attention over the prompt keys (paper: Appendix A.1.1; Algorithm 1,
+// "AggregateMaxMean").
+//
+// Three kernels, all built around the bf16 32x32x16 MFMA of gfx950:
+//   stats   one workgroup per (key tile, layer, kv head): logits of the kv
+//           head's whole query group against 256 keys, per-row running
+//           (max, sum of exp) kept per lane, one partial per (row, tile);
+//   merge   log-sum-exp combination of the partials of each row in a fixed
+//           order (deterministic), giving the row's normaliser;
+//   prob    one workgroup per key tile, looping over layers and kv heads:
+//           logits again with the normaliser folded into the MFMA's C operand,
+//           maximum over heads taken on logits (exp is monotone, so
+//           max_h softmax_h = exp(max_h(logit_h - lse_h))), one exp per
+//           (lookahead row, key), sum over lookahead rows and layers in
+//           registers, a single store per key.
+//
+// Register/lane layout facts used throughout (v_mfma_f32_32x32x16_bf16):
+//   A operand: lane i holds row i%32, eight consecutive k-values of half i/32
+//   B operand: lane i holds column i%32, the same eight k-values
+//   D: lane i, register r holds row 8*(r/4) + 4*(i/32) + r%4, column i%32.
+// Since A and B fragments are laid out alike, one fragment of K serves as A
+// (rows = keys) in the stats pass and as B (columns = keys) in the prob pass.
+#include "sp_common.hpp"
+
+#include <cmath>
+#include <cstring>
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kMaxLayers = 128;
+constexpr int kMaxPrompts = 4096;
+constexpr int kMaxRows = 256;          // padded query rows per kv head
+constexpr size_t kLdsBudget = 64 * 1024;
+
+struct LayerPtrs { const uint16_t *p[kMaxLayers]; };
+
+struct TileInfo {
+    int64_t j0;          // first key of the tile (index into the packed token axis)
+    int64_t end;         // one past the last key of the tile's prompt
+    int32_t prompt;
+    int32_t first_tile;  // index of the prompt's first tile
+};
+
+struct ScoreArgs {
+    const uint16_t *q;        // [B][Lyr][H][n_q][d]
+    int64_t k_stride_token, k_stride_head;
+    const TileInfo *tiles;    // null: single prompt, tile t starts at t * tile_keys
+    const int32_t *prompt_tiles;  // [B+1] first tile of each prompt (batch only)
+    int64_t L;                // single prompt length
+    float2 *part;             // [n_phases][n_tiles][rows_pad]
+    float *lse_neg;           // [B][n_phases][rows_pad]  (-lse in raw-logit units, permuted)
+    float *scores;
+    int32_t n_tiles, n_prompts;
+    int32_t n_layers, n_q_heads, n_kv_heads, group, n_q;
+    int32_t n_nblk, n_gblk, rows_pad;   // blocks of 8 lookahead rows / 4 group heads
+    int32_t layer_agg;
+    float c;                  // scale * log2(e)
+    float inv_c;
+    float out_scale;          // 1/n_q or 1/(n_q * Lyr)
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+__device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
+
+// LDS tiles hold rows of D bf16 as D/8 chunks of 16 bytes; the chunk index is
+// XOR-swizzled by the row so that 16 lanes reading one chunk column of 16
+// consecutive rows hit 16 different bank groups.
+template <int D>
+__device__ __forceinline__ int lds_slot(int row, int chunk)
+{
+    constexpr int CH = D / 8;
+    const int s = (CH == 8) ? ((row >> 1) & 7) : (row & 15);
+    return row * CH + (chunk ^ s);
+}
+
+__device__ __forceinline__ TileInfo get_tile(const ScoreArgs &a, int tile, int tile_keys)
+{
+    if (a.tiles) return a.tiles[tile];
+    TileInfo t;
+    t.j0 = (int64_t)tile * tile_keys;
+    t.end = a.L;
+    t.prompt = 0;
+    t.first_tile = 0;
+    return t;
+}
+
+// Padded query-row order of one kv head's group: row = blk*32 + rho with
+// blk = gblk * n_nblk + nblk, rho = 8*gl + nl  ->  group head g = 4*gblk + gl,
+// lookahead row n = 8*nblk + nl. In the D layout of the prob pass this puts the
+// four group heads of a block in registers r/4 of one lane.
+__device__ __forceinline__ bool row_to_gn(const ScoreArgs &a, int row, int &g, int &n)
+{
+    const int blk = row >> 5, rho = row & 31;
+    const int gblk = blk / a.n_nblk, nblk = blk - gblk * a.n_nblk;
+    g = 4 * gblk + (rho >> 3);
+    n = 8 * nblk + (rho & 7);
+    return g < a.group && n < a.n_q;
+}
+
+template <int D>
+__device__ __forceinline__ void stage_q(u32x4 *qs, const ScoreArgs &a, int prompt, int layer, int kv, int tid)
+{
+    constexpr int CH = D / 8;
+    const uint16_t *qb = a.q + (((int64_t)prompt * a.n_layers + layer) * a.n_q_heads + (int64_t)kv * a.group) *
+                                   a.n_q * D;
+    for (int i = tid; i < a.rows_pad * CH; i += kThreads) {
+        const int row = i / CH, ch = i - row * CH;
+        int g, n;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (row_to_gn(a, row, g, n))
+            v = *reinterpret_cast<const u32x4 *>(qb + ((int64_t)g * a.n_q + n) * D + ch * 8);
+        qs[lds_slot<D>(row, ch)] = v;
+    }
+}
+
+template <int D, int NS>
+__device__ __forceinline__ void stage_k(u32x4 *ks, const uint16_t *kb, int64_t stride_token, int64_t j0,
+                                        int64_t end, int tid)
+{
+    constexpr int CH = D / 8;
+    constexpr int TILE = kWaves * NS * 32;
+    constexpr int N = TILE * CH / kThreads;
+    u32x4 v[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int idx = tid + i * kThreads;
+        const int row = idx / CH, ch = idx % CH;
+        const int64_t j = j0 + row;
+        if (j < end)
+            v[i] = *reinterpret_cast<const u32x4 *>(kb + j * stride_token + ch * 8);
+        else
+            v[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int idx = tid + i * kThreads;
+        ks[lds_slot<D>(idx / CH, idx % CH)] = v[i];
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void load_frag(const u32x4 *tile, int row, int hf, bf16x8 (&f)[D / 16])
+{
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t) f[t] = __builtin_bit_cast(bf16x8, tile[lds_slot<D>(row, 2 * t + hf)]);
+}
+
+// (m, l) <- (m, l) (+) (m2, l2) for running softmax statistics in raw-logit units.
+__device__ __forceinline__ void lse_merge(float &m, float &l, float m2, float l2, float c)
+{
+    const float mm = fmaxf(m, m2);
+    if (mm == neg_inf()) { l = 0.f; return; }
+    l = l * fast_exp2((m - mm) * c) + l2 * fast_exp2((m2 - mm) * c);
+    m = mm;
+}
+
+// ---------------------------------------------------------------------------
+// stats: partial (max, sum exp) of every query row of one (layer, kv head)
+// over one key tile.
+// ---------------------------------------------------------------------------
+template <int D, int NS>
+__global__ __launch_bounds__(kThreads, 2) void sp_stats_kernel(ScoreArgs a, LayerPtrs kp)
+{
+    constexpr int KS = D / 16;
+    constexpr int TILE = kWaves * NS * 32;
+    extern __shared__ u32x4 lds[];
+    u32x4 *ks = lds;                         // TILE rows
+    u32x4 *qs = lds + TILE * (D / 8);        // rows_pad rows
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hf = lane >> 5, col = lane & 31;
+    const int tile = blockIdx.x, phase = blockIdx.y;
+    const int layer = phase / a.n_kv_heads, kv = phase - layer * a.n_kv_heads;
+    const TileInfo ti = get_tile(a, tile, TILE);
+
+    stage_q<D>(qs, a, ti.prompt, layer, kv, tid);
+    stage_k<D, NS>(ks, kp.p[layer] + (int64_t)kv * a.k_stride_head, a.k_stride_token, ti.j0, ti.end, tid);
+    __syncthreads();
+
+    bf16x8 kf[NS][KS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) load_frag<D>(ks, (wave * NS + s) * 32 + col, hf, kf[s]);
+    __syncthreads();                         // ks is reused for the per-wave statistics below
+    float2 *wstats = reinterpret_cast<float2 *>(ks);   // [kWaves][rows_pad]
+
+    const float c = a.c;
+    const int n_blk = a.rows_pad >> 5;
+    for (int blk = 0; blk < n_blk; ++blk) {
+        bf16x8 qf[KS];
+        load_frag<D>(qs, blk * 32 + col, hf, qf);
+        float m = neg_inf(), l = 0.f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            f32x16 acc = {0.f};
+#pragma unroll
+            for (int t = 0; t < KS; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s][t], qf[t], acc, 0, 0, 0);
+            // acc[r]: key (wave*NS+s)*32 + 8*(r/4) + 4*hf + r%4 of the tile, query row blk*32 + col
+            const int64_t left = ti.end - (ti.j0 + (wave * NS + s) * 32);
+            if (left >= 32) {
+                float tm = acc[0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) tm = fmaxf(tm, acc[r]);
+                const float mn = fmaxf(m, tm);
+                l *= fast_exp2((m - mn) * c);
+                m = mn;
+                const float mc = mn * c;
+                float sum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c, -mc));
+                l += sum;
+            } else if (left > 0) {
+                float tm = neg_inf();
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
+                    if (key < left) tm = fmaxf(tm, acc[r]);
+                }
+                if (tm > neg_inf()) {
+                    const float mn = fmaxf(m, tm);
+                    l *= fast_exp2((m - mn) * c);
+                    m = mn;
+                    const float mc = mn * c;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
+                        if (key < left) l += fast_exp2(fmaf(acc[r], c, -mc));
+                    }
+                }
+            }
+        }
+        const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
+        lse_merge(m, l, m2, l2, c);
+        if (hf == 0) wstats[wave * a.rows_pad + blk * 32 + col] = make_float2(m, l);
+    }
+    __syncthreads();
+    for (int row = tid; row < a.rows_pad; row += kThreads) {
+        float2 s0 = wstats[row];
+        float m = s0.x, l = s0.y;
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) {
+            const float2 sw = wstats[w * a.rows_pad + row];
+            lse_merge(m, l, sw.x, sw.y, c);
+        }
+        a.part[((int64_t)phase * a.n_tiles + tile) * a.rows_pad + row] = make_float2(m, l);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// merge: one workgroup per (32-row block, phase, prompt). 8 slices of the
+// prompt's tiles are reduced by 8 thread groups, then combined in slice order.
+// Writes -lse in raw-logit units, i.e. -(m + log2(l)/c), at the position the
+// prob pass reads it from: within a block, row rho = 8*q + 4*hf + e goes to
+// hf*16 + 4*q + e. Padding rows get -inf so they never win a maximum.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void sp_merge_kernel(ScoreArgs a)
+{
+    __shared__ float2 red[8][32];
+    const int tid = threadIdx.x, rho = tid & 31, slice = tid >> 5;
+    const int blk = blockIdx.x, phase = blockIdx.y, prompt = blockIdx.z;
+    const int n_phases = a.n_layers * a.n_kv_heads;
+    int t0 = 0, t1 = a.n_tiles;
+    if (a.prompt_tiles) { t0 = a.prompt_tiles[prompt]; t1 = a.prompt_tiles[prompt + 1]; }
+    const int row = blk * 32 + rho;
+    float m = neg_inf(), l = 0.f;
+    for (int t = t0 + slice; t < t1; t += 8) {
+        const float2 p = a.part[((int64_t)phase * a.n_tiles + t) * a.rows_pad + row];
+        lse_merge(m, l, p.x, p.y, a.c);
+    }
+    red[slice][rho] = make_float2(m, l);
+    __syncthreads();
+    if (slice == 0) {
+#pragma unroll
+        for (int s = 1; s < 8; ++s) lse_merge(m, l, red[s][rho].x, red[s][rho].y, a.c);
+        int g, n;
+        const bool valid = row_to_gn(a, row, g, n) && l > 0.f;
+        const float v = valid ? -(m + fast_log2(l) * a.inv_c) : neg_inf();
+        const int pos = ((rho >> 2) & 1) * 16 + 4 * (rho >> 3) + (rho & 3);
+        a.lse_neg[((int64_t)prompt * n_phases + phase) * a.rows_pad + blk * 32 + pos] = v;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// prob: per key, sum over lookahead rows (and layers) of the head-maximum of
+// the attention probability.
+// ---------------------------------------------------------------------------
+template <int D, int NS, int NB>
+__global__ __launch_bounds__(kThreads) void sp_prob_kernel(ScoreArgs a, LayerPtrs kp)
+{
+    constexpr int KS = D / 16;
+    constexpr int TILE = kWaves * NS * 32;
+    extern __shared__ u32x4 lds[];
+    u32x4 *ks = lds;
+    u32x4 *qs = lds + TILE * (D / 8);
+    float *ci = reinterpret_cast<float *>(qs + kMaxRows * 0 + a.rows_pad * (D / 8));   // rows_pad floats
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hf = lane >> 5, col = lane & 31;
+    const int tile = blockIdx.x;
+    const TileInfo ti = get_tile(a, tile, TILE);
+    const int n_phases = a.n_layers * a.n_kv_heads;
+    const float c = a.c;
+
+    float mx[NS][NB][4];
+    float total[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        total[s] = 0.f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mx[s][b][e] = neg_inf();
+    }
+
+    for (int layer = 0; layer < a.n_layers; ++layer) {
+        for (int kv = 0; kv < a.n_kv_heads; ++kv) {
+            const int phase = layer * a.n_kv_heads + kv;
+            __syncthreads();
+            stage_q<D>(qs, a, ti.prompt, layer, kv, tid);
+            stage_k<D, NS>(ks, kp.p[layer] + (int64_t)kv * a.k_stride_head, a.k_stride_token, ti.j0, ti.end, tid);
+            for (int i = tid; i < a.rows_pad; i += kThreads)
+                ci[i] = a.lse_neg[((int64_t)ti.prompt * n_phases + phase) * a.rows_pad + i];
+            __syncthreads();
+
+            bf16x8 kf[NS][KS];
+#pragma unroll
+            for (int s = 0; s < NS; ++s) load_frag<D>(ks, (wave * NS + s) * 32 + col, hf, kf[s]);
+
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                for (int gb = 0; gb < a.n_gblk; ++gb) {
+                    const int blk = gb * NB + nb;
+                    bf16x8 qf[KS];
+                    load_frag<D>(qs, blk * 32 + col, hf, qf);
+                    f32x16 cinit;
+                    const float4 *cp = reinterpret_cast<const float4 *>(ci + blk * 32 + hf * 16);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float4 x = cp[v];
+                        cinit[4 * v + 0] = x.x; cinit[4 * v + 1] = x.y;
+                        cinit[4 * v + 2] = x.z; cinit[4 * v + 3] = x.w;
+                    }
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) {
+                        f32x16 acc = cinit;
+#pragma unroll
+                        for (int t = 0; t < KS; ++t)
+                            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t], kf[s][t], acc, 0, 0, 0);
+                        // acc[r]: group head r/4, lookahead row 8*nb + 4*hf + r%4, key (wave*NS+s)*32 + col
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float v = fmaxf(fmaxf(acc[e], acc[4 + e]), fmaxf(acc[8 + e], acc[12 + e]));
+                            mx[s][nb][e] = fmaxf(mx[s][nb][e], v);
+                        }
+                    }
+                }
+            }
+        }
+        if (a.layer_agg == SP_LAYER_MEAN || layer == a.n_layers - 1) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                float sum = 0.f;
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        sum += fast_exp2(mx[s][b][e] * c);
+                        mx[s][b][e] = neg_inf();
+                    }
+                total[s] += sum;
+            }
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const float both = total[s] + __shfl_xor(total[s], 32);
+        const int64_t j = ti.j0 + (wave * NS + s) * 32 + col;
+        if (hf == 0 && j < ti.end) a.scores[j] = both * a.out_scale;
+    }
+}
+
+// Tile table of a ragged batch: tiles never straddle prompts.
+__global__ void sp_tiles_kernel(const int64_t *offsets, int n_prompts, int tile_keys, TileInfo *tiles,
+                                int32_t *prompt_tiles, int n_tiles_cap)
+{
+    for (int b = threadIdx.x; b <= n_prompts; b += blockDim.x) {
+        int64_t first = 0;
+        for (int p = 0; p < b; ++p) first += (offsets[p + 1] - offsets[p] + tile_keys - 1) / tile_keys;
+        prompt_tiles[b] = (int32_t)first;
+        if (b == n_prompts) continue;
+        const int64_t beg = offsets[b], end = offsets[b + 1];
+        int64_t t = first;
+        for (int64_t j = beg; j < end && t < n_tiles_cap; j += tile_keys, ++t) {
+            TileInfo ti;
+            ti.j0 = j; ti.end = end; ti.prompt = b; ti.first_tile = (int32_t)first;
+            tiles[t] = ti;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+struct Plan {
+    int D, NS, NB, n_gblk, rows_pad, tile_keys, n_phases;
+    size_t lds_bytes;
+};
+
+sp_status make_plan(const sp_score_desc *d, Plan &p)
+{
+    if (!d) return sp::fail(SP_ERR_INVALID_ARG, "desc is null");
+    if (d->n_layers < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_q < 1 || d->head_dim < 1)
+        return sp::fail(SP_ERR_INVALID_ARG, "desc: sizes must be positive");
+    if (d->n_q_heads % d->n_kv_heads != 0)
+        return sp::fail(SP_ERR_INVALID_ARG, "desc: n_q_heads (%d) is not a multiple of n_kv_heads (%d)",
+                        d->n_q_heads, d->n_kv_heads);
+    if (!(d->scale > 0.f) || !std::isfinite(d->scale))
+        return sp::fail(SP_ERR_INVALID_ARG, "desc: scale must be finite and > 0");
+    if (d->layer_agg != SP_LAYER_MEAN && d->layer_agg != SP_LAYER_MAX)
+        return sp::fail(SP_ERR_INVALID_ARG, "desc: layer_agg must be SP_LAYER_MEAN or SP_LAYER_MAX");
+    if (d->head_dim != 64 && d->head_dim != 128)
+        return sp::fail(SP_ERR_UNSUPPORTED, "desc: head_dim %d (supported: 64, 128)", d->head_dim);
+    if (d->n_q > 16) return sp::fail(SP_ERR_UNSUPPORTED, "desc: n_q %d (supported: 1..16)", d->n_q);
+    if (d->n_layers > kMaxLayers)
+        return sp::fail(SP_ERR_UNSUPPORTED, "desc: n_layers %d (supported: <= %d)", d->n_layers, kMaxLayers);
+    const int G = d->n_q_heads / d->n_kv_heads;
+    if (G > 16) return sp::fail(SP_ERR_UNSUPPORTED, "desc: %d query heads per kv head (supported: <= 16)", G);
+    if (d->k_stride_token < d->head_dim || d->k_stride_head < 0 || d->k_stride_token % 8 != 0 ||
+        d->k_stride_head % 8 != 0)
+        return sp::fail(SP_ERR_INVALID_ARG, "desc: K strides must be multiples of 8 elements, token stride >= head_dim");
+    p.D = d->head_dim;
+    p.NS = (p.D == 64) ? 2 : 1;
+    p.NB = (d->n_q + 7) / 8;
+    p.n_gblk = (G + 3) / 4;
+    p.rows_pad = p.NB * p.n_gblk * 32;
+    p.tile_keys = kWaves * p.NS * 32;
+    p.n_phases = d->n_layers * d->n_kv_heads;
+    p.lds_bytes = (size_t)p.tile_keys * p.D * 2 + (size_t)p.rows_pad * p.D * 2 + (size_t)p.rows_pad * 4;
+    if (p.lds_bytes > kLdsBudget)
+        return sp::fail(SP_ERR_UNSUPPORTED, "desc: query group of %d heads x %d rows at head_dim %d exceeds on-chip staging",
+                        G, d->n_q, p.D);
+    return SP_OK;
+}
+
+struct WsLayout {
+    size_t part, lse, tiles, prompt_tiles, total;
+};
+
+WsLayout ws_layout(const Plan &p, int64_t n_tiles, int n_prompts)
+{
+    WsLayout w;
+    size_t off = 0;
+    w.part = off;  off = sp::align_up(off + sizeof(float2) * (size_t)p.n_phases * (size_t)n_tiles * p.rows_pad, 256);
+    w.lse = off;   off = sp::align_up(off + sizeof(float) * (size_t)n_prompts * p.n_phases * p.rows_pad, 256);
+    w.tiles = off; off = sp::align_up(off + sizeof(TileInfo) * (size_t)n_tiles, 256);
+    w.prompt_tiles = off; off = sp::align_up(off + sizeof(int32_t) * (size_t)(n_prompts + 1), 256);
+    w.total = off;
+    return w;
+}
+
+template <int D, int NS>
+sp_status launch_all(const Plan &p, const ScoreArgs &a, const LayerPtrs &kp, hipStream_t st)
+{
+    const dim3 block(kThreads);
+    hipLaunchKernelGGL((sp_stats_kernel<D, NS>), dim3(a.n_tiles, p.n_phases), block, p.lds_bytes, st, a, kp);
+    SP_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(sp_merge_kernel, dim3(p.rows_pad / 32, p.n_phases, a.n_prompts), block, 0, st, a);
+    SP_HIP_CHECK(hipGetLastError());
+    if (p.NB == 1)
+        hipLaunchKernelGGL((sp_prob_kernel<D, NS, 1>), dim3(a.n_tiles), block, p.lds_bytes, st, a, kp);
+    else
+        hipLaunchKernelGGL((sp_prob_kernel<D, NS, 2>), dim3(a.n_tiles), block, p.lds_bytes, st, a, kp);
+    SP_HIP_CHECK(hipGetLastError());
+    return SP_OK;
+}
+
+sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
+                     const int64_t *offsets_host, const int64_t *offsets_dev, int32_t B, int64_t L_single,
+                     float *scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
+{
+    Plan p;
+    sp_status rc = make_plan(desc, p);
+    if (rc != SP_OK) return rc;
+    if (!q_dev || !k_layers_host || !scores_dev)
+        return sp::fail(SP_ERR_INVALID_ARG, "q_dev, k_layers_host and scores_dev must not be null");
+    LayerPtrs kp;
+    std::memset(&kp, 0, sizeof kp);
+    for (int l = 0; l < desc->n_layers; ++l) {
+        if (!k_layers_host[l]) return sp::fail(SP_ERR_INVALID_ARG, "k_layers_host[%d] is null", l);
+        if ((uintptr_t)k_layers_host[l] % 16 != 0)
+            return sp::fail(SP_ERR_INVALID_ARG, "k_layers_host[%d] is not 16-byte aligned", l);
+        kp.p[l] = static_cast<const uint16_t *>(k_layers_host[l]);
+    }
+    if ((uintptr_t)q_dev % 16 != 0) return sp::fail(SP_ERR_INVALID_ARG, "q_dev is not 16-byte aligned");
+
+    int64_t total = 0, n_tiles = 0;
+    const bool batch = offsets_host != nullptr;
+    if (batch) {
+        if (!offsets_dev) return sp::fail(SP_ERR_INVALID_ARG, "offsets_dev is null");
+        if (B < 1 || B > kMaxPrompts) return sp::fail(SP_ERR_INVALID_ARG, "B = %d (supported: 1..%d)", B, kMaxPrompts);
+        if (offsets_host[0] != 0) return sp::fail(SP_ERR_INVALID_ARG, "offsets_host[0] must be 0");
+        for (int b = 0; b < B; ++b) {
+            const int64_t len = offsets_host[b + 1] - offsets_host[b];
+            if (len < 0) return sp::fail(SP_ERR_INVALID_ARG, "offsets_host decreases at prompt %d", b);
+            n_tiles += (len + p.tile_keys - 1) / p.tile_keys;
+        }
+        total = offsets_host[B];
+    } else {
+        if (L_single < 0) return sp::fail(SP_ERR_INVALID_ARG, "L = %lld is negative", (long long)L_single);
+        total = L_single;
+        n_tiles = (total + p.tile_keys - 1) / p.tile_keys;
+        B = 1;
+    }
+    if (total == 0) return SP_OK;
+    if (n_tiles > 0x7fffffff / 2) return sp::fail(SP_ERR_UNSUPPORTED, "too many key tiles (%lld)", (long long)n_tiles);
+
+    const WsLayout w = ws_layout(p, n_tiles, B);
+    if (!ws_dev) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is null (%zu bytes needed)", w.total);
+    if ((uintptr_t)ws_dev % 256 != 0) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is not 256-byte aligned");
+    if (ws_bytes < w.total) return sp::fail(SP_ERR_WORKSPACE, "workspace too small: %zu < %zu", ws_bytes, w.total);
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(ws_dev);
+    ScoreArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.q = static_cast<const uint16_t *>(q_dev);
+    a.k_stride_token = desc->k_stride_token;
+    a.k_stride_head = desc->k_stride_head;
+    a.L = total;
+    a.part = reinterpret_cast<float2 *>(ws + w.part);
+    a.lse_neg = reinterpret_cast<float *>(ws + w.lse);
+    a.scores = scores_dev;
+    a.n_tiles = (int32_t)n_tiles;
+    a.n_prompts = B;
+    a.n_layers = desc->n_layers;
+    a.n_q_heads = desc->n_q_heads;
+    a.n_kv_heads = desc->n_kv_heads;
+    a.group = desc->n_q_heads / desc->n_kv_heads;
+    a.n_q = desc->n_q;
+    a.n_nblk = p.NB;
+    a.n_gblk = p.n_gblk;
+    a.rows_pad = p.rows_pad;
+    a.layer_agg = desc->layer_agg;
+    a.c = desc->scale * 1.44269504088896340736f;
+    a.inv_c = 1.0f / a.c;
+    a.out_scale = (desc->layer_agg == SP_LAYER_MAX) ? 1.0f / (float)desc->n_q
+                                                   : 1.0f / ((float)desc->n_q * (float)desc->n_layers);
+    if (batch) {
+        TileInfo *tiles = reinterpret_cast<TileInfo *>(ws + w.tiles);
+        int32_t *pt = reinterpret_cast<int32_t *>(ws + w.prompt_tiles);
+        hipLaunchKernelGGL(sp_tiles_kernel, dim3(1), dim3(256), 0, st, offsets_dev, B, p.tile_keys, tiles, pt,
+                           (int)n_tiles);
+        SP_HIP_CHECK(hipGetLastError());
+        a.tiles = tiles;
+        a.prompt_tiles = pt;
+    }
+    if (p.D == 64) return launch_all<64, 2>(p, a, kp, st);
+    return launch_all<128, 1>(p, a, kp, st);
+}
+
+}  // namespace
+
+extern "C" sp_status sp_score_workspace(const sp_score_desc *desc, int64_t total_tokens, int32_t n_prompts,
+                                        size_t *bytes)
+{
+    Plan p;
+    sp_status rc = make_plan(desc, p);
+    if (rc != SP_OK) return rc;
+    if (!bytes) return sp::fail(SP_ERR_INVALID_ARG, "bytes is null");
+    if (total_tokens < 0 || n_prompts < 1 || n_prompts > kMaxPrompts)
+        return sp::fail(SP_ERR_INVALID_ARG, "total_tokens must be >= 0 and n_prompts in 1..%d", kMaxPrompts);
+    const int64_t n_tiles = (total_tokens + p.tile_keys - 1) / p.tile_keys + n_prompts;
+    *bytes = ws_layout(p, n_tiles, n_prompts).total;
+    return SP_OK;
+}
+
+extern "C" sp_status sp_score(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
+                              int64_t L, float *scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
+{
+    return score_impl(desc, q_dev, k_layers_host, nullptr, nullptr, 1, L, scores_dev, ws_dev, ws_bytes, hip_stream);
+}
+
+extern "C" sp_status sp_score_batch(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
+                                    const int64_t *offsets_host, const int64_t *offsets_dev, int32_t B,
+                                    float *scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
+{
+    if (!offsets_host) return sp::fail(SP_ERR_INVALID_ARG, "offsets_host is null");
+    return score_impl(desc, q_dev, k_layers_host, offsets_host, offsets_dev, B, 0, scores_dev, ws_dev, ws_bytes,
+                      hip_stream);
+}

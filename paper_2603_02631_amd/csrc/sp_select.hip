@@ -1,0 +1,231 @@
+// sp_select: average pooling, chunk means, top-k chunks, merged spans
+// (paper: Algorithm 1 "AvgPool1D", "PartitionIntoChunks", "TopKChunks",
+// "MergeAdjacentChunks"; Appendix A.1.2; Appendix A.3).
+//
+// Two kernels:
+//   sp_chunk_kernel  one wavefront per chunk. The wave stages the chunk's
+//                    scores plus a (w-1)/2 halo through its own LDS slice in
+//                    segments, each lane forms the window sums of four
+//                    consecutive tokens, and a fixed-order shuffle tree gives
+//                    the chunk mean. The pooled vector is never written out.
+//   sp_topk_kernel   one workgroup. MSB-first radix select (4 passes of 8 bits)
+//                    on order-preserving integer images of the fp32 chunk
+//                    scores finds the k-th largest score exactly; chunks above
+//                    it are kept, chunks equal to it are kept in index order
+//                    until k is reached (lower index wins a tie). Two block
+//                    scans then emit the kept indices in ascending order and
+//                    the merged spans.
+// Everything is integer or fixed-order fp32 work, so results are deterministic.
+#include "sp_common.hpp"
+
+namespace {
+
+constexpr int kChunkThreads = 256;           // 4 waves, one chunk each
+constexpr int kSeg = 256;                    // tokens staged per wave per step
+constexpr int kMaxPool = 129;                // halo (w-1)/2 <= 64 fits the staging slice
+constexpr int kSegLds = kSeg + kMaxPool - 1; // staged floats per wave
+constexpr int kTopkThreads = 1024;
+
+__global__ __launch_bounds__(kChunkThreads) void sp_chunk_kernel(const float *__restrict__ scores, int64_t L,
+                                                                 int pool_w, int chunk, int64_t n_chunks,
+                                                                 float *__restrict__ cs_ws,
+                                                                 float *__restrict__ cs_out)
+{
+    __shared__ float stage[kChunkThreads / 64][kSegLds + 3];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t ci = (int64_t)blockIdx.x * (kChunkThreads / 64) + wave;
+    if (ci >= n_chunks) return;              // whole wave leaves together; no block barrier is used
+    float *st = stage[wave];
+    const int half = (pool_w - 1) / 2;
+    const int64_t begin = ci * chunk;
+    const int64_t end = (begin + chunk < L) ? begin + chunk : L;
+    float part = 0.f;
+    for (int64_t seg = begin; seg < end; seg += kSeg) {
+        const int n_tok = (int)((end - seg < kSeg) ? end - seg : kSeg);
+        const int n_stage = n_tok + 2 * half;
+        for (int i = lane; i < n_stage; i += 64) {
+            const int64_t j = seg - half + i;
+            st[i] = (j >= 0 && j < L) ? scores[j] : 0.f;
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        // lane handles tokens 4*lane .. 4*lane+3 of the segment; each window is summed on its own
+        const int t0 = 4 * lane;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (t0 + e < n_tok) {
+                float win = 0.f;
+                for (int i = 0; i < pool_w; ++i) win += st[t0 + e + i];
+                part += win;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off);
+    if (lane == 0) {
+        const float v = part / ((float)pool_w * (float)(end - begin)) + 0.0f;
+        cs_ws[ci] = v;
+        if (cs_out) cs_out[ci] = v;
+    }
+}
+
+// fp32 -> uint32 whose unsigned order is the float order (-0 mapped onto +0 first).
+__device__ __forceinline__ uint32_t order_key(float v)
+{
+    const uint32_t u = __float_as_uint(v + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Inclusive block scan of one int per thread (1024 threads = 16 waves).
+__device__ __forceinline__ int block_scan_incl(int v, int *wave_tot /*[16]*/, int &block_total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(x, off);
+        if (lane >= off) x += y;
+    }
+    __syncthreads();                         // protects wave_tot from the previous use
+    if (lane == 63) wave_tot[wave] = x;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kTopkThreads / 64; ++w) {
+        const int t = wave_tot[w];
+        if (w < wave) base += t;
+        tot += t;
+    }
+    block_total = tot;
+    return x + base;
+}
+
+__global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__restrict__ cs, int64_t n_chunks,
+                                                               int64_t k, int chunk, int64_t L,
+                                                               int32_t *sel,
+                                                               int64_t *__restrict__ spans,
+                                                               int32_t *__restrict__ n_spans)
+{
+    __shared__ int hist[256];
+    __shared__ int wave_tot[kTopkThreads / 64];
+    __shared__ uint32_t s_prefix;
+    __shared__ int64_t s_need;
+    const int tid = threadIdx.x;
+
+    // ---- radix select: key of the k-th largest chunk score ----
+    uint32_t prefix = 0, mask = 0;
+    int64_t need = k;                        // how many still to take from the current bucket
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int64_t i = tid; i < n_chunks; i += kTopkThreads) {
+            const uint32_t key = order_key(cs[i]);
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int64_t above = 0;
+            int b = 255;
+            for (; b > 0; --b) {
+                if (above + hist[b] >= need) break;
+                above += hist[b];
+            }
+            s_prefix = prefix | ((uint32_t)b << shift);
+            s_need = need - above;
+        }
+        __syncthreads();
+        prefix = s_prefix;
+        need = s_need;
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    const uint32_t thr = prefix;             // exact key of the k-th largest score
+    // `need` = number of chunks equal to thr to keep, taken in index order.
+
+    // ---- emit kept chunk indices in ascending order ----
+    int64_t eq_seen = 0, out_base = 0;
+    for (int64_t base = 0; base < n_chunks; base += kTopkThreads) {
+        const int64_t i = base + tid;
+        uint32_t key = 0;
+        if (i < n_chunks) key = order_key(cs[i]);
+        const int is_eq = (i < n_chunks && key == thr) ? 1 : 0;
+        int eq_total;
+        const int eq_rank = block_scan_incl(is_eq, wave_tot, eq_total);   // 1-based among equals of this segment
+        const int keep = (i < n_chunks) && (key > thr || (is_eq && eq_seen + eq_rank <= need));
+        int keep_total;
+        const int pos = block_scan_incl(keep, wave_tot, keep_total);
+        if (keep) sel[out_base + pos - 1] = (int32_t)i;
+        eq_seen += eq_total;
+        out_base += keep_total;
+    }
+    __syncthreads();                         // sel[] written by this block is read below
+
+    // ---- merge runs of adjacent kept chunks into token spans ----
+    int64_t span_base = 0;
+    for (int64_t base = 0; base < k; base += kTopkThreads) {
+        const int64_t p = base + tid;
+        int start = 0, last = 0;
+        int32_t c = 0;
+        if (p < k) {
+            c = sel[p];
+            start = (p == 0) || (sel[p - 1] != c - 1);
+            last = (p == k - 1) || (sel[p + 1] != c + 1);
+        }
+        int tot;
+        const int id = block_scan_incl(start, wave_tot, tot);            // 1-based span id of this element
+        if (p < k) {
+            const int64_t s = span_base + id - 1;
+            if (start) spans[2 * s] = (int64_t)c * chunk;
+            if (last) {
+                const int64_t e = ((int64_t)c + 1) * chunk;
+                spans[2 * s + 1] = e < L ? e : L;
+            }
+        }
+        span_base += tot;
+    }
+    if (tid == 0) *n_spans = (int32_t)span_base;
+}
+
+}  // namespace
+
+extern "C" sp_status sp_select_workspace(int64_t L, int32_t chunk, size_t *bytes)
+{
+    if (!bytes) return sp::fail(SP_ERR_INVALID_ARG, "bytes is null");
+    if (L < 1 || chunk < 1) return sp::fail(SP_ERR_INVALID_ARG, "L and chunk must be >= 1");
+    const int64_t C = (L + chunk - 1) / chunk;
+    *bytes = sp::align_up(sizeof(float) * (size_t)C, 256);
+    return SP_OK;
+}
+
+extern "C" sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_w, int32_t chunk, int64_t k,
+                               int32_t *sel_chunks_dev, int64_t *spans_dev, int32_t *n_spans_dev,
+                               float *chunk_scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
+{
+    if (!scores_dev || !sel_chunks_dev || !spans_dev || !n_spans_dev)
+        return sp::fail(SP_ERR_INVALID_ARG, "scores_dev, sel_chunks_dev, spans_dev and n_spans_dev must not be null");
+    if (L < 1) return sp::fail(SP_ERR_INVALID_ARG, "L = %lld must be >= 1", (long long)L);
+    if (chunk < 1) return sp::fail(SP_ERR_INVALID_ARG, "chunk = %d must be >= 1", chunk);
+    if (pool_w < 1 || pool_w % 2 == 0) return sp::fail(SP_ERR_INVALID_ARG, "pool_w = %d must be odd and >= 1", pool_w);
+    if (pool_w > kMaxPool) return sp::fail(SP_ERR_UNSUPPORTED, "pool_w = %d (supported: <= %d)", pool_w, kMaxPool);
+    const int64_t C = (L + chunk - 1) / chunk;
+    if (C > (1 << 30)) return sp::fail(SP_ERR_UNSUPPORTED, "too many chunks (%lld)", (long long)C);
+    if (k < 1 || k > C) return sp::fail(SP_ERR_INVALID_ARG, "k = %lld outside 1..%lld", (long long)k, (long long)C);
+    const size_t need = sp::align_up(sizeof(float) * (size_t)C, 256);
+    if (!ws_dev) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is null (%zu bytes needed)", need);
+    if ((uintptr_t)ws_dev % 256 != 0) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is not 256-byte aligned");
+    if (ws_bytes < need) return sp::fail(SP_ERR_WORKSPACE, "workspace too small: %zu < %zu", ws_bytes, need);
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    float *cs = static_cast<float *>(ws_dev);
+    const int waves_per_block = kChunkThreads / 64;
+    const unsigned grid = (unsigned)((C + waves_per_block - 1) / waves_per_block);
+    hipLaunchKernelGGL(sp_chunk_kernel, dim3(grid), dim3(kChunkThreads), 0, st, scores_dev, L, (int)pool_w,
+                       (int)chunk, C, cs, chunk_scores_dev);
+    SP_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(sp_topk_kernel, dim3(1), dim3(kTopkThreads), 0, st, (const float *)cs, C, k, (int)chunk, L,
+                       sel_chunks_dev, spans_dev, n_spans_dev);
+    SP_HIP_CHECK(hipGetLastError());
+    return SP_OK;
+}

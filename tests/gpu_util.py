@@ -1,0 +1,118 @@
+"""Helpers that drive the C-ABI library from numpy inputs (GPU tests only).
+
+torch is used for device memory and nothing else: every tensor here is a raw
+buffer whose address is handed to the library.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+import paper_2603_02631_amd as sp
+
+DEV = "cuda:0"
+
+
+def dev_bits(a: np.ndarray) -> torch.Tensor:
+    """uint16 bf16 bit patterns -> device buffer (int16 view, same bytes)."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint16).view(np.int16)).to(DEV)
+
+
+def make_desc(n_layers, H, Hkv, d, n_q, scale, layer_agg, layout, T) -> sp.ScoreDesc:
+    if layout == "HND":
+        st, sh = d, T * d
+    else:
+        st, sh = Hkv * d, d
+    return sp.ScoreDesc(n_layers, H, Hkv, d, n_q, float(scale), int(layer_agg), st, sh)
+
+
+def workspace(nbytes: int) -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=DEV)
+
+
+def gpu_score(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], scale: float, layer_agg: int = 0,
+              layout: str = "HND", k_dev: Optional[List[torch.Tensor]] = None) -> np.ndarray:
+    """q_bits: uint16 [Lyr][H][n_q][d]; k_layers: uint16 [Hkv][L][d] (HND) or [L][Hkv][d] (NHD)."""
+    Lyr, H, n_q, d = q_bits.shape
+    if layout == "HND":
+        Hkv, L, _ = k_layers[0].shape
+    else:
+        L, Hkv, _ = k_layers[0].shape
+    desc = make_desc(Lyr, H, Hkv, d, n_q, scale, layer_agg, layout, L)
+    qd = dev_bits(q_bits)
+    kd = k_dev if k_dev is not None else [dev_bits(k) for k in k_layers]
+    ws = workspace(sp.sp_score_workspace(desc, L, 1))
+    scores = torch.full((max(L, 1),), float("nan"), dtype=torch.float32, device=DEV)
+    sp.sp_score(desc, qd, kd, L, scores, ws)
+    torch.cuda.synchronize()
+    return scores[:L].cpu().numpy()
+
+
+def gpu_score_batch(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], offsets: np.ndarray, scale: float,
+                    layer_agg: int = 0, layout: str = "HND") -> np.ndarray:
+    """q_bits: uint16 [B][Lyr][H][n_q][d]; k_layers packed along tokens."""
+    B, Lyr, H, n_q, d = q_bits.shape
+    T = int(offsets[-1])
+    Hkv = k_layers[0].shape[0] if layout == "HND" else k_layers[0].shape[1]
+    desc = make_desc(Lyr, H, Hkv, d, n_q, scale, layer_agg, layout, T)
+    qd = dev_bits(q_bits)
+    kd = [dev_bits(k) for k in k_layers]
+    off_d = torch.from_numpy(np.ascontiguousarray(offsets, dtype=np.int64)).to(DEV)
+    ws = workspace(sp.sp_score_workspace(desc, T, B))
+    scores = torch.full((max(T, 1),), float("nan"), dtype=torch.float32, device=DEV)
+    sp.sp_score_batch(desc, qd, kd, [int(v) for v in offsets], off_d, scores, ws)
+    torch.cuda.synchronize()
+    return scores[:T].cpu().numpy()
+
+
+def gpu_select(scores: np.ndarray, pool_w: int, chunk: int, k: int, want_chunk_scores: bool = True):
+    """Returns (sel int32[k], spans int64[n][2], chunk_scores float32[C] or None)."""
+    L = scores.size
+    C = (L + chunk - 1) // chunk
+    sd = torch.from_numpy(np.ascontiguousarray(scores, dtype=np.float32)).to(DEV)
+    sel = torch.full((k,), -1, dtype=torch.int32, device=DEV)
+    spans = torch.full((k, 2), -1, dtype=torch.int64, device=DEV)
+    n_spans = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    cs = torch.full((C,), float("nan"), dtype=torch.float32, device=DEV) if want_chunk_scores else None
+    ws = workspace(sp.sp_select_workspace(L, chunk))
+    sp.sp_select(sd, L, pool_w, chunk, k, sel, spans, n_spans, cs, ws)
+    torch.cuda.synchronize()
+    n = int(n_spans.item())
+    return sel.cpu().numpy(), spans[:n].cpu().numpy(), (cs.cpu().numpy() if cs is not None else None)
+
+
+def gpu_project(draft_off: np.ndarray, target_off: np.ndarray, spans: np.ndarray, want_mask: bool = True,
+                max_spans: Optional[int] = None):
+    """Returns (tspans int64[n][2], mask uint8[M] or None, n_kept)."""
+    L, M = draft_off.size - 1, target_off.size - 1
+    spans = np.ascontiguousarray(spans, dtype=np.int64).reshape(-1, 2)
+    ns = spans.shape[0]
+    cap = max_spans if max_spans is not None else max(ns, 1)
+    dd = torch.from_numpy(np.ascontiguousarray(draft_off, dtype=np.int64)).to(DEV)
+    td = torch.from_numpy(np.ascontiguousarray(target_off, dtype=np.int64)).to(DEV)
+    sp_buf = torch.zeros((cap, 2), dtype=torch.int64, device=DEV)
+    if ns:
+        sp_buf[:ns] = torch.from_numpy(spans).to(DEV)
+    n_sp = torch.tensor([ns], dtype=torch.int32, device=DEV)
+    tsp = torch.full((cap, 2), -1, dtype=torch.int64, device=DEV)
+    n_t = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    mask = torch.full((M,), 7, dtype=torch.uint8, device=DEV) if want_mask else None
+    n_kept = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    sp.sp_project(dd, L, td, M, sp_buf, n_sp, cap, tsp, n_t, mask, n_kept)
+    torch.cuda.synchronize()
+    n = int(n_t.item())
+    return tsp[:n].cpu().numpy(), (mask.cpu().numpy() if mask is not None else None), int(n_kept.item())
+
+
+def assert_scores_close(got: np.ndarray, want: np.ndarray, rel: float = 1e-3):
+    """|g - o| <= rel * |o| + 1e-30 element by element."""
+    got = got.astype(np.float64)
+    assert got.shape == want.shape
+    assert np.isfinite(got).all(), "non-finite GPU scores"
+    err = np.abs(got - want)
+    bound = rel * np.abs(want) + 1e-30
+    bad = np.nonzero(err > bound)[0]
+    assert bad.size == 0, (f"{bad.size} of {got.size} scores off; worst rel err "
+                           f"{(err / np.maximum(np.abs(want), 1e-300)).max():.3e} at {int(np.argmax(err / np.maximum(np.abs(want), 1e-300)))}")

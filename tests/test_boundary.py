@@ -1,0 +1,161 @@
+"""CPU-side checks of the C-ABI boundary: the library loads, exports every
+symbol the header declares, and rejects bad host-visible arguments before
+anything is launched (so these calls never touch a GPU)."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2603_02631_amd as sp
+from paper_2603_02631_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sp_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sp.load_library()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert "gfx950" in sp.sp_version()
+
+
+def test_keep_count_host_function():
+    for line in open(os.path.join(ROOT, "tests", "golden", "keep_count.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        C, num, den, k = map(int, line.split())
+        assert sp.sp_keep_count(C, num, den) == k
+    assert sp.sp_keep_count(10, 0, 100) == 1
+    assert sp.sp_keep_count(10, 1000, 100) == 10
+    assert sp.sp_keep_count(0, 1, 2) == -1
+    assert sp.sp_keep_count(5, 1, 0) == -1
+    assert sp.sp_keep_count(5, -1, 2) == -1
+    assert sp.sp_keep_count(2 ** 40, 2 ** 30, 2 ** 31) == 2 ** 39
+
+
+def good_desc(**kw):
+    base = dict(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64, n_q=8, scale=0.125, layer_agg=0,
+                k_stride_token=64, k_stride_head=64 * 1024)
+    base.update(kw)
+    return sp.ScoreDesc(*[base[f[0]] for f in sp.ScoreDesc._fields_])
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_layers=0), 1), (dict(n_q_heads=5), 1), (dict(n_q=0), 1), (dict(scale=0.0), 1),
+    (dict(scale=float("nan")), 1), (dict(scale=-1.0), 1), (dict(layer_agg=2), 1),
+    (dict(k_stride_token=60), 1), (dict(k_stride_token=32), 1), (dict(k_stride_head=-8), 1),
+    (dict(head_dim=96), 2), (dict(n_q=17), 2), (dict(n_layers=129), 2),
+    (dict(n_q_heads=34, n_kv_heads=2), 2),
+    (dict(n_q_heads=32, n_kv_heads=2, n_q=16, head_dim=128, k_stride_token=128), 2),
+])
+def test_score_desc_validation(kw, status):
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_score_workspace(good_desc(**kw), 1024, 1)
+    assert e.value.status == status
+    assert sp.sp_last_error() != ""
+
+
+def test_score_workspace_and_argument_errors():
+    d = good_desc()
+    n = sp.sp_score_workspace(d, 1024, 1)
+    assert n > 0 and n % 256 == 0
+    assert sp.sp_score_workspace(d, 0, 1) >= 0
+    with pytest.raises(sp.SpError):
+        sp.sp_score_workspace(d, -1, 1)
+    with pytest.raises(sp.SpError):
+        sp.sp_score_workspace(d, 10, 0)
+    lib = sp.load_library()
+    assert lib.sp_score_workspace(None, 10, 1, ctypes.byref(ctypes.c_size_t())) == 1
+    assert lib.sp_score_workspace(ctypes.byref(d), 10, 1, None) == 1
+
+    fake = 0x1000  # never dereferenced: validation fails first
+    layers = [fake, fake]
+    with pytest.raises(sp.SpError) as e:        # null q
+        sp.sp_score(d, None, layers, 1024, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:        # null layer pointer
+        sp.sp_score(d, fake, [fake, None], 1024, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:        # misaligned layer pointer
+        sp.sp_score(d, fake, [fake, fake + 2], 1024, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:        # negative length
+        sp.sp_score(d, fake, layers, -5, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:        # workspace missing
+        sp.sp_score(d, fake, layers, 1024, fake, None, 0, stream=0)
+    assert e.value.status == 3
+    with pytest.raises(sp.SpError) as e:        # workspace too small
+        sp.sp_score(d, fake, layers, 1024, fake, fake, 256, stream=0)
+    assert e.value.status == 3
+    with pytest.raises(sp.SpError) as e:        # workspace misaligned
+        sp.sp_score(d, fake, layers, 1024, fake, fake + 16, n, stream=0)
+    assert e.value.status == 3
+    with pytest.raises(sp.SpError):             # wrong number of layers (caught by the binding)
+        sp.sp_score(d, fake, [fake], 1024, fake, fake, n, stream=0)
+    sp.sp_score(d, fake, layers, 0, fake, None, 0, stream=0)   # empty prompt: no-op, SP_OK
+
+
+def test_score_batch_argument_errors():
+    d = good_desc()
+    fake = 0x1000
+    layers = [fake, fake]
+    n = sp.sp_score_workspace(d, 4096, 3)
+    with pytest.raises(sp.SpError) as e:        # offsets must start at 0
+        sp.sp_score_batch(d, fake, layers, [1, 5, 9], fake, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:        # decreasing offsets
+        sp.sp_score_batch(d, fake, layers, [0, 9, 5], fake, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:        # device copy missing
+        sp.sp_score_batch(d, fake, layers, [0, 5, 9], None, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:        # no prompts
+        sp.sp_score_batch(d, fake, layers, [0], fake, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    sp.sp_score_batch(d, fake, layers, [0, 0, 0], fake, fake, None, 0, stream=0)   # all empty: no-op
+
+
+def test_select_argument_errors():
+    fake = 0x1000
+    n = sp.sp_select_workspace(1000, 32)
+    assert n >= 32 * 4 and n % 256 == 0
+    with pytest.raises(sp.SpError):
+        sp.sp_select_workspace(0, 32)
+    with pytest.raises(sp.SpError):
+        sp.sp_select_workspace(10, 0)
+
+    def call(L=1000, pool=13, chunk=32, k=4, scores=fake, sel=fake, spans=fake, ns=fake, ws=fake, wsb=n):
+        sp.sp_select(scores, L, pool, chunk, k, sel, spans, ns, None, ws, wsb, stream=0)
+
+    for kw, status in [(dict(scores=None), 1), (dict(sel=None), 1), (dict(spans=None), 1), (dict(ns=None), 1),
+                       (dict(L=0), 1), (dict(chunk=0), 1), (dict(pool=12), 1), (dict(pool=0), 1), (dict(pool=-3), 1),
+                       (dict(pool=131), 2), (dict(k=0), 1), (dict(k=33), 1), (dict(ws=None, wsb=0), 3),
+                       (dict(wsb=0), 3), (dict(ws=fake + 8), 3)]:
+        with pytest.raises(sp.SpError) as e:
+            call(**kw)
+        assert e.value.status == status, kw
+
+
+def test_project_argument_errors():
+    fake = 0x1000
+
+    def call(doff=fake, L=10, toff=fake, M=12, spans=fake, ns=fake, cap=4, tsp=fake, nt=fake, nk=fake):
+        sp.sp_project(doff, L, toff, M, spans, ns, cap, tsp, nt, None, nk, stream=0)
+
+    for kw in [dict(doff=None), dict(toff=None), dict(spans=None), dict(ns=None), dict(tsp=None), dict(nt=None),
+               dict(nk=None), dict(L=0), dict(M=0), dict(cap=0), dict(cap=(1 << 24) + 1)]:
+        with pytest.raises(sp.SpError) as e:
+            call(**kw)
+        assert e.value.status == 1, kw

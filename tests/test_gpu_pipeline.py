@@ -1,0 +1,92 @@
+"""End-to-end GPU parity of the whole path (score -> select -> project) on the
+synthetic workloads, chained on the device the way the benchmark runs it."""
+from __future__ import annotations
+
+import sys
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_pipeline_gpu(w, q_bits, k_dev, L, doff, toff, mode):
+    """One pass of the hot path with every intermediate left on the device."""
+    import torch
+    import paper_2603_02631_amd as sp
+    from gpu_util import DEV, dev_bits, make_desc, workspace
+    C = (L + w.chunk - 1) // w.chunk
+    k = sp.sp_keep_count(C, w.keep_num, w.keep_den)
+    M = toff.size - 1
+    desc = make_desc(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_q, w.scale, mode, "HND", L)
+    qd = dev_bits(q_bits)
+    ws1 = workspace(sp.sp_score_workspace(desc, L, 1))
+    ws2 = workspace(sp.sp_select_workspace(L, w.chunk))
+    scores = torch.empty(L, dtype=torch.float32, device=DEV)
+    sel = torch.empty(k, dtype=torch.int32, device=DEV)
+    spans = torch.empty((k, 2), dtype=torch.int64, device=DEV)
+    n_spans = torch.zeros(1, dtype=torch.int32, device=DEV)
+    cs = torch.empty(C, dtype=torch.float32, device=DEV)
+    dd = torch.from_numpy(doff).to(DEV)
+    td = torch.from_numpy(toff).to(DEV)
+    tsp = torch.empty((k, 2), dtype=torch.int64, device=DEV)
+    n_t = torch.zeros(1, dtype=torch.int32, device=DEV)
+    mask = torch.empty(M, dtype=torch.uint8, device=DEV)
+    n_kept = torch.zeros(1, dtype=torch.int64, device=DEV)
+    sp.sp_score(desc, qd, k_dev, L, scores, ws1)
+    sp.sp_select(scores, L, w.pool, w.chunk, k, sel, spans, n_spans, cs, ws2)
+    sp.sp_project(dd, L, td, M, spans, n_spans, k, tsp, n_t, mask, n_kept)
+    torch.cuda.synchronize()
+    ns, nt = int(n_spans.item()), int(n_t.item())
+    return dict(scores=scores.cpu().numpy(), sel=sel.cpu().numpy().astype(np.int64), spans=spans[:ns].cpu().numpy(),
+                cs=cs.cpu().numpy(), tspans=tsp[:nt].cpu().numpy(), mask=mask.cpu().numpy(),
+                n_kept=int(n_kept.item()), k=k)
+
+
+def check_pipeline(w, out, I, doff, toff, eps=2e-3):
+    from gpu_util import assert_scores_close
+    L = I.size
+    assert_scores_close(out["scores"], I)
+    o_sel, o_spans, o_cs = oracle.select(I, w.pool, w.chunk, out["k"])
+    np.testing.assert_allclose(out["cs"].astype(np.float64), o_cs, rtol=1e-3)
+    # selection: exact on the GPU's own chunk scores, and equal to the oracle's modulo near-ties
+    np.testing.assert_array_equal(out["sel"], oracle.topk(out["cs"].astype(np.float64), out["k"]))
+    tau = np.sort(o_cs)[::-1][out["k"] - 1]
+    kept = np.zeros(o_cs.size, bool)
+    kept[out["sel"]] = True
+    assert kept[o_cs > tau * (1 + eps)].all() and not kept[o_cs < tau * (1 - eps)].any()
+    diff = np.setxor1d(out["sel"], o_sel).size
+    # spans and projection: exact given the GPU's selection
+    np.testing.assert_array_equal(out["spans"], oracle.merge(out["sel"], w.chunk, L))
+    ts, mask, n = oracle.project(doff, toff, out["spans"])
+    np.testing.assert_array_equal(out["tspans"], ts)
+    np.testing.assert_array_equal(out["mask"], mask)
+    assert out["n_kept"] == n
+    return diff
+
+
+@pytest.mark.parametrize("name", ["tiny", "llama1b-8k", "qwen06b-32k"])
+def test_pipeline_small_configs(name):
+    from gpu_util import dev_bits
+    w = synth.get_config(name)
+    say(f"[pipeline] {name}: generating")
+    inp = synth.make_score_inputs(w)
+    doff, toff = synth.gen_char_offsets(w, w.L)
+    k_dev = [dev_bits(k) for k in inp["k"]]
+    for mode in (0, 1):
+        t0 = time.time()
+        I = oracle.score(inp["q"][0], inp["k"], w.scale, mode)
+        say(f"[pipeline] {name} mode {mode}: oracle {time.time() - t0:.1f}s")
+        out = run_pipeline_gpu(w, inp["q"][0], k_dev, w.L, doff, toff, mode)
+        diff = check_pipeline(w, out, I, doff, toff)
+        say(f"[pipeline] {name} mode {mode}: ok, selection differs from oracle in {diff} chunks, "
+            f"kept {out['n_kept']} of {toff.size - 1} target tokens")

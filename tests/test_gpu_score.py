@@ -1,0 +1,147 @@
+"""GPU parity of sp_score / sp_score_batch against the CPU float64 oracle,
+element by element on the same seeded inputs. Tolerance (stated target of the
+build): |gpu - oracle| <= 1e-3 * |oracle| for every token, both aggregation
+modes. All calls go through the C ABI."""
+from __future__ import annotations
+
+import dataclasses
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def small_workload(name, Lyr, H, Hkv, d, n_q, L, cfg_id=100, hh=(1, 100)):
+    return synth.Workload(name, cfg_id, Lyr, H, Hkv, d, n_q, L, hh_frac_num=hh[0], hh_frac_den=hh[1])
+
+
+SHAPES = [
+    # name, Lyr, H, Hkv, d, n_q, L   (several key tiles and a ragged tail unless noted)
+    ("g4_nq16_d64", 3, 8, 2, 64, 16, 1500),
+    ("g4_nq8_d64", 2, 8, 2, 64, 8, 777),
+    ("g2_nq8_d128", 3, 4, 2, 128, 8, 777),
+    ("g1_nq3_d64", 2, 3, 3, 64, 3, 333),
+    ("g8_nq5_d128", 2, 8, 1, 128, 5, 300),
+    ("g16_nq16_d64", 1, 16, 1, 64, 16, 260),
+    ("g3_nq9_d64", 2, 6, 2, 64, 9, 515),
+    ("one_key", 2, 4, 2, 64, 8, 1),
+    ("exact_tile", 2, 4, 2, 64, 8, 256),
+    ("tile_plus_one", 2, 4, 2, 64, 8, 257),
+    ("sub_tile_d128", 2, 4, 2, 128, 8, 31),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=[s[0] for s in SHAPES])
+@pytest.mark.parametrize("mode", [oracle.LAYER_MEAN, oracle.LAYER_MAX], ids=["mean", "max"])
+def test_score_matches_oracle(shape, mode):
+    from gpu_util import assert_scores_close, gpu_score
+    name, Lyr, H, Hkv, d, n_q, L = shape
+    say(f"[score] {name} mode={mode} Lyr={Lyr} H={H} Hkv={Hkv} d={d} n_q={n_q} L={L}")
+    w = small_workload(name, Lyr, H, Hkv, d, n_q, L, cfg_id=100 + SHAPES.index(shape))
+    inp = synth.make_score_inputs(w)
+    want = oracle.score(inp["q"][0], inp["k"], w.scale, mode)
+    got = gpu_score(inp["q"][0], inp["k"], w.scale, mode)
+    assert_scores_close(got, want)
+
+
+@pytest.mark.parametrize("cfg", ["tiny"])
+@pytest.mark.parametrize("layout", ["HND", "NHD"])
+@pytest.mark.parametrize("mode", [0, 1], ids=["mean", "max"])
+def test_score_tiny_config_both_layouts(cfg, layout, mode):
+    from gpu_util import assert_scores_close, gpu_score
+    say(f"[score] cfg={cfg} layout={layout} mode={mode}")
+    w = synth.get_config(cfg)
+    inp = synth.make_score_inputs(w, layout=layout)
+    want = oracle.score(inp["q"][0], inp["k"], w.scale, mode, layout=layout)
+    got = gpu_score(inp["q"][0], inp["k"], w.scale, mode, layout=layout)
+    assert_scores_close(got, want)
+
+
+def test_score_closed_forms_on_gpu():
+    """Uniform keys give 1/L; a single dominant key captures the score; a huge
+    common shift of all keys does not change the result (max-subtraction)."""
+    from gpu_util import gpu_score
+    say("[score] closed forms")
+    rng = np.random.default_rng(5)
+    Lyr, H, Hkv, n_q, d, L = 2, 8, 2, 8, 64, 700
+    q = synth.f32_to_bf16_bits(rng.integers(-3, 4, size=(Lyr, H, n_q, d)).astype(np.float32) * 0.25)
+    krow = rng.integers(-3, 4, size=(Hkv, 1, d)).astype(np.float32)
+    k = [synth.f32_to_bf16_bits(np.repeat(krow, L, axis=1)) for _ in range(Lyr)]
+    for mode in (0, 1):
+        got = gpu_score(q, k, 0.125, mode)
+        np.testing.assert_allclose(got, 1.0 / L, rtol=1e-5)
+    # dominant key
+    kz = np.zeros((Hkv, L, d), np.float32)
+    kz[:, 123, :] = 8.0 * synth.bf16_bits_to_f32(q[0, 0, 0])[None, :]
+    kd = [synth.f32_to_bf16_bits(kz) for _ in range(Lyr)]
+    want = oracle.score(q, kd, 0.125, 1)
+    got = gpu_score(q, kd, 0.125, 1)
+    np.testing.assert_allclose(got, want, rtol=1e-3)
+    assert got.argmax() == 123
+    # shift invariance with a large shift (exact in bf16: |k + v| <= 67)
+    kf = rng.integers(-3, 4, size=(Hkv, L, d)).astype(np.float32)
+    v = rng.choice([-64.0, 64.0], size=(1, 1, d)).astype(np.float32)
+    base = gpu_score(q, [synth.f32_to_bf16_bits(kf)] * Lyr, 0.125, 0)
+    shifted = gpu_score(q, [synth.f32_to_bf16_bits(kf + v)] * Lyr, 0.125, 0)
+    assert np.isfinite(shifted).all()
+    np.testing.assert_allclose(shifted, base, rtol=2e-4)
+
+
+def test_score_is_deterministic():
+    from gpu_util import gpu_score
+    say("[score] determinism")
+    w = small_workload("det", 3, 8, 2, 64, 16, 2100, cfg_id=150)
+    inp = synth.make_score_inputs(w)
+    a = gpu_score(inp["q"][0], inp["k"], w.scale, 0)
+    b = gpu_score(inp["q"][0], inp["k"], w.scale, 0)
+    assert a.tobytes() == b.tobytes()
+
+
+@pytest.mark.parametrize("layout", ["HND", "NHD"])
+def test_score_batch_matches_oracle_per_prompt(layout):
+    """Ragged batch with an empty prompt, a one-token prompt and lengths around
+    the tile size; each prompt is softmaxed over its own keys only."""
+    from gpu_util import assert_scores_close, gpu_score, gpu_score_batch
+    say(f"[score_batch] layout={layout}")
+    lengths = np.array([300, 1, 0, 513, 256, 77], dtype=np.int64)
+    w = dataclasses.replace(small_workload("rag", 2, 8, 2, 64, 8, 0, cfg_id=160), batch=len(lengths))
+    hh = synth.heavy_hitter_positions(w, lengths)
+    q = synth.gen_q(w, len(lengths))
+    ks = [synth.gen_k_layer(w, l, q, lengths, hh) for l in range(w.n_layers)]      # [Hkv][T][d]
+    offsets = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    packed = ks if layout == "HND" else [np.ascontiguousarray(k.transpose(1, 0, 2)) for k in ks]
+    for mode in (0, 1):
+        got = gpu_score_batch(q, packed, offsets, w.scale, mode, layout=layout)
+        for b, Lb in enumerate(lengths):
+            if Lb == 0:
+                continue
+            sl = slice(int(offsets[b]), int(offsets[b + 1]))
+            kb = [np.ascontiguousarray(k[:, sl, :]) for k in ks]
+            want = oracle.score(q[b], kb, w.scale, mode)
+            assert_scores_close(got[sl], want)
+            if layout == "HND":
+                single = gpu_score(q[b], kb, w.scale, mode)
+                np.testing.assert_allclose(got[sl], single, rtol=1e-6)
+
+
+def test_score_mid_size_config():
+    """The 16-layer, 32/8-head, head_dim-64 shape at L = 8192 (second workload), full element-wise parity."""
+    from gpu_util import assert_scores_close, gpu_score
+    say("[score] llama1b-8k full")
+    w = synth.get_config("llama1b-8k")
+    inp = synth.make_score_inputs(w)
+    for mode in (0, 1):
+        want = oracle.score(inp["q"][0], inp["k"], w.scale, mode)
+        got = gpu_score(inp["q"][0], inp["k"], w.scale, mode)
+        assert_scores_close(got, want)
+        say(f"  mode {mode}: max rel err {np.max(np.abs(got - want) / want):.2e}")
