@@ -32,7 +32,8 @@ SHAPES = [
     ("g2_nq8_d128", 3, 4, 2, 128, 8, 777),
     ("g1_nq3_d64", 2, 3, 3, 64, 3, 333),
     ("g8_nq5_d128", 2, 8, 1, 128, 5, 300),
-    ("g16_nq16_d64", 1, 16, 1, 64, 16, 260),
+    ("g16_nq8_d64", 1, 16, 1, 64, 8, 260),
+    ("g8_nq16_d64", 1, 16, 2, 64, 16, 260),
     ("g3_nq9_d64", 2, 6, 2, 64, 9, 515),
     ("one_key", 2, 4, 2, 64, 8, 1),
     ("exact_tile", 2, 4, 2, 64, 8, 256),
