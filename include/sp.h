@@ -96,6 +96,13 @@ sp_status sp_score(const sp_score_desc *desc, const void *q_dev,
                    float *scores_dev, void *ws_dev, size_t ws_bytes,
                    void *hip_stream);
 
+/* Which implementation sp_score picks for this shape and length on the current
+ * device: 1 = the single-launch kernel that keeps K on chip and reads it from
+ * HBM once (long prompts of head_dim 64 whose query group fits 64 padded rows),
+ * 0 = the three-kernel path, -1 = invalid or unsupported desc. Results are the
+ * same either way (to rounding); this is for reporting. Host-only. */
+int32_t sp_score_is_fused(const sp_score_desc *desc, int64_t L);
+
 /*
  * The same for a ragged batch of B prompts whose keys are packed back to back
  * along the token axis: prompt b owns tokens [offsets[b], offsets[b+1]) of each

@@ -20,7 +20,7 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG_DIR, "libsp_amd.so")
 
 EXPORTS = (
-    "sp_score_workspace", "sp_score", "sp_score_batch", "sp_keep_count", "sp_select_workspace",
+    "sp_score_workspace", "sp_score", "sp_score_is_fused", "sp_score_batch", "sp_keep_count", "sp_select_workspace",
     "sp_select", "sp_project", "sp_last_error", "sp_version",
 )
 
@@ -70,6 +70,8 @@ def load_library():
     lib.sp_score_workspace.argtypes = [D, c.c_int64, c.c_int32, c.POINTER(c.c_size_t)]
     lib.sp_score.argtypes = [D, P, c.POINTER(P), c.c_int64, P, P, c.c_size_t, P]
     lib.sp_score_batch.argtypes = [D, P, c.POINTER(P), c.POINTER(c.c_int64), P, c.c_int32, P, P, c.c_size_t, P]
+    lib.sp_score_is_fused.argtypes = [D, c.c_int64]
+    lib.sp_score_is_fused.restype = c.c_int32
     lib.sp_keep_count.argtypes = [c.c_int64, c.c_int64, c.c_int64]
     lib.sp_keep_count.restype = c.c_int64
     lib.sp_select_workspace.argtypes = [c.c_int64, c.c_int32, c.POINTER(c.c_size_t)]
@@ -77,7 +79,7 @@ def load_library():
     lib.sp_project.argtypes = [P, c.c_int64, P, c.c_int64, P, P, c.c_int32, P, P, P, P, P]
     lib.sp_last_error.restype = c.c_char_p
     lib.sp_version.restype = c.c_char_p
-    for name in ("sp_score_workspace", "sp_score", "sp_score_batch", "sp_select_workspace", "sp_select",
+    for name in ("sp_score_workspace", "sp_score", "sp_score_is_fused", "sp_score_batch", "sp_select_workspace", "sp_select",
                  "sp_project"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
@@ -123,6 +125,10 @@ def sp_score_workspace(desc: ScoreDesc, total_tokens: int, n_prompts: int = 1) -
     n = ctypes.c_size_t(0)
     _check(load_library().sp_score_workspace(ctypes.byref(desc), total_tokens, n_prompts, ctypes.byref(n)))
     return int(n.value)
+
+
+def sp_score_is_fused(desc: ScoreDesc, L: int) -> int:
+    return int(load_library().sp_score_is_fused(ctypes.byref(desc), L))
 
 
 def _layer_array(k_layers: Sequence):

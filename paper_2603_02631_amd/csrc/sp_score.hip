@@ -22,24 +22,20 @@
 // Since A and B fragments are laid out alike, one fragment of K serves as A
 // (rows = keys) in the stats pass and as B (columns = keys) in the prob pass.
 #include "sp_common.hpp"
+#include "sp_score_dev.hpp"
+#include "sp_score_fused.hpp"
 
 #include <cmath>
 #include <cstring>
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+using namespace sp_dev;
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
-constexpr int kMaxLayers = 128;
 constexpr int kMaxPrompts = 4096;
-constexpr int kMaxRows = 256;          // padded query rows per kv head
 constexpr size_t kLdsBudget = 64 * 1024;
-
-struct LayerPtrs { const uint16_t *p[kMaxLayers]; };
 
 struct TileInfo {
     int64_t j0;          // first key of the tile (index into the packed token axis)
@@ -65,21 +61,6 @@ struct ScoreArgs {
     float inv_c;
     float out_scale;          // 1/n_q or 1/(n_q * Lyr)
 };
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
-__device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
-
-// LDS tiles hold rows of D bf16 as D/8 chunks of 16 bytes; the chunk index is
-// XOR-swizzled by the row so that 16 lanes reading one chunk column of 16
-// consecutive rows hit 16 different bank groups.
-template <int D>
-__device__ __forceinline__ int lds_slot(int row, int chunk)
-{
-    constexpr int CH = D / 8;
-    const int s = (CH == 8) ? ((row >> 1) & 7) : (row & 15);
-    return row * CH + (chunk ^ s);
-}
 
 __device__ __forceinline__ TileInfo get_tile(const ScoreArgs &a, int tile, int tile_keys)
 {
@@ -144,22 +125,6 @@ __device__ __forceinline__ void stage_k(u32x4 *ks, const uint16_t *kb, int64_t s
         const int idx = tid + i * kThreads;
         ks[lds_slot<D>(idx / CH, idx % CH)] = v[i];
     }
-}
-
-template <int D>
-__device__ __forceinline__ void load_frag(const u32x4 *tile, int row, int hf, bf16x8 (&f)[D / 16])
-{
-#pragma unroll
-    for (int t = 0; t < D / 16; ++t) f[t] = __builtin_bit_cast(bf16x8, tile[lds_slot<D>(row, 2 * t + hf)]);
-}
-
-// (m, l) <- (m, l) (+) (m2, l2) for running softmax statistics in raw-logit units.
-__device__ __forceinline__ void lse_merge(float &m, float &l, float m2, float l2, float c)
-{
-    const float mm = fmaxf(m, m2);
-    if (mm == neg_inf()) { l = 0.f; return; }
-    l = l * fast_exp2((m - mm) * c) + l2 * fast_exp2((m2 - mm) * c);
-    m = mm;
 }
 
 // ---------------------------------------------------------------------------
@@ -297,7 +262,7 @@ __global__ __launch_bounds__(kThreads) void sp_prob_kernel(ScoreArgs a, LayerPtr
     extern __shared__ u32x4 lds[];
     u32x4 *ks = lds;
     u32x4 *qs = lds + TILE * (D / 8);
-    float *ci = reinterpret_cast<float *>(qs + kMaxRows * 0 + a.rows_pad * (D / 8));   // rows_pad floats
+    float *ci = reinterpret_cast<float *>(qs + a.rows_pad * (D / 8));   // rows_pad floats
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hf = lane >> 5, col = lane & 31;
     const int tile = blockIdx.x;
     const TileInfo ti = get_tile(a, tile, TILE);
@@ -446,8 +411,38 @@ sp_status make_plan(const sp_score_desc *d, Plan &p)
 }
 
 struct WsLayout {
-    size_t part, lse, tiles, prompt_tiles, total;
+    size_t part, lse, tiles, prompt_tiles, fused, total;
 };
+
+// Shapes the fused single-launch kernel can hold on chip (any L; the length test is separate).
+bool fused_shape_ok(const Plan &p) { return p.D == 64 && p.rows_pad <= sp_fused::kMaxRows; }
+
+int fused_workgroups(int64_t L) { return (int)((L + sp_fused::kTileKeys - 1) / sp_fused::kTileKeys); }
+
+bool fused_applies(const Plan &p, int64_t L);
+
+// Compute units of the current device (0 if it cannot be queried); the fused kernel needs one per workgroup.
+int device_compute_units()
+{
+    static thread_local int cached_dev = -1, cached_cus = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (dev != cached_dev) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+        cached_dev = dev;
+        cached_cus = cus;
+    }
+    return cached_cus;
+}
+
+// The fused kernel runs one workgroup of 512 keys per compute unit: long single prompts only.
+bool fused_applies(const Plan &p, int64_t L)
+{
+    if (!fused_shape_ok(p)) return false;
+    const int n_wg = fused_workgroups(L);
+    return n_wg >= sp_fused::kMinWorkgroups && n_wg <= 256 && n_wg <= device_compute_units();
+}
 
 WsLayout ws_layout(const Plan &p, int64_t n_tiles, int n_prompts)
 {
@@ -457,6 +452,12 @@ WsLayout ws_layout(const Plan &p, int64_t n_tiles, int n_prompts)
     w.lse = off;   off = sp::align_up(off + sizeof(float) * (size_t)n_prompts * p.n_phases * p.rows_pad, 256);
     w.tiles = off; off = sp::align_up(off + sizeof(TileInfo) * (size_t)n_tiles, 256);
     w.prompt_tiles = off; off = sp::align_up(off + sizeof(int32_t) * (size_t)(n_prompts + 1), 256);
+    w.fused = off;
+    if (fused_shape_ok(p) && n_prompts == 1) {
+        int64_t n_wg = n_tiles * p.tile_keys / sp_fused::kTileKeys + 1;
+        if (n_wg > 1024) n_wg = 1024;
+        off += sp_fused::workspace_bytes(p.rows_pad, (int)n_wg);
+    }
     w.total = off;
     return w;
 }
@@ -548,6 +549,25 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
     a.inv_c = 1.0f / a.c;
     a.out_scale = (desc->layer_agg == SP_LAYER_MAX) ? 1.0f / (float)desc->n_q
                                                    : 1.0f / ((float)desc->n_q * (float)desc->n_layers);
+    if (!batch && fused_applies(p, total)) {
+        const int n_wg = fused_workgroups(total);
+        {
+            sp_fused::FusedArgs f;
+            std::memset(&f, 0, sizeof f);
+            f.q = a.q;
+            f.k_stride_token = a.k_stride_token;
+            f.k_stride_head = a.k_stride_head;
+            f.L = total;
+            f.scores = scores_dev;
+            f.n_wg = n_wg;
+            f.n_layers = a.n_layers; f.n_q_heads = a.n_q_heads; f.n_kv_heads = a.n_kv_heads;
+            f.group = a.group; f.n_q = a.n_q;
+            f.n_nblk = a.n_nblk; f.n_gblk = a.n_gblk; f.rows_pad = a.rows_pad;
+            f.layer_agg = a.layer_agg;
+            f.c = a.c; f.inv_c = a.inv_c; f.out_scale = a.out_scale;
+            return sp_fused::launch(f, kp, ws + w.fused, st);
+        }
+    }
     if (batch) {
         TileInfo *tiles = reinterpret_cast<TileInfo *>(ws + w.tiles);
         int32_t *pt = reinterpret_cast<int32_t *>(ws + w.prompt_tiles);
@@ -575,6 +595,13 @@ extern "C" sp_status sp_score_workspace(const sp_score_desc *desc, int64_t total
     const int64_t n_tiles = (total_tokens + p.tile_keys - 1) / p.tile_keys + n_prompts;
     *bytes = ws_layout(p, n_tiles, n_prompts).total;
     return SP_OK;
+}
+
+extern "C" int32_t sp_score_is_fused(const sp_score_desc *desc, int64_t L)
+{
+    Plan p;
+    if (make_plan(desc, p) != SP_OK) return -1;
+    return fused_applies(p, L) ? 1 : 0;
 }
 
 extern "C" sp_status sp_score(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,

@@ -1,0 +1,35 @@
+// Host interface of the fused single-launch score kernel (see sp_score_fused.hip).
+#pragma once
+
+#include "sp_common.hpp"
+#include "sp_score_dev.hpp"
+
+namespace sp_fused {
+
+constexpr int kTileKeys = 512;   // keys owned by one workgroup
+constexpr int kMaxRows = 64;     // padded query rows per kv head the kernel holds on chip
+constexpr int kSlots = 8;        // depth of the exchange ring
+constexpr int kMinWorkgroups = 64;
+
+struct FusedArgs {
+    const uint16_t *q;           // [Lyr][H][n_q][64]
+    int64_t k_stride_token, k_stride_head;
+    int64_t L;
+    uint64_t *part;              // [kSlots][rows_pad][n_wg]  (max, sum exp) partials, parity in bit 63
+    uint64_t *lse;               // [kSlots][rows_pad]        (-lse, phase + 1)
+    uint32_t *err;
+    const uint64_t *zeros;       // 128 zero bytes (source of padding query rows)
+    float *scores;
+    int32_t n_wg;
+    int32_t n_layers, n_q_heads, n_kv_heads, group, n_q;
+    int32_t n_nblk, n_gblk, rows_pad;
+    int32_t layer_agg;
+    float c, inv_c, out_scale;
+};
+
+size_t workspace_bytes(int rows_pad, int n_wg);
+
+// Enqueues the clear kernel and the cooperative fused kernel. `ws` must hold workspace_bytes().
+sp_status launch(FusedArgs a, const sp_dev::LayerPtrs &kp, void *ws, hipStream_t st);
+
+}  // namespace sp_fused

@@ -146,3 +146,37 @@ def test_score_mid_size_config():
         got = gpu_score(inp["q"][0], inp["k"], w.scale, mode)
         assert_scores_close(got, want)
         say(f"  mode {mode}: max rel err {np.max(np.abs(got - want) / want):.2e}")
+
+
+# Long single prompts of head_dim 64 take the single-launch kernel that keeps K on chip.
+FUSED_SHAPES = [
+    # name, Lyr, H, Hkv, d, n_q, L
+    ("fused_g4_nq16_tail", 2, 8, 2, 64, 16, 40000),       # 79 workgroups, 64-key tail
+    ("fused_g4_nq8", 2, 8, 2, 64, 8, 33000),
+    ("fused_g2_nq8_rows32", 3, 4, 2, 64, 8, 36001),
+    ("fused_g8_nq8_two_gblocks", 1, 16, 2, 64, 8, 34000),
+    ("fused_g3_nq5_padding", 2, 6, 2, 64, 5, 35000),
+    ("fused_single_phase_full_grid", 1, 4, 1, 64, 16, 131072),
+    ("fused_20_phases", 5, 8, 4, 64, 16, 40000),
+]
+
+
+@pytest.mark.parametrize("shape", FUSED_SHAPES, ids=[s[0] for s in FUSED_SHAPES])
+def test_fused_score_matches_oracle(shape):
+    import paper_2603_02631_amd as sp
+    from gpu_util import assert_scores_close, gpu_score, make_desc
+    name, Lyr, H, Hkv, d, n_q, L = shape
+    say(f"[score-fused] {name} Lyr={Lyr} H={H} Hkv={Hkv} d={d} n_q={n_q} L={L}")
+    w = small_workload(name, Lyr, H, Hkv, d, n_q, L, cfg_id=200 + FUSED_SHAPES.index(shape), hh=(1, 1000))
+    assert sp.sp_score_is_fused(make_desc(Lyr, H, Hkv, d, n_q, w.scale, 0, "HND", L), L) == 1
+    inp = synth.make_score_inputs(w)
+    for mode in (0, 1):
+        want = oracle.score(inp["q"][0], inp["k"], w.scale, mode)
+        got = gpu_score(inp["q"][0], inp["k"], w.scale, mode)
+        assert_scores_close(got, want)
+        say(f"  mode {mode}: max rel err {np.max(np.abs(got - want) / want):.2e}")
+    again = gpu_score(inp["q"][0], inp["k"], w.scale, 1)
+    assert again.tobytes() == got.tobytes()          # deterministic
+    nhd = [np.ascontiguousarray(k.transpose(1, 0, 2)) for k in inp["k"]]
+    got_nhd = gpu_score(inp["q"][0], nhd, w.scale, 1, layout="NHD")
+    assert got_nhd.tobytes() == got.tobytes()        # same keys through token-major strides
