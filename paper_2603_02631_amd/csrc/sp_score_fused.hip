@@ -242,6 +242,16 @@ struct Pending {
     uint64_t duty[4];         // wave 1: partials of the duty row
 };
 
+// A partial is ready when it carries the parity of this use of its slot and a non-zero sum.
+__device__ __forceinline__ bool duty_ready(const Pending &pend, uint32_t par)
+{
+    bool ok = true;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        ok = ok && ((uint32_t)(pend.duty[q] >> 63) == par) && ((pend.duty[q] >> 32) & 0x7fffffffu) != 0;
+    return ok;
+}
+
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 // Row of phase p that workgroup w combines (>= rows_pad: none). Rows rotate over the workgroups.
@@ -274,16 +284,14 @@ __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &k
         if (duty_row < a.rows_pad && row_valid(a, duty_row, g, n)) {
             const uint32_t par = (uint32_t)(pd / kSlots) & 1u;
             const uint64_t *src = a.part + ((size_t)(pd % kSlots) * a.rows_pad + duty_row) * a.n_wg;
-            unsigned spins = 0;
-            for (;;) {
-                bool ok = true;
+            // fast path: the partials requested last iteration are all there; otherwise poll (bounded)
+            if (__any(!duty_ready(pend, par))) {
+                unsigned spins = 0;
+                do {
+                    if (++spins > kSpinMax) { *s_fail = 1; break; }
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    ok = ok && ((uint32_t)(pend.duty[q] >> 63) == par) && ((pend.duty[q] >> 32) & 0x7fffffffu) != 0;
-                if (!__any(!ok)) break;
-                if (++spins > kSpinMax) { *s_fail = 1; break; }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) pend.duty[q] = ld64(src + min(lane + 64 * q, a.n_wg - 1));
+                    for (int q = 0; q < 4; ++q) pend.duty[q] = ld64(src + min(lane + 64 * q, a.n_wg - 1));
+                } while (__any(!duty_ready(pend, par)));
             }
             float m = neg_inf(), l = 0.f;
 #pragma unroll
@@ -309,10 +317,12 @@ __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &k
         float v = neg_inf();
         if (row_valid(a, lane, g, n)) {
             const uint64_t *src = a.lse + (size_t)(pc % kSlots) * a.rows_pad + lane;
-            unsigned spins = 0;
-            while ((uint32_t)(pend.lse_entry >> 32) != (uint32_t)(pc + 1)) {
-                if (++spins > kSpinMax) { *s_fail = 1; break; }
-                pend.lse_entry = ld64(src);
+            if ((uint32_t)(pend.lse_entry >> 32) != (uint32_t)(pc + 1)) {
+                unsigned spins = 0;
+                do {
+                    if (++spins > kSpinMax) { *s_fail = 1; break; }
+                    pend.lse_entry = ld64(src);
+                } while ((uint32_t)(pend.lse_entry >> 32) != (uint32_t)(pc + 1));
             }
             v = __uint_as_float((uint32_t)pend.lse_entry);
         }
