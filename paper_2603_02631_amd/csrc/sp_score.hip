@@ -430,6 +430,7 @@ int device_compute_units()
     if (dev != cached_dev) {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+        if (cus > 0 && !sp_fused::fits_one_per_cu()) cus = 0;
         cached_dev = dev;
         cached_cus = cus;
     }

@@ -26,8 +26,8 @@
 // every exchanged word is written and read with device-scope relaxed atomics,
 // readiness travels inside the data (the sign bit of the always-positive sum
 // carries the parity of the slot's use; normalisers carry the phase number),
-// and all waits are bounded. The launch is cooperative so that every workgroup
-// is resident.
+// and all waits are bounded. The grid never exceeds the number of compute units
+// (one workgroup fits per unit), so every workgroup is resident on an idle device.
 #include "sp_score_fused.hpp"
 
 #include <cstring>
@@ -47,7 +47,7 @@ constexpr int kFTile = sp_fused::kTileKeys;   // 512 keys per workgroup per phas
 constexpr int kLag = 3;                   // phases between statistics and probability pass
 constexpr int kSlots = sp_fused::kSlots;  // exchange ring depth
 constexpr int kMaxRowsF = sp_fused::kMaxRows;   // 64 padded query rows per kv head
-constexpr unsigned kSpinMax = 1u << 22;
+constexpr unsigned kSpinMax = 1u << 20;    // polls before a wait gives up (about a second)
 
 #define SP_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define SP_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -285,7 +285,7 @@ __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &k
             const uint32_t par = (uint32_t)(pd / kSlots) & 1u;
             const uint64_t *src = a.part + ((size_t)(pd % kSlots) * a.rows_pad + duty_row) * a.n_wg;
             // fast path: the partials requested last iteration are all there; otherwise poll (bounded)
-            if (__any(!duty_ready(pend, par))) {
+            if (__any(!duty_ready(pend, par)) && *s_fail == 0) {
                 unsigned spins = 0;
                 do {
                     if (++spins > kSpinMax) { *s_fail = 1; break; }
@@ -317,7 +317,7 @@ __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &k
         float v = neg_inf();
         if (row_valid(a, lane, g, n)) {
             const uint64_t *src = a.lse + (size_t)(pc % kSlots) * a.rows_pad + lane;
-            if ((uint32_t)(pend.lse_entry >> 32) != (uint32_t)(pc + 1)) {
+            if ((uint32_t)(pend.lse_entry >> 32) != (uint32_t)(pc + 1) && *s_fail == 0) {
                 unsigned spins = 0;
                 do {
                     if (++spins > kSpinMax) { *s_fail = 1; break; }
@@ -470,6 +470,14 @@ size_t workspace_bytes(int rows_pad, int n_wg)
     return sp::align_up(sizeof(uint64_t) * ((size_t)kSlots * rows_pad * n_wg + (size_t)kSlots * rows_pad + 32), 256);
 }
 
+bool fits_one_per_cu()
+{
+    int n1 = 0, n2 = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, sp_fused_kernel<1>, kFThreads, 0) != hipSuccess) return false;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, sp_fused_kernel<2>, kFThreads, 0) != hipSuccess) return false;
+    return n1 >= 1 && n2 >= 1;
+}
+
 sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, hipStream_t st)
 {
     uint64_t *base = static_cast<uint64_t *>(ws);
@@ -482,11 +490,15 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, hipStream_t st)
     hipLaunchKernelGGL(sp_fused_clear_kernel, dim3((unsigned)((n_clear + 255) / 256 > 1024 ? 1024 : (n_clear + 255) / 256)),
                        dim3(256), 0, st, base, n_clear);
     SP_HIP_CHECK(hipGetLastError());
-    LayerPtrs kpc = kp;
-    void *params[] = {&a, &kpc};
-    const void *fn = (a.n_nblk == 1) ? reinterpret_cast<const void *>(&sp_fused_kernel<1>)
-                                     : reinterpret_cast<const void *>(&sp_fused_kernel<2>);
-    SP_HIP_CHECK(hipLaunchCooperativeKernel(fn, dim3(a.n_wg), dim3(kFThreads), params, 0, st));
+    // Every workgroup must be resident for the exchange to make progress: one workgroup fits per
+    // compute unit (LDS), so the grid may not exceed the number of compute units. All waits in the
+    // kernel are bounded; should residency fail (the device shared with other work), the call ends
+    // with NaN scores and the error word set instead of hanging.
+    if (a.n_nblk == 1)
+        hipLaunchKernelGGL(sp_fused_kernel<1>, dim3(a.n_wg), dim3(kFThreads), 0, st, a, kp);
+    else
+        hipLaunchKernelGGL(sp_fused_kernel<2>, dim3(a.n_wg), dim3(kFThreads), 0, st, a, kp);
+    SP_HIP_CHECK(hipGetLastError());
     return SP_OK;
 }
 

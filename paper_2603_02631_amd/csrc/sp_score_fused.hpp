@@ -29,7 +29,10 @@ struct FusedArgs {
 
 size_t workspace_bytes(int rows_pad, int n_wg);
 
-// Enqueues the clear kernel and the cooperative fused kernel. `ws` must hold workspace_bytes().
+// True when the device can hold one workgroup of the fused kernel per compute unit.
+bool fits_one_per_cu();
+
+// Enqueues the clear kernel and the fused kernel. `ws` must hold workspace_bytes().
 sp_status launch(FusedArgs a, const sp_dev::LayerPtrs &kp, void *ws, hipStream_t st);
 
 }  // namespace sp_fused
