@@ -16,6 +16,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # device code never produces NaNs on purpose: lets fmaxf chains become v_max3_f32 without
+    # canonicalising moves (host-side argument checks keep full NaN semantics)
+    "-Xarch_device", "-fno-honor-nans",
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -10,8 +10,13 @@
 //    keys for the whole call; a "phase" is one (layer, kv head) pair, and the
 //    workgroup's share of a phase is a 512 x 64 bf16 tile (64 KB);
 //  * tiles stream HBM -> LDS with direct-to-LDS loads, two phases ahead, into
-//    two transit buffers; each wave lifts its 64 keys into MFMA fragments held
-//    in registers (a ring of three phases);
+//    two transit buffers. K is wave-private: each wave loads, and later lifts
+//    into MFMA fragments, its own 64 keys, so the K path needs no barrier. The
+//    fragments of four phases live in registers (a ring of 4 x 32 VGPRs);
+//  * a vector-memory instruction blocks its wave while the compute unit's memory
+//    pipe is full, and the pipe drains at the unit's share of HBM bandwidth, so
+//    the eight tile loads of an iteration are issued one by one between the
+//    MFMA steps: while one wave waits for a slot the other waves compute;
 //  * phase p: the statistics pass computes the partial (max, sum exp) of every
 //    query row over the workgroup's keys and publishes it to global memory;
 //  * one wave of some workgroup (rotating "duty") combines the partials of one
@@ -44,10 +49,13 @@ constexpr int kFWaves = 8;
 constexpr int kFThreads = kFWaves * 64;
 constexpr int kNS = 2;                    // 32-key sub-tiles per wave
 constexpr int kFTile = sp_fused::kTileKeys;   // 512 keys per workgroup per phase
+constexpr int kTileInstr = kFTile / 64;   // tile-load instructions per wave per tile (8 rows each)
 constexpr int kLag = 3;                   // phases between statistics and probability pass
+constexpr int kRing = kLag + 1;           // fragment ring: phases it-3 .. it
 constexpr int kSlots = sp_fused::kSlots;  // exchange ring depth
 constexpr int kMaxRowsF = sp_fused::kMaxRows;   // 64 padded query rows per kv head
 constexpr unsigned kSpinMax = 1u << 20;    // polls before a wait gives up (about a second)
+constexpr int kExchangeWave = 0;           // the wave that talks to the exchange area
 
 #define SP_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define SP_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -79,47 +87,127 @@ __device__ __forceinline__ void vm_wait()
     __asm__ volatile("" ::: "memory");
 }
 
+// max(a, b, c); built without NaN honouring the compiler emits a single v_max3_f32 for it
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
 struct Ring {
-    bf16x8 kf[kLag][kNS][kKS];            // K fragments of the three phases in flight
+    bf16x8 kf[kRing][kNS][kKS];           // K fragments of the phases in flight
 };
+
+// LDS reads of tiles filled by direct-to-LDS loads are written as asm blocks: the compiler cannot
+// tell which in-flight load targets which buffer and would put a full vector-memory wait in front
+// of every such read. The kernel waits (vm_wait + barrier) for exactly what it is about to read.
+//
+// Lifts this wave's 64 keys (two 32-key sub-tiles, four k-steps each) from a transit buffer.
+__device__ __forceinline__ void lift_k_tile(const u32x4 *tile, int row0, int hf, bf16x8 (&f)[kNS][kKS])
+{
+    static_assert(kNS == 2 && kKS == 4, "layout of the asm block");
+    const uint32_t base = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(tile));
+    uint32_t ad[kKS];
+#pragma unroll
+    for (int t = 0; t < kKS; ++t) ad[t] = base + 16u * (uint32_t)lds_slot<kD>(row0, 2 * t + hf);
+    u32x4 r[kNS][kKS];
+    // sub-tile 1 starts 32 rows = 4096 bytes later; (row >> 1) & 7 and hence the swizzle are the same
+    __asm__ volatile(
+        "ds_read_b128 %0, %8\n\t"
+        "ds_read_b128 %1, %9\n\t"
+        "ds_read_b128 %2, %10\n\t"
+        "ds_read_b128 %3, %11\n\t"
+        "ds_read_b128 %4, %8 offset:4096\n\t"
+        "ds_read_b128 %5, %9 offset:4096\n\t"
+        "ds_read_b128 %6, %10 offset:4096\n\t"
+        "ds_read_b128 %7, %11 offset:4096\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(r[0][0]), "=&v"(r[0][1]), "=&v"(r[0][2]), "=&v"(r[0][3]),
+          "=&v"(r[1][0]), "=&v"(r[1][1]), "=&v"(r[1][2]), "=&v"(r[1][3])
+        : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3])
+        : "memory");
+#pragma unroll
+    for (int s = 0; s < kNS; ++s)
+#pragma unroll
+        for (int t = 0; t < kKS; ++t) f[s][t] = __builtin_bit_cast(bf16x8, r[s][t]);
+}
+
+// Fragments of one 32-row block of a Q tile.
+__device__ __forceinline__ void lift_q_block(const u32x4 *tile, int row, int hf, bf16x8 (&f)[kKS])
+{
+    static_assert(kKS == 4, "layout of the asm block");
+    const uint32_t base = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(tile));
+    uint32_t ad[kKS];
+#pragma unroll
+    for (int t = 0; t < kKS; ++t) ad[t] = base + 16u * (uint32_t)lds_slot<kD>(row, 2 * t + hf);
+    u32x4 r[kKS];
+    __asm__ volatile(
+        "ds_read_b128 %0, %4\n\t"
+        "ds_read_b128 %1, %5\n\t"
+        "ds_read_b128 %2, %6\n\t"
+        "ds_read_b128 %3, %7\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
+        : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3])
+        : "memory");
+#pragma unroll
+    for (int t = 0; t < kKS; ++t) f[t] = __builtin_bit_cast(bf16x8, r[t]);
+}
+
+// A plain LDS store, opaque to the compiler for the same reason (ordered by the next barrier).
+__device__ __forceinline__ void lds_store_f32(float *p, float v)
+{
+    const uint32_t ad = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(p));
+    __asm__ volatile("ds_write_b32 %0, %1" : : "v"(ad), "v"(v) : "memory");
+}
 
 struct PhaseId { int layer, kv; };
 __device__ __forceinline__ PhaseId phase_of(int p, int n_kv) { PhaseId r; r.layer = p / n_kv; r.kv = p - r.layer * n_kv; return r; }
 
 // padded query row -> (group head, lookahead row); see the row order in sp_score.hip
+template <int NB>
 __device__ __forceinline__ bool row_valid(const FusedArgs &a, int row, int &g, int &n)
 {
     const int blk = row >> 5, rho = row & 31;
-    const int gblk = blk / a.n_nblk, nblk = blk - gblk * a.n_nblk;
+    const int gblk = blk / NB, nblk = blk - gblk * NB;
     g = 4 * gblk + (rho >> 3);
     n = 8 * nblk + (rho & 7);
     return g < a.group && n < a.n_q;
 }
 
-// One wave instruction moves 64 chunks (8 key rows) of the tile; wave w issues
-// instructions w, w+8, ... so the 8 waves cover the 512 rows.
-__device__ __forceinline__ void issue_k_tile(u32x4 *kt, const uint16_t *slab, int64_t stride_token, int64_t j0,
-                                             int n_valid, int wave, int lane)
+// One wave instruction moves 64 chunks = 8 key rows (1 KB, contiguous in HBM when keys are
+// contiguous); a wave's 64 rows take eight of them. The address is a uniform base plus a 32-bit
+// per-lane byte offset, so no address registers stay live between instructions.
+struct KIssue {
+    u32x4 *tile;              // transit buffer being refilled
+    const uint16_t *base;     // first key of this workgroup in the (layer, kv head) being fetched (uniform)
+    uint32_t stride_bytes;    // bytes between consecutive keys
+    int n_valid, wave, lane;
+};
+
+// Issues instructions first .. first+COUNT-1 of the tile (first and COUNT compile-time at call sites).
+template <int COUNT>
+__device__ __forceinline__ void k_issue(const KIssue &ki, int first)
 {
-    const int base_row = wave * 8 + (lane >> 3);
-    const int chunk = (lane & 7) ^ ((base_row >> 1) & 7);     // (row >> 1) & 7 is the same for row + 64*i
 #pragma unroll
-    for (int i = 0; i < kFTile / 64; ++i) {
-        int row = base_row + 64 * i;
-        row = row < n_valid ? row : n_valid - 1;              // tail rows repeat the last valid key
-        const uint16_t *src = slab + (j0 + row) * stride_token + chunk * 8;
-        __builtin_amdgcn_global_load_lds(SP_GPTR(src), SP_LPTR(kt + (i * 8 + wave) * 64), 16, 0, 0);
+    for (int i = 0; i < COUNT; ++i) {
+        const int idx = first + i;
+        int row = ki.wave * 64 + 8 * idx + (ki.lane >> 3);
+        const uint32_t chunk = (uint32_t)((ki.lane & 7) ^ ((row >> 1) & 7));
+        row = row < ki.n_valid ? row : ki.n_valid - 1;        // tail rows repeat the last valid key
+        const uint32_t off = (uint32_t)row * ki.stride_bytes + chunk * 16u;
+        const char *src = reinterpret_cast<const char *>(ki.base) + off;
+        __builtin_amdgcn_global_load_lds(SP_GPTR(src), SP_LPTR(ki.tile + (ki.wave * 64 + 8 * idx) * kCH), 16, 0, 0);
     }
 }
 
-// Q tile of one (layer, kv head) in the padded row order. Every wave always issues exactly one
-// instruction (8 rows); padding rows read a zero line kept in the workspace.
-__device__ __forceinline__ void issue_q_tile(u32x4 *qt, const FusedArgs &a, int layer, int kv, int wave, int lane)
+// Each wave loads eight rows (one instruction) of a Q tile of one (layer, kv head), in the padded
+// row order; padding rows read a zero line kept in the workspace.
+template <int NB>
+__device__ __forceinline__ void issue_q_slice(u32x4 *qt, const FusedArgs &a, int layer, int kv, int wave, int lane)
 {
     const int row = wave * 8 + (lane >> 3);
     int g, n;
     const uint16_t *src = reinterpret_cast<const uint16_t *>(a.zeros) + (lane & 7) * 8;
-    if (row < a.rows_pad && row_valid(a, row, g, n)) {
+    if (row < a.rows_pad && row_valid<NB>(a, row, g, n)) {
         const int chunk = (lane & 7) ^ ((row >> 1) & 7);
         src = a.q + ((((int64_t)layer * a.n_q_heads + (int64_t)kv * a.group + g) * a.n_q + n) * kD) + chunk * 8;
     }
@@ -132,17 +220,19 @@ struct Acc {
     float total[kNS];
 };
 
-// ---- probability pass of one phase from the fragment ring ----
-template <int NB>
-__device__ __forceinline__ void prob_pass(const FusedArgs &a, const bf16x8 (&kf)[kNS][kKS], const u32x4 *q2,
-                                          const float *cinit, Acc<NB> &acc, int hf, int col)
+// ---- probability pass of one phase from the fragment ring; tile loads are issued between the MFMA steps ----
+template <int NB, int GB>
+__device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const u32x4 *q2, const float *cinit,
+                                          Acc<NB> &acc, int hf, int col, const KIssue &ki, int first)
 {
+    constexpr int kPerStep = (kTileInstr / 2) / (NB * GB * kNS);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        for (int gb = 0; gb < a.n_gblk; ++gb) {
+#pragma unroll
+        for (int gb = 0; gb < GB; ++gb) {
             const int blk = gb * NB + nb;
             bf16x8 qf[kKS];
-            load_frag<kD>(q2, blk * 32 + col, hf, qf);
+            lift_q_block(q2, blk * 32 + col, hf, qf);
             f32x16 ci;
             const float4 *cp = reinterpret_cast<const float4 *>(cinit + blk * 32 + hf * 16);
 #pragma unroll
@@ -155,11 +245,12 @@ __device__ __forceinline__ void prob_pass(const FusedArgs &a, const bf16x8 (&kf)
                 f32x16 d = ci;
 #pragma unroll
                 for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t], kf[s][t], d, 0, 0, 0);
+                // d[r]: group head r/4, lookahead row 8*nb + 4*hf + r%4, key (wave*2+s)*32 + col
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float v = fmaxf(fmaxf(d[e], d[4 + e]), fmaxf(d[8 + e], d[12 + e]));
-                    acc.mx[s][nb][e] = fmaxf(acc.mx[s][nb][e], v);
-                }
+                for (int e = 0; e < 4; ++e)
+                    acc.mx[s][nb][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[s][nb][e]);
+                k_issue<kPerStep>(ki, first + ((nb * GB + gb) * kNS + s) * kPerStep);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
@@ -183,14 +274,16 @@ __device__ __forceinline__ void close_layer(Acc<NB> &acc, float c)
 }
 
 // ---- statistics pass of one phase: per-wave (max, sum exp) of every row into wstats ----
-__device__ __forceinline__ void stats_pass(const FusedArgs &a, const bf16x8 (&kf)[kNS][kKS], const u32x4 *q1,
-                                           float2 *wstats_wave, int n_valid, int wave, int hf, int col)
+template <int NBLK>
+__device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS], const u32x4 *q1,
+                                           float2 *wstats_wave, int n_valid, int wave, int hf, int col,
+                                           const KIssue &ki)
 {
-    const float c = a.c;
-    const int n_blk = a.rows_pad >> 5;
-    for (int blk = 0; blk < n_blk; ++blk) {
+    constexpr int kPerStep = (kTileInstr / 2) / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) {
         bf16x8 qf[kKS];
-        load_frag<kD>(q1, blk * 32 + col, hf, qf);
+        lift_q_block(q1, blk * 32 + col, hf, qf);
         float m = neg_inf(), l = 0.f;
 #pragma unroll
         for (int s = 0; s < kNS; ++s) {
@@ -200,10 +293,9 @@ __device__ __forceinline__ void stats_pass(const FusedArgs &a, const bf16x8 (&kf
             // d[r]: key (wave*2+s)*32 + 8*(r/4) + 4*hf + r%4 of the tile, query row blk*32 + col
             const int left = n_valid - (wave * kNS + s) * 32;
             if (left >= 32) {
-                float tm = d[0];
+                float mn = max3(m, d[0], d[1]);      // running maximum including these 16 logits
 #pragma unroll
-                for (int r = 1; r < 16; ++r) tm = fmaxf(tm, d[r]);
-                const float mn = fmaxf(m, tm);
+                for (int r = 2; r < 16; r += 2) mn = max3(mn, d[r], d[r + 1]);
                 l *= fast_exp2((m - mn) * c);
                 m = mn;
                 const float mc = mn * c;
@@ -230,6 +322,8 @@ __device__ __forceinline__ void stats_pass(const FusedArgs &a, const bf16x8 (&kf
                     }
                 }
             }
+            k_issue<kPerStep>(ki, (blk * kNS + s) * kPerStep);
+            __builtin_amdgcn_sched_barrier(0);
         }
         const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
         lse_merge(m, l, m2, l2, c);
@@ -237,159 +331,233 @@ __device__ __forceinline__ void stats_pass(const FusedArgs &a, const bf16x8 (&kf
     }
 }
 
-struct Pending {
-    uint64_t lse_entry;       // wave 0: normaliser entry of the phase whose probability pass comes next
-    uint64_t duty[4];         // wave 1: partials of the duty row
-};
+// Exchange data requested with direct-to-LDS loads lands in two small staging areas private to
+// the exchange wave: xduty holds the n_wg partials of the duty row (entry e at byte 8e), xlse the
+// normaliser entries of one phase. Reading them back in asm keeps the compiler from waiting for
+// every vector-memory operation in flight.
+struct DutyEntries { uint64_t e[4]; };     // entries lane, lane + 64, lane + 128, lane + 192
 
-// A partial is ready when it carries the parity of this use of its slot and a non-zero sum.
-__device__ __forceinline__ bool duty_ready(const Pending &pend, uint32_t par)
+__device__ __forceinline__ DutyEntries read_duty_staging(const u32x4 *xduty, int lane)
 {
-    bool ok = true;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        ok = ok && ((uint32_t)(pend.duty[q] >> 63) == par) && ((pend.duty[q] >> 32) & 0x7fffffffu) != 0;
-    return ok;
+    const uint32_t ad = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(xduty)) + 8u * (uint32_t)lane;
+    DutyEntries d;
+    __asm__ volatile(
+        "ds_read_b64 %0, %4\n\t"
+        "ds_read_b64 %1, %4 offset:512\n\t"
+        "ds_read_b64 %2, %4 offset:1024\n\t"
+        "ds_read_b64 %3, %4 offset:1536\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(d.e[0]), "=&v"(d.e[1]), "=&v"(d.e[2]), "=&v"(d.e[3])
+        : "v"(ad)
+        : "memory");
+    return d;
 }
 
-__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+__device__ __forceinline__ uint64_t read_lse_staging(const u32x4 *xlse, int lane)
+{
+    const uint32_t ad = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(xlse)) + 8u * (uint32_t)lane;
+    uint64_t v;
+    __asm__ volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(ad) : "memory");
+    return v;
+}
+
+// Direct-to-LDS load of 64 x 16 bytes: the 16-byte pairs first .. first+63 of a row of 8-byte
+// entries (row 16-byte aligned) that holds `pairs` pairs; lanes beyond the row repeat its last pair.
+// The load bypasses the non-coherent cache levels like the atomic loads of the retry paths do.
+__device__ __forceinline__ void stage_entries(u32x4 *dst, const uint64_t *row, int first, int pairs, int lane)
+{
+    constexpr int kDeviceScope = 16;      // the sc1 bit of the cache-policy operand
+    const uint64_t *p = row + 2 * min(first + lane, pairs - 1);
+    __builtin_amdgcn_global_load_lds(SP_GPTR(p), SP_LPTR(dst), 16, 0, kDeviceScope);
+}
+
+// A partial is ready when it carries the parity of this use of its slot and a non-zero sum.
+// Entries beyond the last workgroup do not exist and count as ready.
+__device__ __forceinline__ bool duty_ready(const DutyEntries &d, uint32_t par, int lane, int n_wg)
+{
+    uint32_t ok = 1u;           // branch-free: one straight-line test of the four entries
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        ok &= (uint32_t)(lane + 64 * q >= n_wg) |
+              ((uint32_t)((uint32_t)(d.e[q] >> 63) == par) & (uint32_t)(((d.e[q] >> 32) & 0x7fffffffu) != 0));
+    return ok != 0;
+}
 
 // Row of phase p that workgroup w combines (>= rows_pad: none). Rows rotate over the workgroups.
 __device__ __forceinline__ int duty_row_of(const FusedArgs &a, int p, int w)
 {
-    const int first = (int)(((int64_t)p * a.rows_pad) % a.n_wg);
-    int r = w - first;
+    const int first = (int)(((uint32_t)p * (uint32_t)a.rows_pad) % (uint32_t)a.n_wg);
+    const int r = w - first;
     return r < 0 ? r + a.n_wg : r;
 }
 
-// One iteration of the software pipeline. Every wave issues the same vector-memory instructions in
-// the same order in every iteration (exchange loads of waves 0/1 aside), the eight K-tile loads last,
-// so "at most eight outstanding" always means "everything but the newest K tile has landed".
-template <int NB, int SLOT, int BUF>
+// One iteration `it` of the software pipeline. Per wave, in program order:
+//   top     wait for everything but the four newest loads; exchange wave: combine the duty row of
+//           phase it-2 and publish its normaliser, put the normalisers of phase it-3 into LDS
+//   B1
+//   lift    this wave's slice of Q(it-2) for the next iteration's probability pass; this wave's keys
+//           of K(it) from transit buffer it%2 into ring slot it%4
+//   stats   statistics pass of phase it; first four loads of K(it+2) into the buffer just emptied
+//   B2
+//   mid     exchange wave: publish this workgroup's partials of phase it, request the partials of
+//           phase it-1 (duty) and the normalisers of phase it-2; every wave: its slice of Q(it+1)
+//   prob    probability pass of phase it-3; last four loads of K(it+2)
+// The four newest vector-memory operations of a wave are therefore always K-tile loads whose data
+// is not needed before the iteration after next; everything older has landed after vm_wait<4>.
+template <int NB, int GB, int SLOT, int BUF>
 __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &kp, int it, int n_phases, Ring &ring,
-                                          Acc<NB> &acc, Pending &pend, u32x4 *kt0, u32x4 *kt1, u32x4 *q1, u32x4 *q2,
-                                          float2 (*wstats)[kMaxRowsF], float *cinit, int *s_fail, int n_valid)
+                                          Acc<NB> &acc, u32x4 *xduty, u32x4 *xlse, u32x4 *kt0, u32x4 *kt1, u32x4 *q1, u32x4 *q2a,
+                                          u32x4 *q2b, float2 (*wstats)[kMaxRowsF], float (*cinit2)[kMaxRowsF],
+                                          int *s_fail, int n_valid)
 {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hf = lane >> 5, col = lane & 31;
+    // Lane-derived LDS and global offsets are recomputed every iteration instead of being kept in
+    // registers across the whole loop (the opaque copy stops the compiler from hoisting them).
+    int tid = threadIdx.x;
+    __asm__ volatile("" : "+v"(tid));
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, hf = lane >> 5, col = lane & 31;
     const int w = blockIdx.x;
     u32x4 *kt = BUF ? kt1 : kt0;
-    const int pc = it - kLag;             // phase whose probability pass runs now
+    u32x4 *q2 = BUF ? q2b : q2a;          // Q of phase it-3; the other buffer receives Q of phase it-2
+    u32x4 *q2_next = BUF ? q2a : q2b;
+    float *cinit = cinit2[BUF];           // double-buffered: waves may still read the other one
+    const int pc = it - kLag;             // phase whose probability pass runs in this iteration
     const int pd = it - 2;                // phase whose duty loads were issued last iteration
+    const bool do_prob = pc >= 0 && pc < n_phases, do_stats = it < n_phases;
 
-    // ---- S1: take in what was requested last iteration ----
-    vm_wait<kFTile / 64>();
-    if (wave == 1 && pd >= 0 && pd < n_phases) {
-        const int duty_row = duty_row_of(a, pd, w);
-        int g, n;
-        if (duty_row < a.rows_pad && row_valid(a, duty_row, g, n)) {
-            const uint32_t par = (uint32_t)(pd / kSlots) & 1u;
-            const uint64_t *src = a.part + ((size_t)(pd % kSlots) * a.rows_pad + duty_row) * a.n_wg;
-            // fast path: the partials requested last iteration are all there; otherwise poll (bounded)
-            if (__any(!duty_ready(pend, par)) && *s_fail == 0) {
-                unsigned spins = 0;
-                do {
-                    if (++spins > kSpinMax) { *s_fail = 1; break; }
+    // ---- top ----
+    vm_wait<kTileInstr / 2>();
+    if (wave == kExchangeWave) {
+        if (pd >= 0 && pd < n_phases) {
+            const int duty_row = duty_row_of(a, pd, w);
+            int g, n;
+            if (duty_row < a.rows_pad && row_valid<NB>(a, duty_row, g, n)) {
+                const uint32_t par = (uint32_t)(pd / kSlots) & 1u;
+                const uint64_t *src = a.part + ((size_t)(pd % kSlots) * a.rows_pad + duty_row) * a.part_stride;
+                // fast path: the partials requested last iteration are all there; otherwise poll (bounded)
+                DutyEntries de = read_duty_staging(xduty, lane);
+                if (__any(!duty_ready(de, par, lane, a.n_wg)) && *s_fail == 0) {
+                    unsigned spins = 0;
+                    do {
+                        if (++spins > kSpinMax) { *s_fail = 1; break; }
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) pend.duty[q] = ld64(src + min(lane + 64 * q, a.n_wg - 1));
-                } while (__any(!duty_ready(pend, par)));
-            }
-            float m = neg_inf(), l = 0.f;
+                        for (int q = 0; q < 4; ++q) de.e[q] = ld64(src + min(lane + 64 * q, a.n_wg - 1));
+                    } while (__any(!duty_ready(de, par, lane, a.n_wg)));
+                }
+                float m = neg_inf(), l = 0.f;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float pm = __uint_as_float((uint32_t)pend.duty[q]);
-                const float pl = __uint_as_float((uint32_t)(pend.duty[q] >> 32) & 0x7fffffffu);
-                if (lane + 64 * q < a.n_wg) lse_merge(m, l, pm, pl, a.c);
-            }
+                for (int q = 0; q < 4; ++q) {
+                    const float pm = __uint_as_float((uint32_t)de.e[q]);
+                    const float pl = __uint_as_float((uint32_t)(de.e[q] >> 32) & 0x7fffffffu);
+                    if (lane + 64 * q < a.n_wg) lse_merge(m, l, pm, pl, a.c);
+                }
 #pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const float m2 = __shfl_xor(m, off), l2 = __shfl_xor(l, off);
-                lse_merge(m, l, m2, l2, a.c);
-            }
-            if (lane == 0) {
-                const float v = -(m + fast_log2(l) * a.inv_c);
-                st64(a.lse + (size_t)(pd % kSlots) * a.rows_pad + duty_row,
-                     (uint64_t)__float_as_uint(v) | ((uint64_t)(uint32_t)(pd + 1) << 32));
+                for (int off = 1; off < 64; off <<= 1) {
+                    const float m2 = __shfl_xor(m, off), l2 = __shfl_xor(l, off);
+                    lse_merge(m, l, m2, l2, a.c);
+                }
+                if (lane == 0) {
+                    const float v = -(m + fast_log2(l) * a.inv_c);
+                    st64(a.lse + (size_t)(pd % kSlots) * a.rows_pad + duty_row,
+                         (uint64_t)__float_as_uint(v) | ((uint64_t)(uint32_t)(pd + 1) << 32));
+                }
             }
         }
-    }
-    if (wave == 0 && pc >= 0 && pc < n_phases && lane < a.rows_pad) {
-        int g, n;
-        float v = neg_inf();
-        if (row_valid(a, lane, g, n)) {
-            const uint64_t *src = a.lse + (size_t)(pc % kSlots) * a.rows_pad + lane;
-            if ((uint32_t)(pend.lse_entry >> 32) != (uint32_t)(pc + 1) && *s_fail == 0) {
-                unsigned spins = 0;
-                do {
-                    if (++spins > kSpinMax) { *s_fail = 1; break; }
-                    pend.lse_entry = ld64(src);
-                } while ((uint32_t)(pend.lse_entry >> 32) != (uint32_t)(pc + 1));
+        if (do_prob && lane < a.rows_pad) {
+            int g, n;
+            float v = neg_inf();
+            if (row_valid<NB>(a, lane, g, n)) {
+                const uint64_t *src = a.lse + (size_t)(pc % kSlots) * a.rows_pad + lane;
+                uint64_t entry = read_lse_staging(xlse, lane);
+                if ((uint32_t)(entry >> 32) != (uint32_t)(pc + 1) && *s_fail == 0) {
+                    unsigned spins = 0;
+                    do {
+                        if (++spins > kSpinMax) { *s_fail = 1; break; }
+                        entry = ld64(src);
+                    } while ((uint32_t)(entry >> 32) != (uint32_t)(pc + 1));
+                }
+                v = __uint_as_float((uint32_t)entry);
             }
-            v = __uint_as_float((uint32_t)pend.lse_entry);
-        }
-        const int rho = lane & 31;
-        cinit[(lane & ~31) + ((rho >> 2) & 1) * 16 + 4 * (rho >> 3) + (rho & 3)] = v;
-    }
-    lds_barrier();                                                            // B1
-
-    // ---- S2: probability pass of phase pc ----
-    if (pc >= 0 && pc < n_phases) {
-        prob_pass<NB>(a, ring.kf[SLOT], q2, cinit, acc, hf, col);
-        const PhaseId idc = phase_of(pc, a.n_kv_heads);
-        if (idc.kv == a.n_kv_heads - 1 && (a.layer_agg == SP_LAYER_MEAN || idc.layer == a.n_layers - 1))
-            close_layer<NB>(acc, a.c);
-    }
-    // ---- S3 + S4: lift K(it) into the ring slot just freed, statistics pass ----
-    if (it < n_phases) {
-#pragma unroll
-        for (int s = 0; s < kNS; ++s) load_frag<kD>(kt, (wave * kNS + s) * 32 + col, hf, ring.kf[SLOT][s]);
-        stats_pass(a, ring.kf[SLOT], q1, wstats[wave], n_valid, wave, hf, col);
-    }
-    lds_barrier();                                                            // B2
-
-    // ---- S5: publish, then request what the next iteration needs ----
-    if (it < n_phases && tid < a.rows_pad) {
-        int g, n;
-        if (row_valid(a, tid, g, n)) {
-            float m = wstats[0][tid].x, l = wstats[0][tid].y;
-#pragma unroll
-            for (int ww = 1; ww < kFWaves; ++ww) lse_merge(m, l, wstats[ww][tid].x, wstats[ww][tid].y, a.c);
-            const uint64_t bits = (uint64_t)__float_as_uint(m) | ((uint64_t)__float_as_uint(l) << 32) |
-                                  ((uint64_t)((it / kSlots) & 1) << 63);
-            st64(a.part + ((size_t)(it % kSlots) * a.rows_pad + tid) * a.n_wg + w, bits);
+            const int rho = lane & 31;
+            lds_store_f32(cinit + (lane & ~31) + ((rho >> 2) & 1) * 16 + 4 * (rho >> 3) + (rho & 3), v);
         }
     }
-    if (wave == 1) {           // partials of the row this workgroup combines next iteration (phase it - 1)
-        const int pn = clampi(it - 1, 0, n_phases - 1);
-        const int r = min(duty_row_of(a, pn, w), a.rows_pad - 1);
-        const uint64_t *src = a.part + ((size_t)(pn % kSlots) * a.rows_pad + r) * a.n_wg;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) pend.duty[q] = ld64(src + min(lane + 64 * q, a.n_wg - 1));
+    lds_barrier();                                                            // B1: K(it), Q tiles, cinit ready
+
+    // ---- Q of the next probability pass, lift, statistics pass; first half of the loads of K(it+2) ----
+    {
+        const PhaseId id2 = phase_of(clampi(pc + 1, 0, n_phases - 1), a.n_kv_heads);
+        issue_q_slice<NB>(q2_next, a, id2.layer, id2.kv, wave, lane);
     }
-    if (wave == 0) {           // normalisers of the phase whose probability pass runs next iteration
-        const int pn = clampi(pc + 1, 0, n_phases - 1);
-        pend.lse_entry = ld64(a.lse + (size_t)(pn % kSlots) * a.rows_pad + min(lane, a.rows_pad - 1));
+    KIssue ki;
+    {
+        const PhaseId id3 = phase_of(min(it + 2, n_phases - 1), a.n_kv_heads);
+        ki.tile = kt;
+        ki.base = kp.p[id3.layer] + (int64_t)id3.kv * a.k_stride_head + (int64_t)w * kFTile * a.k_stride_token;
+        ki.stride_bytes = (uint32_t)a.k_stride_token * 2u;
+        ki.n_valid = (it + 2 < n_phases) ? n_valid : 1;     // past the last phase: a one-row dummy keeps the count fixed
+        ki.wave = wave; ki.lane = lane;
+    }
+    if (do_stats) {
+        lift_k_tile(kt, wave * kNS * 32 + col, hf, ring.kf[SLOT]);
+        stats_pass<NB * GB>(a.c, ring.kf[SLOT], q1, wstats[wave], n_valid, wave, hf, col, ki);
+    } else {
+        k_issue<kTileInstr / 2>(ki, 0);
+    }
+    lds_barrier();                                                            // B2: wstats complete, q1 free
+
+    // ---- mid: exchange traffic and Q of the next statistics pass, ahead of the remaining K loads ----
+    if (wave == kExchangeWave) {
+        if (do_stats && lane < a.rows_pad) {
+            int g, n;
+            if (row_valid<NB>(a, lane, g, n)) {
+                float m = wstats[0][lane].x, l = wstats[0][lane].y;
+#pragma unroll
+                for (int ww = 1; ww < kFWaves; ++ww) lse_merge(m, l, wstats[ww][lane].x, wstats[ww][lane].y, a.c);
+                const uint64_t bits = (uint64_t)__float_as_uint(m) | ((uint64_t)__float_as_uint(l) << 32) |
+                                      ((uint64_t)((it / kSlots) & 1) << 63);
+                st64(a.part + ((size_t)(it % kSlots) * a.rows_pad + lane) * a.part_stride + w, bits);
+            }
+        }
+        {   // partials of the row this workgroup combines at the next top (phase it - 1)
+            const int pn = clampi(it - 1, 0, n_phases - 1);
+            const int r = min(duty_row_of(a, pn, w), a.rows_pad - 1);
+            const uint64_t *src = a.part + ((size_t)(pn % kSlots) * a.rows_pad + r) * a.part_stride;
+            stage_entries(xduty, src, 0, a.part_stride / 2, lane);
+            stage_entries(xduty + 64, src, 64, a.part_stride / 2, lane);
+        }
+        {   // normalisers of the phase whose probability pass runs next iteration
+            const int pn = clampi(pc + 1, 0, n_phases - 1);
+            stage_entries(xlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, 0, a.rows_pad / 2, lane);
+        }
     }
     {
         const PhaseId id1 = phase_of(min(it + 1, n_phases - 1), a.n_kv_heads);
-        issue_q_tile(q1, a, id1.layer, id1.kv, wave, lane);
-        const PhaseId id2 = phase_of(clampi(pc + 1, 0, n_phases - 1), a.n_kv_heads);
-        issue_q_tile(q2, a, id2.layer, id2.kv, wave, lane);
-        // K two phases ahead; past the last phase a one-row dummy keeps the instruction count fixed
-        const PhaseId id3 = phase_of(min(it + 2, n_phases - 1), a.n_kv_heads);
-        issue_k_tile(kt, kp.p[id3.layer] + (int64_t)id3.kv * a.k_stride_head, a.k_stride_token,
-                     (int64_t)w * kFTile, (it + 2 < n_phases) ? n_valid : 1, wave, lane);
+        issue_q_slice<NB>(q1, a, id1.layer, id1.kv, wave, lane);
+    }
+
+    // ---- probability pass of phase pc; second half of the loads of K(it+2) ----
+    if (do_prob) {
+        prob_pass<NB, GB>(ring.kf[(SLOT + 1) % kRing], q2, cinit, acc, hf, col, ki, kTileInstr / 2);
+        const PhaseId idc = phase_of(pc, a.n_kv_heads);
+        if (idc.kv == a.n_kv_heads - 1 && (a.layer_agg == SP_LAYER_MEAN || idc.layer == a.n_layers - 1))
+            close_layer<NB>(acc, a.c);
+    } else {
+        k_issue<kTileInstr / 2>(ki, kTileInstr / 2);
     }
 }
 
-template <int NB>
+template <int NB, int GB>
 __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, LayerPtrs kp)
 {
     __shared__ u32x4 kt0[kFTile * kCH];
     __shared__ u32x4 kt1[kFTile * kCH];
     __shared__ u32x4 q1[kMaxRowsF * kCH];
-    __shared__ u32x4 q2[kMaxRowsF * kCH];
+    __shared__ u32x4 q2a[kMaxRowsF * kCH];
+    __shared__ u32x4 q2b[kMaxRowsF * kCH];
     __shared__ float2 wstats[kFWaves][kMaxRowsF];
-    __shared__ float cinit[kMaxRowsF];
+    __shared__ float cinit2[2][kMaxRowsF];
+    __shared__ u32x4 xduty[128];             // partials of the duty row, 256 entries
+    __shared__ u32x4 xlse[64];               // normaliser entries of one phase (64 used, the load moves 128)
     __shared__ int s_fail;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hf = lane >> 5, col = lane & 31;
@@ -398,16 +566,12 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     const int64_t j0 = (int64_t)w * kFTile;
     const int n_valid = (int)((a.L - j0 < kFTile) ? a.L - j0 : kFTile);
 
-    if (tid < kMaxRowsF) cinit[tid] = neg_inf();
+    if (tid < 2 * kMaxRowsF) cinit2[tid / kMaxRowsF][tid % kMaxRowsF] = neg_inf();
     if (tid == 0) s_fail = 0;
     lds_barrier();
 
     Ring ring;
     Acc<NB> acc;
-    Pending pend;
-    pend.lse_entry = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) pend.duty[q] = 0;
 #pragma unroll
     for (int s = 0; s < kNS; ++s) {
         acc.total[s] = 0.f;
@@ -417,29 +581,31 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
             for (int e = 0; e < 4; ++e) acc.mx[s][b][e] = neg_inf();
     }
 
-    // prologue: Q(0), K(0), K(1)
-    issue_q_tile(q1, a, 0, 0, wave, lane);
-    issue_k_tile(kt0, kp.p[0], a.k_stride_token, j0, n_valid, wave, lane);
+    // prologue: this wave's slice of Q(0), then its rows of K(0) and K(1)
+    issue_q_slice<NB>(q1, a, 0, 0, wave, lane);
     {
+        KIssue ki;
+        ki.stride_bytes = (uint32_t)a.k_stride_token * 2u; ki.wave = wave; ki.lane = lane;
+        ki.tile = kt0; ki.base = kp.p[0] + j0 * a.k_stride_token; ki.n_valid = n_valid;
+        k_issue<kTileInstr>(ki, 0);
         const PhaseId id = phase_of(min(1, n_phases - 1), a.n_kv_heads);
-        issue_k_tile(kt1, kp.p[id.layer] + (int64_t)id.kv * a.k_stride_head, a.k_stride_token, j0,
-                     n_phases > 1 ? n_valid : 1, wave, lane);
+        ki.tile = kt1; ki.base = kp.p[id.layer] + (int64_t)id.kv * a.k_stride_head + j0 * a.k_stride_token;
+        ki.n_valid = n_phases > 1 ? n_valid : 1;
+        k_issue<kTileInstr>(ki, 0);
     }
 
-    // The body is unrolled six times so that the ring slot (it % 3) and the transit buffer (it % 2)
+    // The body is unrolled four times so that the ring slot (it % 4) and the transit buffer (it % 2)
     // are compile-time; the trip count is rounded up, surplus iterations do no work but keep the
     // instruction stream uniform.
-    const int n_iter = (n_phases + kLag + 5) / 6 * 6;
-    for (int it0 = 0; it0 < n_iter; it0 += 6) {
-#define SP_ITER(SLOT, BUF, OFF)                                                                           \
-        iteration<NB, SLOT, BUF>(a, kp, it0 + OFF, n_phases, ring, acc, pend, kt0, kt1, q1, q2, wstats,   \
-                                 cinit, &s_fail, n_valid);
+    const int n_iter = (n_phases + kLag + 3) / 4 * 4;
+    for (int it0 = 0; it0 < n_iter; it0 += 4) {
+#define SP_ITER(SLOT, BUF, OFF)                                                                               \
+        iteration<NB, GB, SLOT, BUF>(a, kp, it0 + OFF, n_phases, ring, acc, xduty, xlse, kt0, kt1, q1, q2a, q2b,     \
+                                     wstats, cinit2, &s_fail, n_valid);
         SP_ITER(0, 0, 0)
         SP_ITER(1, 1, 1)
         SP_ITER(2, 0, 2)
-        SP_ITER(0, 1, 3)
-        SP_ITER(1, 0, 4)
-        SP_ITER(2, 1, 5)
+        SP_ITER(3, 1, 3)
 #undef SP_ITER
     }
     vm_wait<0>();               // no direct-to-LDS load may outlive the workgroup
@@ -450,7 +616,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     for (int s = 0; s < kNS; ++s) {
         const float both = acc.total[s] + __shfl_xor(acc.total[s], 32);
         const int key = (wave * kNS + s) * 32 + col;
-        if (hf == 0 && key < n_valid) a.scores[j0 + key] = failed ? __builtin_nanf("") : both * a.out_scale;
+        if (hf == 0 && key < n_valid) a.scores[j0 + key] = failed ? __uint_as_float(0x7fc00000u) : both * a.out_scale;   // quiet NaN marks a failed call
     }
 }
 
@@ -465,23 +631,27 @@ __global__ void sp_fused_clear_kernel(uint64_t *p, size_t n)
 
 namespace sp_fused {
 
+// Rows of partials start on 16-byte boundaries.
+static int part_stride(int n_wg) { return (n_wg + 1) & ~1; }
+
 size_t workspace_bytes(int rows_pad, int n_wg)
 {
-    return sp::align_up(sizeof(uint64_t) * ((size_t)kSlots * rows_pad * n_wg + (size_t)kSlots * rows_pad + 32), 256);
+    return sp::align_up(sizeof(uint64_t) * ((size_t)kSlots * rows_pad * part_stride(n_wg) + (size_t)kSlots * rows_pad + 32), 256);
 }
 
 bool fits_one_per_cu()
 {
     int n1 = 0, n2 = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, sp_fused_kernel<1>, kFThreads, 0) != hipSuccess) return false;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, sp_fused_kernel<2>, kFThreads, 0) != hipSuccess) return false;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, sp_fused_kernel<1, 1>, kFThreads, 0) != hipSuccess) return false;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, sp_fused_kernel<2, 1>, kFThreads, 0) != hipSuccess) return false;
     return n1 >= 1 && n2 >= 1;
 }
 
 sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, hipStream_t st)
 {
     uint64_t *base = static_cast<uint64_t *>(ws);
-    const size_t n_part = (size_t)kSlots * a.rows_pad * a.n_wg, n_lse = (size_t)kSlots * a.rows_pad;
+    a.part_stride = part_stride(a.n_wg);
+    const size_t n_part = (size_t)kSlots * a.rows_pad * a.part_stride, n_lse = (size_t)kSlots * a.rows_pad;
     a.part = base;
     a.lse = base + n_part;
     a.err = reinterpret_cast<uint32_t *>(base + n_part + n_lse);
@@ -494,10 +664,14 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, hipStream_t st)
     // compute unit (LDS), so the grid may not exceed the number of compute units. All waits in the
     // kernel are bounded; should residency fail (the device shared with other work), the call ends
     // with NaN scores and the error word set instead of hanging.
-    if (a.n_nblk == 1)
-        hipLaunchKernelGGL(sp_fused_kernel<1>, dim3(a.n_wg), dim3(kFThreads), 0, st, a, kp);
+    if (a.n_nblk == 2 && a.n_gblk == 1)
+        hipLaunchKernelGGL((sp_fused_kernel<2, 1>), dim3(a.n_wg), dim3(kFThreads), 0, st, a, kp);
+    else if (a.n_nblk == 1 && a.n_gblk == 2)
+        hipLaunchKernelGGL((sp_fused_kernel<1, 2>), dim3(a.n_wg), dim3(kFThreads), 0, st, a, kp);
+    else if (a.n_nblk == 1 && a.n_gblk == 1)
+        hipLaunchKernelGGL((sp_fused_kernel<1, 1>), dim3(a.n_wg), dim3(kFThreads), 0, st, a, kp);
     else
-        hipLaunchKernelGGL(sp_fused_kernel<2>, dim3(a.n_wg), dim3(kFThreads), 0, st, a, kp);
+        return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel: %d x %d row blocks", a.n_nblk, a.n_gblk);
     SP_HIP_CHECK(hipGetLastError());
     return SP_OK;
 }
