@@ -55,7 +55,8 @@ constexpr int kRing = kLag + 1;           // fragment ring: phases it-3 .. it
 constexpr int kSlots = sp_fused::kSlots;  // exchange ring depth
 constexpr int kMaxRowsF = sp_fused::kMaxRows;   // 64 padded query rows per kv head
 constexpr unsigned kSpinMax = 1u << 20;    // polls before a wait gives up (about a second)
-constexpr int kExchangeWave = 0;           // the wave that talks to the exchange area
+constexpr int kDutyWave = 1;               // the wave that combines this workgroup's duty row
+constexpr int kLseWave = 2;                // the wave that fetches the normalisers
 
 #define SP_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define SP_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -157,6 +158,56 @@ __device__ __forceinline__ void lds_store_f32(float *p, float v)
 {
     const uint32_t ad = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(p));
     __asm__ volatile("ds_write_b32 %0, %1" : : "v"(ad), "v"(v) : "memory");
+}
+
+__device__ __forceinline__ float2 lds_load_f2(const float2 *p)
+{
+    const uint32_t ad = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(p));
+    float2 v;
+    __asm__ volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(ad) : "memory");
+    return v;
+}
+
+// Butterfly reductions with data-parallel-primitive moves: after the three steps every lane of an
+// aligned group of 8 holds the group's result; one more step extends it to the row of 16. Every
+// lane adds the same two operands in either order, so the results are identical across lanes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppXor1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // lane i <- lane 7 - i within groups of 8
+constexpr int kDppMirror = 0x140;       // lane i <- lane 15 - i within rows of 16
+
+__device__ __forceinline__ float group8_max(float v)
+{
+    v = fmaxf(v, dpp_move<kDppXor1>(v));
+    v = fmaxf(v, dpp_move<kDppXor2>(v));
+    return fmaxf(v, dpp_move<kDppHalfMirror>(v));
+}
+__device__ __forceinline__ float group8_sum(float v)
+{
+    v += dpp_move<kDppXor1>(v);
+    v += dpp_move<kDppXor2>(v);
+    return v + dpp_move<kDppHalfMirror>(v);
+}
+__device__ __forceinline__ float lane_value(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = group8_max(v);
+    v = fmaxf(v, dpp_move<kDppMirror>(v));
+    return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v = group8_sum(v);
+    v += dpp_move<kDppMirror>(v);
+    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
 
 struct PhaseId { int layer, kv; };
@@ -392,15 +443,16 @@ __device__ __forceinline__ int duty_row_of(const FusedArgs &a, int p, int w)
 }
 
 // One iteration `it` of the software pipeline. Per wave, in program order:
-//   top     wait for everything but the four newest loads; exchange wave: combine the duty row of
-//           phase it-2 and publish its normaliser, put the normalisers of phase it-3 into LDS
+//   top     wait for everything but the four newest loads; one wave combines the duty row of phase
+//           it-2 and publishes its normaliser, another puts the normalisers of phase it-3 into LDS
 //   B1
 //   lift    this wave's slice of Q(it-2) for the next iteration's probability pass; this wave's keys
 //           of K(it) from transit buffer it%2 into ring slot it%4
 //   stats   statistics pass of phase it; first four loads of K(it+2) into the buffer just emptied
 //   B2
-//   mid     exchange wave: publish this workgroup's partials of phase it, request the partials of
-//           phase it-1 (duty) and the normalisers of phase it-2; every wave: its slice of Q(it+1)
+//   mid     every wave: publish this workgroup's partials of eight rows of phase it, its slice of
+//           Q(it+1); the two exchange waves request the partials of phase it-1 (duty row) and the
+//           normalisers of phase it-2
 //   prob    probability pass of phase it-3; last four loads of K(it+2)
 // The four newest vector-memory operations of a wave are therefore always K-tile loads whose data
 // is not needed before the iteration after next; everything older has landed after vm_wait<4>.
@@ -426,7 +478,7 @@ __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &k
 
     // ---- top ----
     vm_wait<kTileInstr / 2>();
-    if (wave == kExchangeWave) {
+    if (wave == kDutyWave) {
         if (pd >= 0 && pd < n_phases) {
             const int duty_row = duty_row_of(a, pd, w);
             int g, n;
@@ -443,18 +495,20 @@ __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &k
                         for (int q = 0; q < 4; ++q) de.e[q] = ld64(src + min(lane + 64 * q, a.n_wg - 1));
                     } while (__any(!duty_ready(de, par, lane, a.n_wg)));
                 }
-                float m = neg_inf(), l = 0.f;
+                // maximum first, then one exponential per partial: short dependency chains, fixed order
+                float pm[4], pl[4], m = neg_inf();
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const float pm = __uint_as_float((uint32_t)de.e[q]);
-                    const float pl = __uint_as_float((uint32_t)(de.e[q] >> 32) & 0x7fffffffu);
-                    if (lane + 64 * q < a.n_wg) lse_merge(m, l, pm, pl, a.c);
+                    const bool valid = lane + 64 * q < a.n_wg;
+                    pm[q] = valid ? __uint_as_float((uint32_t)de.e[q]) : neg_inf();
+                    pl[q] = valid ? __uint_as_float((uint32_t)(de.e[q] >> 32) & 0x7fffffffu) : 0.f;
+                    m = fmaxf(m, pm[q]);
                 }
+                m = wave_max(m);
+                float l = 0.f;
 #pragma unroll
-                for (int off = 1; off < 64; off <<= 1) {
-                    const float m2 = __shfl_xor(m, off), l2 = __shfl_xor(l, off);
-                    lse_merge(m, l, m2, l2, a.c);
-                }
+                for (int q = 0; q < 4; ++q) l += pl[q] * fast_exp2((pm[q] - m) * a.c);
+                l = wave_sum(l);
                 if (lane == 0) {
                     const float v = -(m + fast_log2(l) * a.inv_c);
                     st64(a.lse + (size_t)(pd % kSlots) * a.rows_pad + duty_row,
@@ -462,6 +516,7 @@ __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &k
                 }
             }
         }
+    } else if (wave == kLseWave) {
         if (do_prob && lane < a.rows_pad) {
             int g, n;
             float v = neg_inf();
@@ -506,29 +561,29 @@ __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &k
     lds_barrier();                                                            // B2: wstats complete, q1 free
 
     // ---- mid: exchange traffic and Q of the next statistics pass, ahead of the remaining K loads ----
-    if (wave == kExchangeWave) {
-        if (do_stats && lane < a.rows_pad) {
-            int g, n;
-            if (row_valid<NB>(a, lane, g, n)) {
-                float m = wstats[0][lane].x, l = wstats[0][lane].y;
-#pragma unroll
-                for (int ww = 1; ww < kFWaves; ++ww) lse_merge(m, l, wstats[ww][lane].x, wstats[ww][lane].y, a.c);
-                const uint64_t bits = (uint64_t)__float_as_uint(m) | ((uint64_t)__float_as_uint(l) << 32) |
-                                      ((uint64_t)((it / kSlots) & 1) << 63);
-                st64(a.part + ((size_t)(it % kSlots) * a.rows_pad + lane) * a.part_stride + w, bits);
-            }
+    if (do_stats) {
+        // every wave combines the eight per-wave statistics of eight rows (lane = row x source wave)
+        // and publishes them: maximum first, then one exponential per source
+        const int row = wave * 8 + (lane >> 3);
+        const float2 st = lds_load_f2(&wstats[lane & 7][row]);
+        const float m = group8_max(st.x);
+        const float l = group8_sum(st.y * fast_exp2((st.x - m) * a.c));
+        int g, n;
+        if ((lane & 7) == 0 && row < a.rows_pad && row_valid<NB>(a, row, g, n)) {
+            const uint64_t bits = (uint64_t)__float_as_uint(m) | ((uint64_t)__float_as_uint(l) << 32) |
+                                  ((uint64_t)((it / kSlots) & 1) << 63);
+            st64(a.part + ((size_t)(it % kSlots) * a.rows_pad + row) * a.part_stride + w, bits);
         }
-        {   // partials of the row this workgroup combines at the next top (phase it - 1)
-            const int pn = clampi(it - 1, 0, n_phases - 1);
-            const int r = min(duty_row_of(a, pn, w), a.rows_pad - 1);
-            const uint64_t *src = a.part + ((size_t)(pn % kSlots) * a.rows_pad + r) * a.part_stride;
-            stage_entries(xduty, src, 0, a.part_stride / 2, lane);
-            stage_entries(xduty + 64, src, 64, a.part_stride / 2, lane);
-        }
-        {   // normalisers of the phase whose probability pass runs next iteration
-            const int pn = clampi(pc + 1, 0, n_phases - 1);
-            stage_entries(xlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, 0, a.rows_pad / 2, lane);
-        }
+    }
+    if (wave == kDutyWave) {        // partials of the row this workgroup combines at the next top (phase it - 1)
+        const int pn = clampi(it - 1, 0, n_phases - 1);
+        const int r = min(duty_row_of(a, pn, w), a.rows_pad - 1);
+        const uint64_t *src = a.part + ((size_t)(pn % kSlots) * a.rows_pad + r) * a.part_stride;
+        stage_entries(xduty, src, 0, a.part_stride / 2, lane);
+        stage_entries(xduty + 64, src, 64, a.part_stride / 2, lane);
+    } else if (wave == kLseWave) {  // normalisers of the phase whose probability pass runs next iteration
+        const int pn = clampi(pc + 1, 0, n_phases - 1);
+        stage_entries(xlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, 0, a.rows_pad / 2, lane);
     }
     {
         const PhaseId id1 = phase_of(min(it + 1, n_phases - 1), a.n_kv_heads);
