@@ -27,6 +27,34 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM traffic of one sp_score call on the default workload, from hardware counters (rocprofv3 --pmc
+# FETCH_SIZE, then WRITE_SIZE, each scaled by what the counter reads for the 1 GiB calibration copy).
+# It is reported only while the kernel sources are the ones the counters were taken on.
+TRAFFIC = {
+    "workload": "long-128k",
+    "sources_sha256": None,
+    "fetch_bytes": None,
+    "write_bytes": None,
+}
+KERNEL_SOURCES = ["sp_score_fused.hip", "sp_score_fused.hpp", "sp_score_dev.hpp", "sp_score.hip"]
+
+
+def kernel_sources_sha256() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2603_02631_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload: str):
+    if TRAFFIC["sources_sha256"] is None or TRAFFIC["workload"] != workload:
+        return None
+    if kernel_sources_sha256() != TRAFFIC["sources_sha256"]:
+        return None
+    return float(TRAFFIC["fetch_bytes"] + TRAFFIC["write_bytes"])
+
 
 def log(msg: str) -> None:
     print(msg, file=sys.stderr, flush=True)
@@ -40,8 +68,15 @@ def main() -> int:
     ap.add_argument("--workload", default="long-128k")
     ap.add_argument("--layer-agg", default="mean", choices=["mean", "max"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-layers", type=int, default=1)
+    ap.add_argument("--cpu-sample-layers", type=int, default=0,
+                    help="layers the CPU oracle is timed on (0 = all layers of the workload)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one 1 GiB device copy before the timed region (reference for HBM counters)")
+    ap.add_argument("--print-sources-hash", action="store_true")
     args = ap.parse_args()
+    if args.print_sources_hash:
+        print(kernel_sources_sha256())
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
@@ -62,6 +97,8 @@ def main() -> int:
         return 2
     mode = sp.SP_LAYER_MEAN if args.layer_agg == "mean" else sp.SP_LAYER_MAX
     L = w.L
+    if args.cpu_sample_layers <= 0:
+        args.cpu_sample_layers = w.n_layers
 
     # ---- inputs: generated on the host by the seeded generator, uploaded once ----
     t0 = time.time()
@@ -110,6 +147,13 @@ def main() -> int:
         if ev is not None:
             ev[2].record(stream)
 
+    if args.calibration_copy:
+        a_src = torch.ones(2**28, dtype=torch.float32, device=dev)       # 1 GiB read + 1 GiB written
+        a_dst = torch.empty_like(a_src)
+        torch.cuda.synchronize()
+        a_dst.copy_(a_src)
+        torch.cuda.synchronize()
+        del a_src, a_dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -146,7 +190,7 @@ def main() -> int:
                    "layer_agg": args.layer_agg, "k_layout": "HND"},
         "stage_ms": {"sp_score": score_ms, "sp_select+sp_project": rest_ms},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "kernel": "sp_score (all its launches)", "algorithmic_bytes": k_bytes},
     }
 
