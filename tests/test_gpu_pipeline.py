@@ -90,3 +90,57 @@ def test_pipeline_small_configs(name):
         diff = check_pipeline(w, out, I, doff, toff)
         say(f"[pipeline] {name} mode {mode}: ok, selection differs from oracle in {diff} chunks, "
             f"kept {out['n_kept']} of {toff.size - 1} target tokens")
+
+
+@pytest.mark.timeout(400)
+def test_pipeline_full_size_benchmark_workload():
+    """The 128K-token workload the benchmark times, in the benchmark's launch configuration (one
+    prompt, HND keys, default stream, the single-launch score kernel): every score, then the chained
+    selection and projection, against the oracle; both aggregation modes."""
+    import paper_2603_02631_amd as sp
+    from gpu_util import assert_scores_close, dev_bits, gpu_score, make_desc
+    w = synth.get_config("long-128k")
+    say(f"[pipeline] {w.name}: generating {w.k_bytes_per_token * w.L / 2**30:.2f} GiB of keys")
+    inp = synth.make_score_inputs(w)
+    doff, toff = synth.gen_char_offsets(w, w.L)
+    assert sp.sp_score_is_fused(make_desc(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_q, w.scale, 0,
+                                          "HND", w.L), w.L) == 1
+    k_dev = [dev_bits(k) for k in inp["k"]]
+    t0 = time.time()
+    I = oracle.score(inp["q"][0], inp["k"], w.scale, oracle.LAYER_MEAN)
+    say(f"[pipeline] {w.name} mean: oracle {time.time() - t0:.1f}s")
+    out = run_pipeline_gpu(w, inp["q"][0], k_dev, w.L, doff, toff, oracle.LAYER_MEAN)
+    diff = check_pipeline(w, out, I, doff, toff)
+    say(f"[pipeline] {w.name} mean: ok, max rel err {np.max(np.abs(out['scores'] - I) / I):.2e}, selection differs "
+        f"from oracle in {diff} chunks, kept {out['n_kept']} of {toff.size - 1} target tokens")
+    del k_dev
+    t0 = time.time()
+    I = oracle.score(inp["q"][0], inp["k"], w.scale, oracle.LAYER_MAX)
+    say(f"[pipeline] {w.name} max: oracle {time.time() - t0:.1f}s")
+    got = gpu_score(inp["q"][0], inp["k"], w.scale, oracle.LAYER_MAX)
+    assert_scores_close(got, I)
+    say(f"[pipeline] {w.name} max: ok, max rel err {np.max(np.abs(got - I) / I):.2e}")
+
+
+@pytest.mark.timeout(400)
+def test_score_batch_full_size_ragged_workload():
+    """The 16-prompt ragged batch (2K to 64K tokens, 332K in all) at full size: every prompt's
+    scores against the oracle run on that prompt alone."""
+    from gpu_util import assert_scores_close, gpu_score_batch
+    w = synth.get_config("ragged-16")
+    lengths = synth.gen_prompt_lengths(w)
+    say(f"[score_batch] {w.name}: {lengths.size} prompts, {int(lengths.sum())} tokens")
+    hh = synth.heavy_hitter_positions(w, lengths)
+    q = synth.gen_q(w, lengths.size)
+    ks = [synth.gen_k_layer(w, l, q, lengths, hh) for l in range(w.n_layers)]
+    offsets = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    got = gpu_score_batch(q, ks, offsets, w.scale, oracle.LAYER_MEAN)
+    t0 = time.time()
+    worst = 0.0
+    for b in range(lengths.size):
+        sl = slice(int(offsets[b]), int(offsets[b + 1]))
+        kb = [np.ascontiguousarray(k[:, sl, :]) for k in ks]
+        want = oracle.score(q[b], kb, w.scale, oracle.LAYER_MEAN)
+        assert_scores_close(got[sl], want)
+        worst = max(worst, float(np.max(np.abs(got[sl] - want) / want)))
+    say(f"[score_batch] {w.name}: ok, oracle {time.time() - t0:.1f}s, max rel err {worst:.2e}")
