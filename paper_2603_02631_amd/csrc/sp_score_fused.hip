@@ -9,10 +9,11 @@
 //  * one persistent workgroup per compute unit (8 waves) owns 512 consecutive
 //    keys for the whole call; a "phase" is one (layer, kv head) pair, and the
 //    workgroup's share of a phase is a 512 x 64 bf16 tile (64 KB);
-//  * tiles stream HBM -> LDS with direct-to-LDS loads, two phases ahead, into
-//    two transit buffers. K is wave-private: each wave loads, and later lifts
-//    into MFMA fragments, its own 64 keys, so the K path needs no barrier. The
-//    fragments of four phases live in registers (a ring of 4 x 32 VGPRs);
+//  * tiles stream HBM -> LDS with direct-to-LDS loads about one and a half
+//    phases ahead. K is wave-private: each wave loads its own 64 keys, in two
+//    32-key sub-tiles, into a ring of three sub-tile slots, and later lifts them
+//    into MFMA fragments, so the K path needs no barrier. The fragments of four
+//    phases live in registers (a ring of 4 x 32 VGPRs);
 //  * a vector-memory instruction blocks its wave while the compute unit's memory
 //    pipe is full, and the pipe drains at the unit's share of HBM bandwidth, so
 //    the eight tile loads of an iteration are issued one by one between the
@@ -25,7 +26,9 @@
 //    probability pass of phase p from the fragments still in its registers:
 //    logits again with -lse folded into the MFMA accumulator, maximum over
 //    heads on logits, one exp per (lookahead row, key), accumulation over
-//    lookahead rows and layers in registers. Scores are stored once at the end.
+//    lookahead rows and layers in registers. Scores are stored once at the end;
+//  * Q tiles, per-wave statistics and accumulator seeds are double-buffered in
+//    LDS so that one workgroup barrier per phase orders everything shared.
 //
 // The exchange uses no read-modify-write atomics and no cache-wide fences:
 // every exchanged word is written and read with device-scope relaxed atomics,
@@ -49,9 +52,11 @@ constexpr int kFWaves = 8;
 constexpr int kFThreads = kFWaves * 64;
 constexpr int kNS = 2;                    // 32-key sub-tiles per wave
 constexpr int kFTile = sp_fused::kTileKeys;   // 512 keys per workgroup per phase
-constexpr int kTileInstr = kFTile / 64;   // tile-load instructions per wave per tile (8 rows each)
+constexpr int kSubInstr = 4;              // tile-load instructions per sub-tile (8 rows, 1 KB each)
+constexpr int kSubSlots = 3;              // sub-tile slots in a wave's transit ring
+constexpr int kSubChunks = 32 * kCH;      // 16-byte chunks per sub-tile slot
 constexpr int kLag = 3;                   // phases between statistics and probability pass
-constexpr int kRing = kLag + 1;           // fragment ring: phases it-3 .. it
+constexpr int kRing = kLag + 1;           // fragment ring: four phases
 constexpr int kSlots = sp_fused::kSlots;  // exchange ring depth
 constexpr int kMaxRowsF = sp_fused::kMaxRows;   // 64 padded query rows per kv head
 constexpr unsigned kSpinMax = 1u << 20;    // polls before a wait gives up (about a second)
@@ -97,45 +102,17 @@ struct Ring {
     bf16x8 kf[kRing][kNS][kKS];           // K fragments of the phases in flight
 };
 
-// LDS reads of tiles filled by direct-to-LDS loads are written as asm blocks: the compiler cannot
-// tell which in-flight load targets which buffer and would put a full vector-memory wait in front
-// of every such read. The kernel waits (vm_wait + barrier) for exactly what it is about to read.
-//
-// Lifts this wave's 64 keys (two 32-key sub-tiles, four k-steps each) from a transit buffer.
-__device__ __forceinline__ void lift_k_tile(const u32x4 *tile, int row0, int hf, bf16x8 (&f)[kNS][kKS])
-{
-    static_assert(kNS == 2 && kKS == 4, "layout of the asm block");
-    const uint32_t base = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(tile));
-    uint32_t ad[kKS];
-#pragma unroll
-    for (int t = 0; t < kKS; ++t) ad[t] = base + 16u * (uint32_t)lds_slot<kD>(row0, 2 * t + hf);
-    u32x4 r[kNS][kKS];
-    // sub-tile 1 starts 32 rows = 4096 bytes later; (row >> 1) & 7 and hence the swizzle are the same
-    __asm__ volatile(
-        "ds_read_b128 %0, %8\n\t"
-        "ds_read_b128 %1, %9\n\t"
-        "ds_read_b128 %2, %10\n\t"
-        "ds_read_b128 %3, %11\n\t"
-        "ds_read_b128 %4, %8 offset:4096\n\t"
-        "ds_read_b128 %5, %9 offset:4096\n\t"
-        "ds_read_b128 %6, %10 offset:4096\n\t"
-        "ds_read_b128 %7, %11 offset:4096\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(r[0][0]), "=&v"(r[0][1]), "=&v"(r[0][2]), "=&v"(r[0][3]),
-          "=&v"(r[1][0]), "=&v"(r[1][1]), "=&v"(r[1][2]), "=&v"(r[1][3])
-        : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3])
-        : "memory");
-#pragma unroll
-    for (int s = 0; s < kNS; ++s)
-#pragma unroll
-        for (int t = 0; t < kKS; ++t) f[s][t] = __builtin_bit_cast(bf16x8, r[s][t]);
-}
+// All LDS traffic of the main loop is written as asm: the compiler cannot tell which in-flight
+// direct-to-LDS load targets which buffer and would put a full vector-memory wait in front of
+// LDS accesses it can see. The kernel waits (vm_wait, barrier) for exactly what it is about to read.
+__device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(p)); }
 
-// Fragments of one 32-row block of a Q tile.
-__device__ __forceinline__ void lift_q_block(const u32x4 *tile, int row, int hf, bf16x8 (&f)[kKS])
+// MFMA fragments of 32 rows of a swizzled 64-wide bf16 tile: lane (col, hf) takes row `row`,
+// 16-byte chunks 2t + hf.
+__device__ __forceinline__ void lift_block(const u32x4 *tile, int row, int hf, bf16x8 (&f)[kKS])
 {
     static_assert(kKS == 4, "layout of the asm block");
-    const uint32_t base = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(tile));
+    const uint32_t base = lds_addr(tile);
     uint32_t ad[kKS];
 #pragma unroll
     for (int t = 0; t < kKS; ++t) ad[t] = base + 16u * (uint32_t)lds_slot<kD>(row, 2 * t + hf);
@@ -153,19 +130,39 @@ __device__ __forceinline__ void lift_q_block(const u32x4 *tile, int row, int hf,
     for (int t = 0; t < kKS; ++t) f[t] = __builtin_bit_cast(bf16x8, r[t]);
 }
 
-// A plain LDS store, opaque to the compiler for the same reason (ordered by the next barrier).
 __device__ __forceinline__ void lds_store_f32(float *p, float v)
 {
-    const uint32_t ad = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(p));
-    __asm__ volatile("ds_write_b32 %0, %1" : : "v"(ad), "v"(v) : "memory");
+    __asm__ volatile("ds_write_b32 %0, %1" : : "v"(lds_addr(p)), "v"(v) : "memory");
 }
-
+__device__ __forceinline__ void lds_store_f2(float2 *p, float2 v)
+{
+    __asm__ volatile("ds_write_b64 %0, %1" : : "v"(lds_addr(p)), "v"(v) : "memory");
+}
 __device__ __forceinline__ float2 lds_load_f2(const float2 *p)
 {
-    const uint32_t ad = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(p));
     float2 v;
-    __asm__ volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(ad) : "memory");
+    __asm__ volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(lds_addr(p)) : "memory");
     return v;
+}
+// Sixteen consecutive floats (64-byte aligned).
+__device__ __forceinline__ f32x16 lds_load_f16(const float *p)
+{
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    const uint32_t ad = lds_addr(p);
+    f32x4 r[4];
+    __asm__ volatile(
+        "ds_read_b128 %0, %4\n\t"
+        "ds_read_b128 %1, %4 offset:16\n\t"
+        "ds_read_b128 %2, %4 offset:32\n\t"
+        "ds_read_b128 %3, %4 offset:48\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
+        : "v"(ad)
+        : "memory");
+    f32x16 o;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) { o[4 * v] = r[v].x; o[4 * v + 1] = r[v].y; o[4 * v + 2] = r[v].z; o[4 * v + 3] = r[v].w; }
+    return o;
 }
 
 // Butterfly reductions with data-parallel-primitive moves: after the three steps every lane of an
@@ -225,29 +222,51 @@ __device__ __forceinline__ bool row_valid(const FusedArgs &a, int row, int &g, i
 }
 
 // One wave instruction moves 64 chunks = 8 key rows (1 KB, contiguous in HBM when keys are
-// contiguous); a wave's 64 rows take eight of them. The address is a uniform base plus a 32-bit
+// contiguous); a 32-key sub-tile takes four of them. The address is a uniform base plus a 32-bit
 // per-lane byte offset, so no address registers stay live between instructions.
 struct KIssue {
-    u32x4 *tile;              // transit buffer being refilled
+    u32x4 *slot;              // sub-tile slot being refilled (this wave's)
     const uint16_t *base;     // first key of this workgroup in the (layer, kv head) being fetched (uniform)
     uint32_t stride_bytes;    // bytes between consecutive keys
-    int n_valid, wave, lane;
+    int row0;                 // first key of the sub-tile within the workgroup's tile
+    int n_valid, lane;
 };
 
-// Issues instructions first .. first+COUNT-1 of the tile (first and COUNT compile-time at call sites).
+// Issues instructions first .. first+COUNT-1 of the sub-tile (first and COUNT compile-time at call sites).
 template <int COUNT>
 __device__ __forceinline__ void k_issue(const KIssue &ki, int first)
 {
 #pragma unroll
     for (int i = 0; i < COUNT; ++i) {
         const int idx = first + i;
-        int row = ki.wave * 64 + 8 * idx + (ki.lane >> 3);
-        const uint32_t chunk = (uint32_t)((ki.lane & 7) ^ ((row >> 1) & 7));
+        const int r = 8 * idx + (ki.lane >> 3);               // row within the sub-tile
+        const uint32_t chunk = (uint32_t)((ki.lane & 7) ^ ((r >> 1) & 7));
+        int row = ki.row0 + r;
         row = row < ki.n_valid ? row : ki.n_valid - 1;        // tail rows repeat the last valid key
         const uint32_t off = (uint32_t)row * ki.stride_bytes + chunk * 16u;
         const char *src = reinterpret_cast<const char *>(ki.base) + off;
-        __builtin_amdgcn_global_load_lds(SP_GPTR(src), SP_LPTR(ki.tile + (ki.wave * 64 + 8 * idx) * kCH), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(SP_GPTR(src), SP_LPTR(ki.slot + 8 * idx * kCH), 16, 0, 0);
     }
+}
+
+// Sub-tile s2 of phase p lives in slot (2p + s2) mod 3 of its wave's transit ring.
+__device__ __forceinline__ u32x4 *sub_slot(u32x4 *kring, int wave, int p, int s2)
+{
+    return kring + (wave * kSubSlots + (2 * p + s2) % kSubSlots) * kSubChunks;
+}
+
+__device__ __forceinline__ KIssue k_issue_setup(const FusedArgs &a, const LayerPtrs &kp, u32x4 *kring, int p, int s2,
+                                                int n_phases, int n_valid, int wave, int lane)
+{
+    const PhaseId id = phase_of(min(p, n_phases - 1), a.n_kv_heads);
+    KIssue ki;
+    ki.slot = sub_slot(kring, wave, p, s2);
+    ki.base = kp.p[id.layer] + (int64_t)id.kv * a.k_stride_head + (int64_t)blockIdx.x * kFTile * a.k_stride_token;
+    ki.stride_bytes = (uint32_t)a.k_stride_token * 2u;
+    ki.row0 = wave * 64 + s2 * 32;
+    ki.n_valid = p < n_phases ? n_valid : 1;      // past the last phase: a one-row dummy keeps the count fixed
+    ki.lane = lane;
+    return ki;
 }
 
 // Each wave loads eight rows (one instruction) of a Q tile of one (layer, kv head), in the padded
@@ -274,23 +293,17 @@ struct Acc {
 // ---- probability pass of one phase from the fragment ring; tile loads are issued between the MFMA steps ----
 template <int NB, int GB>
 __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const u32x4 *q2, const float *cinit,
-                                          Acc<NB> &acc, int hf, int col, const KIssue &ki, int first)
+                                          Acc<NB> &acc, int hf, int col, const KIssue &ki)
 {
-    constexpr int kPerStep = (kTileInstr / 2) / (NB * GB * kNS);
+    constexpr int kPerStep = kSubInstr / (NB * GB * kNS);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
         for (int gb = 0; gb < GB; ++gb) {
             const int blk = gb * NB + nb;
             bf16x8 qf[kKS];
-            lift_q_block(q2, blk * 32 + col, hf, qf);
-            f32x16 ci;
-            const float4 *cp = reinterpret_cast<const float4 *>(cinit + blk * 32 + hf * 16);
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float4 x = cp[v];
-                ci[4 * v + 0] = x.x; ci[4 * v + 1] = x.y; ci[4 * v + 2] = x.z; ci[4 * v + 3] = x.w;
-            }
+            lift_block(q2, blk * 32 + col, hf, qf);
+            const f32x16 ci = lds_load_f16(cinit + blk * 32 + hf * 16);
 #pragma unroll
             for (int s = 0; s < kNS; ++s) {
                 f32x16 d = ci;
@@ -300,7 +313,7 @@ __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const u3
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     acc.mx[s][nb][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[s][nb][e]);
-                k_issue<kPerStep>(ki, first + ((nb * GB + gb) * kNS + s) * kPerStep);
+                k_issue<kPerStep>(ki, ((nb * GB + gb) * kNS + s) * kPerStep);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -330,11 +343,11 @@ __device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS]
                                            float2 *wstats_wave, int n_valid, int wave, int hf, int col,
                                            const KIssue &ki)
 {
-    constexpr int kPerStep = (kTileInstr / 2) / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
+    constexpr int kPerStep = kSubInstr / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
 #pragma unroll
     for (int blk = 0; blk < NBLK; ++blk) {
         bf16x8 qf[kKS];
-        lift_q_block(q1, blk * 32 + col, hf, qf);
+        lift_block(q1, blk * 32 + col, hf, qf);
         float m = neg_inf(), l = 0.f;
 #pragma unroll
         for (int s = 0; s < kNS; ++s) {
@@ -378,19 +391,18 @@ __device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS]
         }
         const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
         lse_merge(m, l, m2, l2, c);
-        if (hf == 0) wstats_wave[blk * 32 + col] = make_float2(m, l);
+        if (hf == 0) lds_store_f2(wstats_wave + blk * 32 + col, make_float2(m, l));
     }
 }
 
-// Exchange data requested with direct-to-LDS loads lands in two small staging areas private to
-// the exchange wave: xduty holds the n_wg partials of the duty row (entry e at byte 8e), xlse the
-// normaliser entries of one phase. Reading them back in asm keeps the compiler from waiting for
-// every vector-memory operation in flight.
+// Exchange data requested with direct-to-LDS loads lands in two small staging areas, each private
+// to one wave: xduty holds the n_wg partials of the duty row (entry e at byte 8e), xlse the
+// normaliser entries of one phase.
 struct DutyEntries { uint64_t e[4]; };     // entries lane, lane + 64, lane + 128, lane + 192
 
 __device__ __forceinline__ DutyEntries read_duty_staging(const u32x4 *xduty, int lane)
 {
-    const uint32_t ad = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(xduty)) + 8u * (uint32_t)lane;
+    const uint32_t ad = lds_addr(xduty) + 8u * (uint32_t)lane;
     DutyEntries d;
     __asm__ volatile(
         "ds_read_b64 %0, %4\n\t"
@@ -406,7 +418,7 @@ __device__ __forceinline__ DutyEntries read_duty_staging(const u32x4 *xduty, int
 
 __device__ __forceinline__ uint64_t read_lse_staging(const u32x4 *xlse, int lane)
 {
-    const uint32_t ad = (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(xlse)) + 8u * (uint32_t)lane;
+    const uint32_t ad = lds_addr(xlse) + 8u * (uint32_t)lane;
     uint64_t v;
     __asm__ volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(ad) : "memory");
     return v;
@@ -442,42 +454,108 @@ __device__ __forceinline__ int duty_row_of(const FusedArgs &a, int p, int w)
     return r < 0 ? r + a.n_wg : r;
 }
 
-// One iteration `it` of the software pipeline. Per wave, in program order:
-//   top     wait for everything but the four newest loads; one wave combines the duty row of phase
-//           it-2 and publishes its normaliser, another puts the normalisers of phase it-3 into LDS
-//   B1
-//   lift    this wave's slice of Q(it-2) for the next iteration's probability pass; this wave's keys
-//           of K(it) from transit buffer it%2 into ring slot it%4
-//   stats   statistics pass of phase it; first four loads of K(it+2) into the buffer just emptied
-//   B2
-//   mid     every wave: publish this workgroup's partials of eight rows of phase it, its slice of
-//           Q(it+1); the two exchange waves request the partials of phase it-1 (duty row) and the
-//           normalisers of phase it-2
-//   prob    probability pass of phase it-3; last four loads of K(it+2)
-// The four newest vector-memory operations of a wave are therefore always K-tile loads whose data
-// is not needed before the iteration after next; everything older has landed after vm_wait<4>.
-template <int NB, int GB, int SLOT, int BUF>
-__device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &kp, int it, int n_phases, Ring &ring,
-                                          Acc<NB> &acc, u32x4 *xduty, u32x4 *xlse, u32x4 *kt0, u32x4 *kt1, u32x4 *q1, u32x4 *q2a,
-                                          u32x4 *q2b, float2 (*wstats)[kMaxRowsF], float (*cinit2)[kMaxRowsF],
-                                          int *s_fail, int n_valid)
+struct Shared {
+    u32x4 *kring;                         // [8 waves][3 slots][32 rows x 8 chunks]
+    u32x4 *q1[2], *q2[2];                 // Q tiles of the statistics / probability pass, by phase parity
+    float2 (*wstats)[kFWaves][kMaxRowsF]; // [2]
+    float (*cinit)[kMaxRowsF];            // [2]
+    u32x4 *xduty, *xlse;
+    int *fail;
+};
+
+// One step `s` of the software pipeline: everything between two workgroup barriers. Per wave, in
+// program order (phase numbers in brackets are skipped when out of range):
+//   mid     publish this workgroup's partials of eight rows of phase s-1 (all waves); the duty wave
+//           requests the partials of its duty row of phase s-2; every wave requests its slices of
+//           Q(s+1) for the next statistics pass and of Q(s-3) for the next probability pass
+//   prob    probability pass of phase s-4 from ring slot s%4; loads of sub-tile 0 of K(s+1)
+//   lse     the normaliser wave requests the normalisers of phase s-3
+//   lift    wait for sub-tile 1 of K(s); lift K(s) into ring slot s%4
+//   stats   statistics pass of phase s; loads of sub-tile 1 of K(s+1)
+//   pre     wait for the Q slices (and the exchange data); duty wave: combine the duty row of phase
+//           s-2 and publish its normaliser; normaliser wave: seeds of the probability pass of phase s-3
+//   barrier
+// Vector-memory operations per wave and step, oldest first: [publish store] [2 duty loads] Q, Q,
+// 4 K loads (prob), [normaliser load], 4 K loads (stats); the bracketed ones exist on some waves or
+// in some steps only, so every wait counts only operations that are certainly issued behind the
+// ones it needs.
+template <int NB, int GB, int SLOT, int PAR>
+__device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, int s, int n_phases, Ring &ring,
+                                     Acc<NB> &acc, const Shared &sh, int n_valid)
 {
-    // Lane-derived LDS and global offsets are recomputed every iteration instead of being kept in
+    // Lane-derived LDS and global offsets are recomputed every step instead of being kept in
     // registers across the whole loop (the opaque copy stops the compiler from hoisting them).
     int tid = threadIdx.x;
     __asm__ volatile("" : "+v"(tid));
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, hf = lane >> 5, col = lane & 31;
     const int w = blockIdx.x;
-    u32x4 *kt = BUF ? kt1 : kt0;
-    u32x4 *q2 = BUF ? q2b : q2a;          // Q of phase it-3; the other buffer receives Q of phase it-2
-    u32x4 *q2_next = BUF ? q2a : q2b;
-    float *cinit = cinit2[BUF];           // double-buffered: waves may still read the other one
-    const int pc = it - kLag;             // phase whose probability pass runs in this iteration
-    const int pd = it - 2;                // phase whose duty loads were issued last iteration
-    const bool do_prob = pc >= 0 && pc < n_phases, do_stats = it < n_phases;
+    const int pp = s - 1;                 // phase whose partials are published
+    const int pc = s - 1 - kLag;          // phase of this step's probability pass
+    const int pd = s - 2;                 // phase whose duty row is combined in this step
+    const int pl = s - kLag;              // phase whose normalisers are fetched in this step
+    const bool do_stats = s < n_phases, do_prob = pc >= 0 && pc < n_phases;
 
-    // ---- top ----
-    vm_wait<kTileInstr / 2>();
+    // ---- mid ----
+    if (pp >= 0 && pp < n_phases) {
+        // every wave combines the eight per-wave statistics of eight rows (lane = row x source wave)
+        // and publishes them: maximum first, then one exponential per source
+        const int row = wave * 8 + (lane >> 3);
+        const float2 st = lds_load_f2(&sh.wstats[1 - PAR][lane & 7][row]);
+        const float m = group8_max(st.x);
+        const float l = group8_sum(st.y * fast_exp2((st.x - m) * a.c));
+        int g, n;
+        if ((lane & 7) == 0 && row < a.rows_pad && row_valid<NB>(a, row, g, n)) {
+            const uint64_t bits = (uint64_t)__float_as_uint(m) | ((uint64_t)__float_as_uint(l) << 32) |
+                                  ((uint64_t)((pp / kSlots) & 1) << 63);
+            st64(a.part + ((size_t)(pp % kSlots) * a.rows_pad + row) * a.part_stride + w, bits);
+        }
+    }
+    if (wave == kDutyWave) {
+        const int pn = clampi(pd, 0, n_phases - 1);
+        const int r = min(duty_row_of(a, pn, w), a.rows_pad - 1);
+        const uint64_t *src = a.part + ((size_t)(pn % kSlots) * a.rows_pad + r) * a.part_stride;
+        stage_entries(sh.xduty, src, 0, a.part_stride / 2, lane);
+        stage_entries(sh.xduty + 64, src, 64, a.part_stride / 2, lane);
+    }
+    {
+        const PhaseId id1 = phase_of(min(s + 1, n_phases - 1), a.n_kv_heads);
+        issue_q_slice<NB>(sh.q1[1 - PAR], a, id1.layer, id1.kv, wave, lane);
+        const PhaseId id2 = phase_of(clampi(pl, 0, n_phases - 1), a.n_kv_heads);
+        issue_q_slice<NB>(sh.q2[PAR], a, id2.layer, id2.kv, wave, lane);
+    }
+
+    // ---- probability pass of phase pc; sub-tile 0 of K(s+1) ----
+    {
+        const KIssue ki = k_issue_setup(a, kp, sh.kring, s + 1, 0, n_phases, n_valid, wave, lane);
+        if (do_prob) {
+            prob_pass<NB, GB>(ring.kf[SLOT], sh.q2[1 - PAR], sh.cinit[1 - PAR], acc, hf, col, ki);
+            const PhaseId idc = phase_of(pc, a.n_kv_heads);
+            if (idc.kv == a.n_kv_heads - 1 && (a.layer_agg == SP_LAYER_MEAN || idc.layer == a.n_layers - 1))
+                close_layer<NB>(acc, a.c);
+        } else {
+            k_issue<kSubInstr>(ki, 0);
+        }
+    }
+    if (wave == kLseWave) {
+        const int pn = clampi(pl, 0, n_phases - 1);
+        stage_entries(sh.xlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, 0, a.rows_pad / 2, lane);
+    }
+
+    // ---- lift K(s), statistics pass of phase s; sub-tile 1 of K(s+1) ----
+    vm_wait<2 + kSubInstr>();             // behind sub-tile 1 of K(s): at least Q, Q and the 4 loads of the prob part
+    {
+        const KIssue ki = k_issue_setup(a, kp, sh.kring, s + 1, 1, n_phases, n_valid, wave, lane);
+        if (do_stats) {
+#pragma unroll
+            for (int s2 = 0; s2 < kNS; ++s2) lift_block(sub_slot(sh.kring, wave, s, s2), col, hf, ring.kf[SLOT][s2]);
+            stats_pass<NB * GB>(a.c, ring.kf[SLOT], sh.q1[PAR], sh.wstats[PAR][wave], n_valid, wave, hf, col, ki);
+        } else {
+            k_issue<kSubInstr>(ki, 0);
+        }
+    }
+
+    // ---- pre-barrier: exchange data in, seeds out ----
+    if (wave == kLseWave) vm_wait<kSubInstr>(); else vm_wait<2 * kSubInstr>();
     if (wave == kDutyWave) {
         if (pd >= 0 && pd < n_phases) {
             const int duty_row = duty_row_of(a, pd, w);
@@ -485,29 +563,29 @@ __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &k
             if (duty_row < a.rows_pad && row_valid<NB>(a, duty_row, g, n)) {
                 const uint32_t par = (uint32_t)(pd / kSlots) & 1u;
                 const uint64_t *src = a.part + ((size_t)(pd % kSlots) * a.rows_pad + duty_row) * a.part_stride;
-                // fast path: the partials requested last iteration are all there; otherwise poll (bounded)
-                DutyEntries de = read_duty_staging(xduty, lane);
-                if (__any(!duty_ready(de, par, lane, a.n_wg)) && *s_fail == 0) {
+                // fast path: the partials requested at the start of this step are all there; otherwise poll (bounded)
+                DutyEntries de = read_duty_staging(sh.xduty, lane);
+                if (__any(!duty_ready(de, par, lane, a.n_wg)) && *sh.fail == 0) {
                     unsigned spins = 0;
                     do {
-                        if (++spins > kSpinMax) { *s_fail = 1; break; }
+                        if (++spins > kSpinMax) { *sh.fail = 1; break; }
 #pragma unroll
                         for (int q = 0; q < 4; ++q) de.e[q] = ld64(src + min(lane + 64 * q, a.n_wg - 1));
                     } while (__any(!duty_ready(de, par, lane, a.n_wg)));
                 }
                 // maximum first, then one exponential per partial: short dependency chains, fixed order
-                float pm[4], pl[4], m = neg_inf();
+                float pm[4], pl4[4], m = neg_inf();
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const bool valid = lane + 64 * q < a.n_wg;
                     pm[q] = valid ? __uint_as_float((uint32_t)de.e[q]) : neg_inf();
-                    pl[q] = valid ? __uint_as_float((uint32_t)(de.e[q] >> 32) & 0x7fffffffu) : 0.f;
+                    pl4[q] = valid ? __uint_as_float((uint32_t)(de.e[q] >> 32) & 0x7fffffffu) : 0.f;
                     m = fmaxf(m, pm[q]);
                 }
                 m = wave_max(m);
                 float l = 0.f;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) l += pl[q] * fast_exp2((pm[q] - m) * a.c);
+                for (int q = 0; q < 4; ++q) l += pl4[q] * fast_exp2((pm[q] - m) * a.c);
                 l = wave_sum(l);
                 if (lane == 0) {
                     const float v = -(m + fast_log2(l) * a.inv_c);
@@ -517,100 +595,35 @@ __device__ __forceinline__ void iteration(const FusedArgs &a, const LayerPtrs &k
             }
         }
     } else if (wave == kLseWave) {
-        if (do_prob && lane < a.rows_pad) {
+        if (pl >= 0 && pl < n_phases && lane < a.rows_pad) {
             int g, n;
             float v = neg_inf();
             if (row_valid<NB>(a, lane, g, n)) {
-                const uint64_t *src = a.lse + (size_t)(pc % kSlots) * a.rows_pad + lane;
-                uint64_t entry = read_lse_staging(xlse, lane);
-                if ((uint32_t)(entry >> 32) != (uint32_t)(pc + 1) && *s_fail == 0) {
+                const uint64_t *src = a.lse + (size_t)(pl % kSlots) * a.rows_pad + lane;
+                uint64_t entry = read_lse_staging(sh.xlse, lane);
+                if ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1) && *sh.fail == 0) {
                     unsigned spins = 0;
                     do {
-                        if (++spins > kSpinMax) { *s_fail = 1; break; }
+                        if (++spins > kSpinMax) { *sh.fail = 1; break; }
                         entry = ld64(src);
-                    } while ((uint32_t)(entry >> 32) != (uint32_t)(pc + 1));
+                    } while ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1));
                 }
                 v = __uint_as_float((uint32_t)entry);
             }
             const int rho = lane & 31;
-            lds_store_f32(cinit + (lane & ~31) + ((rho >> 2) & 1) * 16 + 4 * (rho >> 3) + (rho & 3), v);
+            lds_store_f32(sh.cinit[PAR] + (lane & ~31) + ((rho >> 2) & 1) * 16 + 4 * (rho >> 3) + (rho & 3), v);
         }
     }
-    lds_barrier();                                                            // B1: K(it), Q tiles, cinit ready
-
-    // ---- Q of the next probability pass, lift, statistics pass; first half of the loads of K(it+2) ----
-    {
-        const PhaseId id2 = phase_of(clampi(pc + 1, 0, n_phases - 1), a.n_kv_heads);
-        issue_q_slice<NB>(q2_next, a, id2.layer, id2.kv, wave, lane);
-    }
-    KIssue ki;
-    {
-        const PhaseId id3 = phase_of(min(it + 2, n_phases - 1), a.n_kv_heads);
-        ki.tile = kt;
-        ki.base = kp.p[id3.layer] + (int64_t)id3.kv * a.k_stride_head + (int64_t)w * kFTile * a.k_stride_token;
-        ki.stride_bytes = (uint32_t)a.k_stride_token * 2u;
-        ki.n_valid = (it + 2 < n_phases) ? n_valid : 1;     // past the last phase: a one-row dummy keeps the count fixed
-        ki.wave = wave; ki.lane = lane;
-    }
-    if (do_stats) {
-        lift_k_tile(kt, wave * kNS * 32 + col, hf, ring.kf[SLOT]);
-        stats_pass<NB * GB>(a.c, ring.kf[SLOT], q1, wstats[wave], n_valid, wave, hf, col, ki);
-    } else {
-        k_issue<kTileInstr / 2>(ki, 0);
-    }
-    lds_barrier();                                                            // B2: wstats complete, q1 free
-
-    // ---- mid: exchange traffic and Q of the next statistics pass, ahead of the remaining K loads ----
-    if (do_stats) {
-        // every wave combines the eight per-wave statistics of eight rows (lane = row x source wave)
-        // and publishes them: maximum first, then one exponential per source
-        const int row = wave * 8 + (lane >> 3);
-        const float2 st = lds_load_f2(&wstats[lane & 7][row]);
-        const float m = group8_max(st.x);
-        const float l = group8_sum(st.y * fast_exp2((st.x - m) * a.c));
-        int g, n;
-        if ((lane & 7) == 0 && row < a.rows_pad && row_valid<NB>(a, row, g, n)) {
-            const uint64_t bits = (uint64_t)__float_as_uint(m) | ((uint64_t)__float_as_uint(l) << 32) |
-                                  ((uint64_t)((it / kSlots) & 1) << 63);
-            st64(a.part + ((size_t)(it % kSlots) * a.rows_pad + row) * a.part_stride + w, bits);
-        }
-    }
-    if (wave == kDutyWave) {        // partials of the row this workgroup combines at the next top (phase it - 1)
-        const int pn = clampi(it - 1, 0, n_phases - 1);
-        const int r = min(duty_row_of(a, pn, w), a.rows_pad - 1);
-        const uint64_t *src = a.part + ((size_t)(pn % kSlots) * a.rows_pad + r) * a.part_stride;
-        stage_entries(xduty, src, 0, a.part_stride / 2, lane);
-        stage_entries(xduty + 64, src, 64, a.part_stride / 2, lane);
-    } else if (wave == kLseWave) {  // normalisers of the phase whose probability pass runs next iteration
-        const int pn = clampi(pc + 1, 0, n_phases - 1);
-        stage_entries(xlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, 0, a.rows_pad / 2, lane);
-    }
-    {
-        const PhaseId id1 = phase_of(min(it + 1, n_phases - 1), a.n_kv_heads);
-        issue_q_slice<NB>(q1, a, id1.layer, id1.kv, wave, lane);
-    }
-
-    // ---- probability pass of phase pc; second half of the loads of K(it+2) ----
-    if (do_prob) {
-        prob_pass<NB, GB>(ring.kf[(SLOT + 1) % kRing], q2, cinit, acc, hf, col, ki, kTileInstr / 2);
-        const PhaseId idc = phase_of(pc, a.n_kv_heads);
-        if (idc.kv == a.n_kv_heads - 1 && (a.layer_agg == SP_LAYER_MEAN || idc.layer == a.n_layers - 1))
-            close_layer<NB>(acc, a.c);
-    } else {
-        k_issue<kTileInstr / 2>(ki, kTileInstr / 2);
-    }
+    lds_barrier();
 }
 
 template <int NB, int GB>
 __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, LayerPtrs kp)
 {
-    __shared__ u32x4 kt0[kFTile * kCH];
-    __shared__ u32x4 kt1[kFTile * kCH];
-    __shared__ u32x4 q1[kMaxRowsF * kCH];
-    __shared__ u32x4 q2a[kMaxRowsF * kCH];
-    __shared__ u32x4 q2b[kMaxRowsF * kCH];
-    __shared__ float2 wstats[kFWaves][kMaxRowsF];
-    __shared__ float cinit2[2][kMaxRowsF];
+    __shared__ u32x4 kring[kFWaves * kSubSlots * kSubChunks];
+    __shared__ u32x4 q1a[kMaxRowsF * kCH], q1b[kMaxRowsF * kCH], q2a[kMaxRowsF * kCH], q2b[kMaxRowsF * kCH];
+    __shared__ float2 wstats[2][kFWaves][kMaxRowsF];
+    __shared__ float cinit[2][kMaxRowsF];
     __shared__ u32x4 xduty[128];             // partials of the duty row, 256 entries
     __shared__ u32x4 xlse[64];               // normaliser entries of one phase (64 used, the load moves 128)
     __shared__ int s_fail;
@@ -621,9 +634,13 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     const int64_t j0 = (int64_t)w * kFTile;
     const int n_valid = (int)((a.L - j0 < kFTile) ? a.L - j0 : kFTile);
 
-    if (tid < 2 * kMaxRowsF) cinit2[tid / kMaxRowsF][tid % kMaxRowsF] = neg_inf();
+    Shared sh;
+    sh.kring = kring;
+    sh.q1[0] = q1a; sh.q1[1] = q1b; sh.q2[0] = q2a; sh.q2[1] = q2b;
+    sh.wstats = wstats; sh.cinit = cinit; sh.xduty = xduty; sh.xlse = xlse; sh.fail = &s_fail;
+
+    if (tid < 2 * kMaxRowsF) cinit[tid / kMaxRowsF][tid % kMaxRowsF] = neg_inf();
     if (tid == 0) s_fail = 0;
-    lds_barrier();
 
     Ring ring;
     Acc<NB> acc;
@@ -636,32 +653,25 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
             for (int e = 0; e < 4; ++e) acc.mx[s][b][e] = neg_inf();
     }
 
-    // prologue: this wave's slice of Q(0), then its rows of K(0) and K(1)
-    issue_q_slice<NB>(q1, a, 0, 0, wave, lane);
-    {
-        KIssue ki;
-        ki.stride_bytes = (uint32_t)a.k_stride_token * 2u; ki.wave = wave; ki.lane = lane;
-        ki.tile = kt0; ki.base = kp.p[0] + j0 * a.k_stride_token; ki.n_valid = n_valid;
-        k_issue<kTileInstr>(ki, 0);
-        const PhaseId id = phase_of(min(1, n_phases - 1), a.n_kv_heads);
-        ki.tile = kt1; ki.base = kp.p[id.layer] + (int64_t)id.kv * a.k_stride_head + j0 * a.k_stride_token;
-        ki.n_valid = n_phases > 1 ? n_valid : 1;
-        k_issue<kTileInstr>(ki, 0);
+    // prologue: this wave's slice of Q(0) and both sub-tiles of K(0); everything lands before step 0
+    issue_q_slice<NB>(q1a, a, 0, 0, wave, lane);
+#pragma unroll
+    for (int s2 = 0; s2 < kNS; ++s2) {
+        const KIssue ki = k_issue_setup(a, kp, kring, 0, s2, n_phases, n_valid, wave, lane);
+        k_issue<kSubInstr>(ki, 0);
     }
+    vm_wait<0>();
+    lds_barrier();
 
-    // The body is unrolled four times so that the ring slot (it % 4) and the transit buffer (it % 2)
-    // are compile-time; the trip count is rounded up, surplus iterations do no work but keep the
-    // instruction stream uniform.
-    const int n_iter = (n_phases + kLag + 3) / 4 * 4;
-    for (int it0 = 0; it0 < n_iter; it0 += 4) {
-#define SP_ITER(SLOT, BUF, OFF)                                                                               \
-        iteration<NB, GB, SLOT, BUF>(a, kp, it0 + OFF, n_phases, ring, acc, xduty, xlse, kt0, kt1, q1, q2a, q2b,     \
-                                     wstats, cinit2, &s_fail, n_valid);
-        SP_ITER(0, 0, 0)
-        SP_ITER(1, 1, 1)
-        SP_ITER(2, 0, 2)
-        SP_ITER(3, 1, 3)
-#undef SP_ITER
+    // The body is unrolled four times so that the fragment ring slot (s % 4) and the buffer parity
+    // (s % 2) are compile-time; the trip count is rounded up, surplus steps do no work but keep the
+    // instruction stream uniform. The last probability pass (phase n_phases - 1) runs in step n_phases + 3.
+    const int n_steps = (n_phases + kLag + 1 + 3) / 4 * 4;
+    for (int s0 = 0; s0 < n_steps; s0 += 4) {
+        step<NB, GB, 0, 0>(a, kp, s0 + 0, n_phases, ring, acc, sh, n_valid);
+        step<NB, GB, 1, 1>(a, kp, s0 + 1, n_phases, ring, acc, sh, n_valid);
+        step<NB, GB, 2, 0>(a, kp, s0 + 2, n_phases, ring, acc, sh, n_valid);
+        step<NB, GB, 3, 1>(a, kp, s0 + 3, n_phases, ring, acc, sh, n_valid);
     }
     vm_wait<0>();               // no direct-to-LDS load may outlive the workgroup
     lds_barrier();
