@@ -60,7 +60,9 @@ constexpr int kRing = kLag + 1;           // fragment ring: four phases
 constexpr int kSlots = sp_fused::kSlots;  // exchange ring depth
 constexpr int kMaxRowsF = sp_fused::kMaxRows;   // 64 padded query rows per kv head
 constexpr unsigned kSpinMax = 1u << 20;    // polls before a wait gives up (about a second)
-constexpr int kDutyWave = 1;               // the wave that combines this workgroup's duty row
+constexpr int kPubWave = 0;                // the wave that publishes this workgroup's partials
+constexpr int kDutyWave = 1;               // the wave that combines this workgroup's duty rows
+constexpr int kDutyRows = 4;               // consecutive query rows one duty covers (32 bytes per source workgroup)
 constexpr int kLseWave = 2;                // the wave that fetches the normalisers
 
 #define SP_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -396,23 +398,39 @@ __device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS]
 }
 
 // Exchange data requested with direct-to-LDS loads lands in two small staging areas, each private
-// to one wave: xduty holds the n_wg partials of the duty row (entry e at byte 8e), xlse the
-// normaliser entries of one phase.
-struct DutyEntries { uint64_t e[4]; };     // entries lane, lane + 64, lane + 128, lane + 192
+// to one wave. Partials are stored workgroup-major, part[slot][workgroup][row], so that a workgroup
+// publishes all its rows with one contiguous store; a duty covers kDutyRows consecutive rows, i.e.
+// one 32-byte piece of every workgroup's line. xduty receives them as 16-byte pairs of rows:
+// chunk (2q + h) * 64 + lane holds rows 2h and 2h+1 of the block from workgroup lane + 64q.
+struct DutyBlock { uint64_t e[kDutyRows][4]; };     // [row of the block][workgroup lane + 64q]
 
-__device__ __forceinline__ DutyEntries read_duty_staging(const u32x4 *xduty, int lane)
+__device__ __forceinline__ DutyBlock read_duty_staging(const u32x4 *xduty, int lane)
 {
-    const uint32_t ad = lds_addr(xduty) + 8u * (uint32_t)lane;
-    DutyEntries d;
+    static_assert(kDutyRows == 4, "layout of the asm block");
+    typedef __attribute__((ext_vector_type(2))) uint64_t u64x2;
+    const uint32_t ad = lds_addr(xduty) + 16u * (uint32_t)lane;
+    u64x2 r[8];
     __asm__ volatile(
-        "ds_read_b64 %0, %4\n\t"
-        "ds_read_b64 %1, %4 offset:512\n\t"
-        "ds_read_b64 %2, %4 offset:1024\n\t"
-        "ds_read_b64 %3, %4 offset:1536\n\t"
+        "ds_read_b128 %0, %8\n\t"
+        "ds_read_b128 %1, %8 offset:1024\n\t"
+        "ds_read_b128 %2, %8 offset:2048\n\t"
+        "ds_read_b128 %3, %8 offset:3072\n\t"
+        "ds_read_b128 %4, %8 offset:4096\n\t"
+        "ds_read_b128 %5, %8 offset:5120\n\t"
+        "ds_read_b128 %6, %8 offset:6144\n\t"
+        "ds_read_b128 %7, %8 offset:7168\n\t"
         "s_waitcnt lgkmcnt(0)"
-        : "=&v"(d.e[0]), "=&v"(d.e[1]), "=&v"(d.e[2]), "=&v"(d.e[3])
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7])
         : "v"(ad)
         : "memory");
+    DutyBlock d;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            d.e[2 * h][q] = r[2 * q + h].x;
+            d.e[2 * h + 1][q] = r[2 * q + h].y;
+        }
     return d;
 }
 
@@ -424,32 +442,49 @@ __device__ __forceinline__ uint64_t read_lse_staging(const u32x4 *xlse, int lane
     return v;
 }
 
-// Direct-to-LDS load of 64 x 16 bytes: the 16-byte pairs first .. first+63 of a row of 8-byte
-// entries (row 16-byte aligned) that holds `pairs` pairs; lanes beyond the row repeat its last pair.
-// The load bypasses the non-coherent cache levels like the atomic loads of the retry paths do.
-__device__ __forceinline__ void stage_entries(u32x4 *dst, const uint64_t *row, int first, int pairs, int lane)
+// Direct-to-LDS loads bypass the non-coherent cache levels like the atomic loads of the retry paths do.
+constexpr int kDeviceScope = 16;          // the sc1 bit of the cache-policy operand
+
+// 64 x 16 bytes: the 16-byte pairs 0 .. 63 of a row of 8-byte entries (row 16-byte aligned) that
+// holds `pairs` pairs; lanes beyond the row repeat its last pair.
+__device__ __forceinline__ void stage_entries(u32x4 *dst, const uint64_t *row, int pairs, int lane)
 {
-    constexpr int kDeviceScope = 16;      // the sc1 bit of the cache-policy operand
-    const uint64_t *p = row + 2 * min(first + lane, pairs - 1);
+    const uint64_t *p = row + 2 * min(lane, pairs - 1);
     __builtin_amdgcn_global_load_lds(SP_GPTR(p), SP_LPTR(dst), 16, 0, kDeviceScope);
 }
 
-// A partial is ready when it carries the parity of this use of its slot and a non-zero sum.
-// Entries beyond the last workgroup do not exist and count as ready.
-__device__ __forceinline__ bool duty_ready(const DutyEntries &d, uint32_t par, int lane, int n_wg)
+// The partials of rows row0 .. row0+3 of one exchange slot from every workgroup: eight loads.
+__device__ __forceinline__ void stage_duty_block(u32x4 *xduty, const uint64_t *slot_base, int rows_pad, int n_wg,
+                                                 int row0, int lane)
 {
-    uint32_t ok = 1u;           // branch-free: one straight-line test of the four entries
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-        ok &= (uint32_t)(lane + 64 * q >= n_wg) |
-              ((uint32_t)((uint32_t)(d.e[q] >> 63) == par) & (uint32_t)(((d.e[q] >> 32) & 0x7fffffffu) != 0));
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint64_t *p = slot_base + (size_t)min(lane + 64 * q, n_wg - 1) * rows_pad + row0 + 2 * h;
+            __builtin_amdgcn_global_load_lds(SP_GPTR(p), SP_LPTR(xduty + (2 * q + h) * 64), 16, 0, kDeviceScope);
+        }
+}
+
+// A partial is ready when it carries the parity of this use of its slot and a non-zero sum.
+// Entries beyond the last workgroup do not exist, rows outside the mask are padding: both count as ready.
+__device__ __forceinline__ bool duty_ready(const DutyBlock &d, uint32_t par, int lane, int n_wg, uint32_t row_mask)
+{
+    uint32_t ok = 1u;           // branch-free: one straight-line test of the sixteen entries
+#pragma unroll
+    for (int r = 0; r < kDutyRows; ++r)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            ok &= (uint32_t)(lane + 64 * q >= n_wg) | (((row_mask >> r) & 1u) ^ 1u) |
+                  ((uint32_t)((uint32_t)(d.e[r][q] >> 63) == par) & (uint32_t)(((d.e[r][q] >> 32) & 0x7fffffffu) != 0));
     return ok != 0;
 }
 
-// Row of phase p that workgroup w combines (>= rows_pad: none). Rows rotate over the workgroups.
-__device__ __forceinline__ int duty_row_of(const FusedArgs &a, int p, int w)
+// Block of kDutyRows rows of phase p that workgroup w combines (>= rows_pad / kDutyRows: none).
+// Blocks rotate over the workgroups.
+__device__ __forceinline__ int duty_block_of(const FusedArgs &a, int p, int w)
 {
-    const int first = (int)(((uint32_t)p * (uint32_t)a.rows_pad) % (uint32_t)a.n_wg);
+    const int first = (int)(((uint32_t)p * (uint32_t)(a.rows_pad / kDutyRows)) % (uint32_t)a.n_wg);
     const int r = w - first;
     return r < 0 ? r + a.n_wg : r;
 }
@@ -496,26 +531,51 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
     const bool do_stats = s < n_phases, do_prob = pc >= 0 && pc < n_phases;
 
     // ---- mid ----
-    if (pp >= 0 && pp < n_phases) {
-        // every wave combines the eight per-wave statistics of eight rows (lane = row x source wave)
-        // and publishes them: maximum first, then one exponential per source
-        const int row = wave * 8 + (lane >> 3);
-        const float2 st = lds_load_f2(&sh.wstats[1 - PAR][lane & 7][row]);
-        const float m = group8_max(st.x);
-        const float l = group8_sum(st.y * fast_exp2((st.x - m) * a.c));
-        int g, n;
-        if ((lane & 7) == 0 && row < a.rows_pad && row_valid<NB>(a, row, g, n)) {
-            const uint64_t bits = (uint64_t)__float_as_uint(m) | ((uint64_t)__float_as_uint(l) << 32) |
-                                  ((uint64_t)((pp / kSlots) & 1) << 63);
-            st64(a.part + ((size_t)(pp % kSlots) * a.rows_pad + row) * a.part_stride + w, bits);
+    if (wave == kPubWave) {
+        if (pp >= 0 && pp < n_phases) {
+            // one wave combines the eight per-wave statistics of every row (lane = row), maximum first,
+            // then one exponential per source, and publishes the rows with one contiguous store
+            float pm[kFWaves], pl8[kFWaves];
+            {
+                typedef __attribute__((ext_vector_type(2))) float f32x2;
+                const uint32_t ad = lds_addr(&sh.wstats[1 - PAR][0][lane]);
+                f32x2 r[kFWaves];
+                static_assert(kFWaves == 8 && sizeof(float2) * kMaxRowsF == 512, "layout of the asm block");
+                __asm__ volatile(
+                    "ds_read_b64 %0, %8\n\t"
+                    "ds_read_b64 %1, %8 offset:512\n\t"
+                    "ds_read_b64 %2, %8 offset:1024\n\t"
+                    "ds_read_b64 %3, %8 offset:1536\n\t"
+                    "ds_read_b64 %4, %8 offset:2048\n\t"
+                    "ds_read_b64 %5, %8 offset:2560\n\t"
+                    "ds_read_b64 %6, %8 offset:3072\n\t"
+                    "ds_read_b64 %7, %8 offset:3584\n\t"
+                    "s_waitcnt lgkmcnt(0)"
+                    : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7])
+                    : "v"(ad)
+                    : "memory");
+#pragma unroll
+                for (int i = 0; i < kFWaves; ++i) { pm[i] = r[i].x; pl8[i] = r[i].y; }
+            }
+            float m = pm[0];
+#pragma unroll
+            for (int i = 1; i < kFWaves; ++i) m = fmaxf(m, pm[i]);
+            float l = 0.f;
+#pragma unroll
+            for (int i = 0; i < kFWaves; ++i) l += pl8[i] * fast_exp2((pm[i] - m) * a.c);
+            if (lane < a.rows_pad) {
+                const uint64_t bits = (uint64_t)__float_as_uint(m) | ((uint64_t)__float_as_uint(l) << 32) |
+                                      ((uint64_t)((pp / kSlots) & 1) << 63);
+                st64(a.part + ((size_t)(pp % kSlots) * a.n_wg + w) * a.rows_pad + lane, bits);
+            }
         }
-    }
-    if (wave == kDutyWave) {
-        const int pn = clampi(pd, 0, n_phases - 1);
-        const int r = min(duty_row_of(a, pn, w), a.rows_pad - 1);
-        const uint64_t *src = a.part + ((size_t)(pn % kSlots) * a.rows_pad + r) * a.part_stride;
-        stage_entries(sh.xduty, src, 0, a.part_stride / 2, lane);
-        stage_entries(sh.xduty + 64, src, 64, a.part_stride / 2, lane);
+    } else if (wave == kDutyWave) {
+        if (pd >= 0 && pd < n_phases) {
+            const int blk = duty_block_of(a, pd, w);
+            if (blk < a.rows_pad / kDutyRows)
+                stage_duty_block(sh.xduty, a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad, a.rows_pad, a.n_wg,
+                                 blk * kDutyRows, lane);
+        }
     }
     {
         const PhaseId id1 = phase_of(min(s + 1, n_phases - 1), a.n_kv_heads);
@@ -538,7 +598,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
     }
     if (wave == kLseWave) {
         const int pn = clampi(pl, 0, n_phases - 1);
-        stage_entries(sh.xlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, 0, a.rows_pad / 2, lane);
+        stage_entries(sh.xlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, a.rows_pad / 2, lane);
     }
 
     // ---- lift K(s), statistics pass of phase s; sub-tile 1 of K(s+1) ----
@@ -558,40 +618,54 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
     if (wave == kLseWave) vm_wait<kSubInstr>(); else vm_wait<2 * kSubInstr>();
     if (wave == kDutyWave) {
         if (pd >= 0 && pd < n_phases) {
-            const int duty_row = duty_row_of(a, pd, w);
-            int g, n;
-            if (duty_row < a.rows_pad && row_valid<NB>(a, duty_row, g, n)) {
+            const int blk = duty_block_of(a, pd, w);
+            uint32_t row_mask = 0;
+            if (blk < a.rows_pad / kDutyRows) {
+#pragma unroll
+                for (int r = 0; r < kDutyRows; ++r) {
+                    int g, n;
+                    if (row_valid<NB>(a, blk * kDutyRows + r, g, n)) row_mask |= 1u << r;
+                }
+            }
+            if (row_mask != 0) {
                 const uint32_t par = (uint32_t)(pd / kSlots) & 1u;
-                const uint64_t *src = a.part + ((size_t)(pd % kSlots) * a.rows_pad + duty_row) * a.part_stride;
+                const uint64_t *src = a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad + blk * kDutyRows;
                 // fast path: the partials requested at the start of this step are all there; otherwise poll (bounded)
-                DutyEntries de = read_duty_staging(sh.xduty, lane);
-                if (__any(!duty_ready(de, par, lane, a.n_wg)) && *sh.fail == 0) {
+                DutyBlock de = read_duty_staging(sh.xduty, lane);
+                if (__any(!duty_ready(de, par, lane, a.n_wg, row_mask)) && *sh.fail == 0) {
                     unsigned spins = 0;
                     do {
                         if (++spins > kSpinMax) { *sh.fail = 1; break; }
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) de.e[q] = ld64(src + min(lane + 64 * q, a.n_wg - 1));
-                    } while (__any(!duty_ready(de, par, lane, a.n_wg)));
-                }
-                // maximum first, then one exponential per partial: short dependency chains, fixed order
-                float pm[4], pl4[4], m = neg_inf();
+                        for (int r = 0; r < kDutyRows; ++r)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const bool valid = lane + 64 * q < a.n_wg;
-                    pm[q] = valid ? __uint_as_float((uint32_t)de.e[q]) : neg_inf();
-                    pl4[q] = valid ? __uint_as_float((uint32_t)(de.e[q] >> 32) & 0x7fffffffu) : 0.f;
-                    m = fmaxf(m, pm[q]);
+                            for (int q = 0; q < 4; ++q)
+                                de.e[r][q] = ld64(src + (size_t)min(lane + 64 * q, a.n_wg - 1) * a.rows_pad + r);
+                    } while (__any(!duty_ready(de, par, lane, a.n_wg, row_mask)));
                 }
-                m = wave_max(m);
-                float l = 0.f;
+                // per row: maximum first, then one exponential per partial (short dependency chains, fixed order)
+                float mine = 0.f;       // lane r keeps the normaliser of row r of the block
 #pragma unroll
-                for (int q = 0; q < 4; ++q) l += pl4[q] * fast_exp2((pm[q] - m) * a.c);
-                l = wave_sum(l);
-                if (lane == 0) {
+                for (int r = 0; r < kDutyRows; ++r) {
+                    float pm[4], pl4[4], m = neg_inf();
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const bool valid = lane + 64 * q < a.n_wg;
+                        pm[q] = valid ? __uint_as_float((uint32_t)de.e[r][q]) : neg_inf();
+                        pl4[q] = valid ? __uint_as_float((uint32_t)(de.e[r][q] >> 32) & 0x7fffffffu) : 0.f;
+                        m = fmaxf(m, pm[q]);
+                    }
+                    m = wave_max(m);
+                    float l = 0.f;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) l += pl4[q] * fast_exp2((pm[q] - m) * a.c);
+                    l = wave_sum(l);
                     const float v = -(m + fast_log2(l) * a.inv_c);
-                    st64(a.lse + (size_t)(pd % kSlots) * a.rows_pad + duty_row,
-                         (uint64_t)__float_as_uint(v) | ((uint64_t)(uint32_t)(pd + 1) << 32));
+                    if (lane == r) mine = v;
                 }
+                if (lane < kDutyRows && ((row_mask >> lane) & 1u))
+                    st64(a.lse + (size_t)(pd % kSlots) * a.rows_pad + blk * kDutyRows + lane,
+                         (uint64_t)__float_as_uint(mine) | ((uint64_t)(uint32_t)(pd + 1) << 32));
             }
         }
     } else if (wave == kLseWave) {
@@ -624,7 +698,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     __shared__ u32x4 q1a[kMaxRowsF * kCH], q1b[kMaxRowsF * kCH], q2a[kMaxRowsF * kCH], q2b[kMaxRowsF * kCH];
     __shared__ float2 wstats[2][kFWaves][kMaxRowsF];
     __shared__ float cinit[2][kMaxRowsF];
-    __shared__ u32x4 xduty[128];             // partials of the duty row, 256 entries
+    __shared__ u32x4 xduty[8 * 64];          // partials of the duty rows: 4 rows x 256 workgroups
     __shared__ u32x4 xlse[64];               // normaliser entries of one phase (64 used, the load moves 128)
     __shared__ int s_fail;
 
@@ -696,12 +770,9 @@ __global__ void sp_fused_clear_kernel(uint64_t *p, size_t n)
 
 namespace sp_fused {
 
-// Rows of partials start on 16-byte boundaries.
-static int part_stride(int n_wg) { return (n_wg + 1) & ~1; }
-
 size_t workspace_bytes(int rows_pad, int n_wg)
 {
-    return sp::align_up(sizeof(uint64_t) * ((size_t)kSlots * rows_pad * part_stride(n_wg) + (size_t)kSlots * rows_pad + 32), 256);
+    return sp::align_up(sizeof(uint64_t) * ((size_t)kSlots * rows_pad * n_wg + (size_t)kSlots * rows_pad + 32), 256);
 }
 
 bool fits_one_per_cu()
@@ -715,8 +786,7 @@ bool fits_one_per_cu()
 sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, hipStream_t st)
 {
     uint64_t *base = static_cast<uint64_t *>(ws);
-    a.part_stride = part_stride(a.n_wg);
-    const size_t n_part = (size_t)kSlots * a.rows_pad * a.part_stride, n_lse = (size_t)kSlots * a.rows_pad;
+    const size_t n_part = (size_t)kSlots * a.rows_pad * a.n_wg, n_lse = (size_t)kSlots * a.rows_pad;
     a.part = base;
     a.lse = base + n_part;
     a.err = reinterpret_cast<uint32_t *>(base + n_part + n_lse);

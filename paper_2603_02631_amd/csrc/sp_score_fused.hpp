@@ -15,13 +15,12 @@ struct FusedArgs {
     const uint16_t *q;           // [Lyr][H][n_q][64]
     int64_t k_stride_token, k_stride_head;
     int64_t L;
-    uint64_t *part;              // [kSlots][rows_pad][part_stride]  (max, sum exp) partials, parity in bit 63
+    uint64_t *part;              // [kSlots][n_wg][rows_pad]  (max, sum exp) partials, parity in bit 63
     uint64_t *lse;               // [kSlots][rows_pad]        (-lse, phase + 1)
     uint32_t *err;
     const uint64_t *zeros;       // 128 zero bytes (source of padding query rows)
     float *scores;
     int32_t n_wg;
-    int32_t part_stride;         // n_wg rounded up to even (set by launch)
     int32_t n_layers, n_q_heads, n_kv_heads, group, n_q;
     int32_t n_nblk, n_gblk, rows_pad;
     int32_t layer_agg;
