@@ -46,7 +46,6 @@ using namespace sp_dev;
 using sp_fused::FusedArgs;
 
 constexpr int kD = 64;
-constexpr int kCH = kD / 8;               // 16-byte chunks per key row
 constexpr int kKS = kD / 16;              // MFMA k-steps per row
 constexpr int kFWaves = 8;
 constexpr int kFThreads = kFWaves * 64;
@@ -54,7 +53,6 @@ constexpr int kNS = 2;                    // 32-key sub-tiles per wave
 constexpr int kFTile = sp_fused::kTileKeys;   // 512 keys per workgroup per phase
 constexpr int kSubInstr = 4;              // tile-load instructions per sub-tile (8 rows, 1 KB each)
 constexpr int kSubSlots = 3;              // sub-tile slots in a wave's transit ring
-constexpr int kSubChunks = 32 * kCH;      // 16-byte chunks per sub-tile slot
 constexpr int kLag = 3;                   // phases between statistics and probability pass
 constexpr int kRing = kLag + 1;           // fragment ring: four phases
 constexpr int kSlots = sp_fused::kSlots;  // exchange ring depth
@@ -64,6 +62,22 @@ constexpr int kPubWave = 0;                // the wave that publishes this workg
 constexpr int kDutyWave = 1;               // the wave that combines this workgroup's duty rows
 constexpr int kDutyRows = 4;               // consecutive query rows one duty covers (32 bytes per source workgroup)
 constexpr int kLseWave = 2;                // the wave that fetches the normalisers
+
+// LDS map in bytes. Everything but the K transit ring sits below 64 KB, so that reads of it can
+// carry the buffer's place in the instruction's offset field.
+constexpr int kQTileBytes = kMaxRowsF * kD * 2;                    // one Q tile: 64 rows x 128 bytes
+constexpr int kOffQ1 = 0;                                          // [2] Q of the statistics pass, by phase parity
+constexpr int kOffQ2 = kOffQ1 + 2 * kQTileBytes;                   // [2] Q of the probability pass
+constexpr int kWstatsBytes = kFWaves * kMaxRowsF * 8;              // (max, sum) of 64 rows from 8 waves
+constexpr int kOffWstats = kOffQ2 + 2 * kQTileBytes;               // [2]
+constexpr int kOffCinit = kOffWstats + 2 * kWstatsBytes;           // [2][64] accumulator seeds
+constexpr int kOffXduty = kOffCinit + 2 * kMaxRowsF * 4;           // 8 KB: partials of the duty rows
+constexpr int kOffXlse = kOffXduty + 8192;                         // 1 KB: normaliser entries of one phase
+constexpr int kOffFail = kOffXlse + 1024;
+constexpr int kOffKring = (kOffFail + 16 + 1023) / 1024 * 1024;    // [8 waves][3 slots][32 rows x 128 bytes]
+constexpr int kSubBytes = 32 * kD * 2;
+constexpr int kLdsBytes = kOffKring + kFWaves * kSubSlots * kSubBytes;
+static_assert(kOffKring < 65536, "offset fields hold 16 bits");
 
 #define SP_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define SP_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -104,21 +118,45 @@ struct Ring {
     bf16x8 kf[kRing][kNS][kKS];           // K fragments of the phases in flight
 };
 
+// Values that depend on the lane only, computed once: they cost a few registers and save the
+// address arithmetic of every load and lift.
+struct LaneConst {
+    uint32_t ld[kKS];       // LDS byte address of this lane's fragment chunk t in a tile at LDS offset 0
+    uint32_t koff[2];       // byte offset of this lane's chunk in an even / odd tile-load instruction (full tiles)
+    int32_t qoff;           // byte offset of this lane's chunk of its wave's Q slice in a (layer, kv head) block; < 0: padding
+};
+
 // All LDS traffic of the main loop is written as asm: the compiler cannot tell which in-flight
 // direct-to-LDS load targets which buffer and would put a full vector-memory wait in front of
 // LDS accesses it can see. The kernel waits (vm_wait, barrier) for exactly what it is about to read.
 __device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(p)); }
 
-// MFMA fragments of 32 rows of a swizzled 64-wide bf16 tile: lane (col, hf) takes row `row`,
-// 16-byte chunks 2t + hf.
-__device__ __forceinline__ void lift_block(const u32x4 *tile, int row, int hf, bf16x8 (&f)[kKS])
+// MFMA fragments of 32 rows of a swizzled 64-wide bf16 tile at compile-time LDS offset OFF:
+// lane (col, hf) takes row col, 16-byte chunks 2t + hf.
+template <int OFF>
+__device__ __forceinline__ void lift_at(const LaneConst &lc, bf16x8 (&f)[kKS])
 {
-    static_assert(kKS == 4, "layout of the asm block");
-    const uint32_t base = lds_addr(tile);
+    static_assert(kKS == 4 && OFF >= 0 && OFF < 65536, "layout of the asm block");
+    u32x4 r[kKS];
+    __asm__ volatile(
+        "ds_read_b128 %0, %4 offset:%8\n\t"
+        "ds_read_b128 %1, %5 offset:%8\n\t"
+        "ds_read_b128 %2, %6 offset:%8\n\t"
+        "ds_read_b128 %3, %7 offset:%8\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
+        : "v"(lc.ld[0]), "v"(lc.ld[1]), "v"(lc.ld[2]), "v"(lc.ld[3]), "i"(OFF)
+        : "memory");
+#pragma unroll
+    for (int t = 0; t < kKS; ++t) f[t] = __builtin_bit_cast(bf16x8, r[t]);
+}
+// The same at a run-time (uniform) LDS offset.
+__device__ __forceinline__ void lift_dyn(const LaneConst &lc, uint32_t off, bf16x8 (&f)[kKS])
+{
+    u32x4 r[kKS];
     uint32_t ad[kKS];
 #pragma unroll
-    for (int t = 0; t < kKS; ++t) ad[t] = base + 16u * (uint32_t)lds_slot<kD>(row, 2 * t + hf);
-    u32x4 r[kKS];
+    for (int t = 0; t < kKS; ++t) ad[t] = lc.ld[t] + off;
     __asm__ volatile(
         "ds_read_b128 %0, %4\n\t"
         "ds_read_b128 %1, %5\n\t"
@@ -132,25 +170,18 @@ __device__ __forceinline__ void lift_block(const u32x4 *tile, int row, int hf, b
     for (int t = 0; t < kKS; ++t) f[t] = __builtin_bit_cast(bf16x8, r[t]);
 }
 
-__device__ __forceinline__ void lds_store_f32(float *p, float v)
+__device__ __forceinline__ void lds_store_f32(uint32_t ad, float v)
 {
-    __asm__ volatile("ds_write_b32 %0, %1" : : "v"(lds_addr(p)), "v"(v) : "memory");
+    __asm__ volatile("ds_write_b32 %0, %1" : : "v"(ad), "v"(v) : "memory");
 }
-__device__ __forceinline__ void lds_store_f2(float2 *p, float2 v)
+__device__ __forceinline__ void lds_store_f2(uint32_t ad, float2 v)
 {
-    __asm__ volatile("ds_write_b64 %0, %1" : : "v"(lds_addr(p)), "v"(v) : "memory");
-}
-__device__ __forceinline__ float2 lds_load_f2(const float2 *p)
-{
-    float2 v;
-    __asm__ volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(lds_addr(p)) : "memory");
-    return v;
+    __asm__ volatile("ds_write_b64 %0, %1" : : "v"(ad), "v"(v) : "memory");
 }
 // Sixteen consecutive floats (64-byte aligned).
-__device__ __forceinline__ f32x16 lds_load_f16(const float *p)
+__device__ __forceinline__ f32x16 lds_load_f16(uint32_t ad)
 {
     typedef __attribute__((ext_vector_type(4))) float f32x4;
-    const uint32_t ad = lds_addr(p);
     f32x4 r[4];
     __asm__ volatile(
         "ds_read_b128 %0, %4\n\t"
@@ -180,37 +211,41 @@ constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141;   // lane i <- lane 7 - i within groups of 8
 constexpr int kDppMirror = 0x140;       // lane i <- lane 15 - i within rows of 16
 
-__device__ __forceinline__ float group8_max(float v)
-{
-    v = fmaxf(v, dpp_move<kDppXor1>(v));
-    v = fmaxf(v, dpp_move<kDppXor2>(v));
-    return fmaxf(v, dpp_move<kDppHalfMirror>(v));
-}
-__device__ __forceinline__ float group8_sum(float v)
-{
-    v += dpp_move<kDppXor1>(v);
-    v += dpp_move<kDppXor2>(v);
-    return v + dpp_move<kDppHalfMirror>(v);
-}
 __device__ __forceinline__ float lane_value(float v, int lane)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
 __device__ __forceinline__ float wave_max(float v)
 {
-    v = group8_max(v);
+    v = fmaxf(v, dpp_move<kDppXor1>(v));
+    v = fmaxf(v, dpp_move<kDppXor2>(v));
+    v = fmaxf(v, dpp_move<kDppHalfMirror>(v));
     v = fmaxf(v, dpp_move<kDppMirror>(v));
     return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
 __device__ __forceinline__ float wave_sum(float v)
 {
-    v = group8_sum(v);
+    v += dpp_move<kDppXor1>(v);
+    v += dpp_move<kDppXor2>(v);
+    v += dpp_move<kDppHalfMirror>(v);
     v += dpp_move<kDppMirror>(v);
     return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
 
-struct PhaseId { int layer, kv; };
-__device__ __forceinline__ PhaseId phase_of(int p, int n_kv) { PhaseId r; r.layer = p / n_kv; r.kv = p - r.layer * n_kv; return r; }
+// (layer, kv head) of a phase, walked step by step instead of divided out every time.
+struct PhaseCtr { int layer, kv; };
+__device__ __forceinline__ PhaseCtr phase_at(int p, int n_phases, int n_kv)
+{
+    p = clampi(p, 0, n_phases - 1);
+    PhaseCtr r; r.layer = p / n_kv; r.kv = p - r.layer * n_kv; return r;
+}
+// c holds clamp(p_next - 1, 0, n_phases - 1); make it hold clamp(p_next, 0, n_phases - 1).
+__device__ __forceinline__ void phase_advance(PhaseCtr &c, int p_next, int n_phases, int n_kv)
+{
+    if (p_next > 0 && p_next < n_phases) {
+        if (++c.kv == n_kv) { c.kv = 0; ++c.layer; }
+    }
+}
 
 // padded query row -> (group head, lookahead row); see the row order in sp_score.hip
 template <int NB>
@@ -225,65 +260,42 @@ __device__ __forceinline__ bool row_valid(const FusedArgs &a, int row, int &g, i
 
 // One wave instruction moves 64 chunks = 8 key rows (1 KB, contiguous in HBM when keys are
 // contiguous); a 32-key sub-tile takes four of them. The address is a uniform base plus a 32-bit
-// per-lane byte offset, so no address registers stay live between instructions.
+// per-lane byte offset.
 struct KIssue {
-    u32x4 *slot;              // sub-tile slot being refilled (this wave's)
-    const uint16_t *base;     // first key of this workgroup in the (layer, kv head) being fetched (uniform)
+    unsigned char *slot;      // LDS sub-tile slot being refilled (this wave's)
+    const char *base;         // first key of the sub-tile in the (layer, kv head) being fetched (uniform)
     uint32_t stride_bytes;    // bytes between consecutive keys
-    int row0;                 // first key of the sub-tile within the workgroup's tile
-    int n_valid, lane;
+    int n_left;               // valid keys from the sub-tile's first key on (>= 32: all of them)
 };
 
 // Issues instructions first .. first+COUNT-1 of the sub-tile (first and COUNT compile-time at call sites).
 template <int COUNT>
-__device__ __forceinline__ void k_issue(const KIssue &ki, int first)
+__device__ __forceinline__ void k_issue(const KIssue &ki, const LaneConst &lc, int lane, int first)
 {
+    if (ki.n_left >= 32) {
 #pragma unroll
-    for (int i = 0; i < COUNT; ++i) {
-        const int idx = first + i;
-        const int r = 8 * idx + (ki.lane >> 3);               // row within the sub-tile
-        const uint32_t chunk = (uint32_t)((ki.lane & 7) ^ ((r >> 1) & 7));
-        int row = ki.row0 + r;
-        row = row < ki.n_valid ? row : ki.n_valid - 1;        // tail rows repeat the last valid key
-        const uint32_t off = (uint32_t)row * ki.stride_bytes + chunk * 16u;
-        const char *src = reinterpret_cast<const char *>(ki.base) + off;
-        __builtin_amdgcn_global_load_lds(SP_GPTR(src), SP_LPTR(ki.slot + 8 * idx * kCH), 16, 0, 0);
+        for (int i = 0; i < COUNT; ++i) {
+            const int idx = first + i;
+            const char *src = ki.base + (uint32_t)(8 * idx) * ki.stride_bytes + lc.koff[idx & 1];
+            __builtin_amdgcn_global_load_lds(SP_GPTR(src), SP_LPTR(ki.slot + idx * 1024), 16, 0, 0);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < COUNT; ++i) {
+            const int idx = first + i;
+            int r = 8 * idx + (lane >> 3);                        // row within the sub-tile
+            const uint32_t chunk = (uint32_t)((lane & 7) ^ ((r >> 1) & 7));
+            r = min(r, max(ki.n_left, 1) - 1);                    // rows past the end repeat the last valid key
+            const char *src = ki.base + (uint32_t)r * ki.stride_bytes + chunk * 16u;
+            __builtin_amdgcn_global_load_lds(SP_GPTR(src), SP_LPTR(ki.slot + idx * 1024), 16, 0, 0);
+        }
     }
 }
 
 // Sub-tile s2 of phase p lives in slot (2p + s2) mod 3 of its wave's transit ring.
-__device__ __forceinline__ u32x4 *sub_slot(u32x4 *kring, int wave, int p, int s2)
+__device__ __forceinline__ uint32_t sub_slot_off(int wave, int p, int s2)
 {
-    return kring + (wave * kSubSlots + (2 * p + s2) % kSubSlots) * kSubChunks;
-}
-
-__device__ __forceinline__ KIssue k_issue_setup(const FusedArgs &a, const LayerPtrs &kp, u32x4 *kring, int p, int s2,
-                                                int n_phases, int n_valid, int wave, int lane)
-{
-    const PhaseId id = phase_of(min(p, n_phases - 1), a.n_kv_heads);
-    KIssue ki;
-    ki.slot = sub_slot(kring, wave, p, s2);
-    ki.base = kp.p[id.layer] + (int64_t)id.kv * a.k_stride_head + (int64_t)blockIdx.x * kFTile * a.k_stride_token;
-    ki.stride_bytes = (uint32_t)a.k_stride_token * 2u;
-    ki.row0 = wave * 64 + s2 * 32;
-    ki.n_valid = p < n_phases ? n_valid : 1;      // past the last phase: a one-row dummy keeps the count fixed
-    ki.lane = lane;
-    return ki;
-}
-
-// Each wave loads eight rows (one instruction) of a Q tile of one (layer, kv head), in the padded
-// row order; padding rows read a zero line kept in the workspace.
-template <int NB>
-__device__ __forceinline__ void issue_q_slice(u32x4 *qt, const FusedArgs &a, int layer, int kv, int wave, int lane)
-{
-    const int row = wave * 8 + (lane >> 3);
-    int g, n;
-    const uint16_t *src = reinterpret_cast<const uint16_t *>(a.zeros) + (lane & 7) * 8;
-    if (row < a.rows_pad && row_valid<NB>(a, row, g, n)) {
-        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
-        src = a.q + ((((int64_t)layer * a.n_q_heads + (int64_t)kv * a.group + g) * a.n_q + n) * kD) + chunk * 8;
-    }
-    __builtin_amdgcn_global_load_lds(SP_GPTR(src), SP_LPTR(qt + wave * 64), 16, 0, 0);
+    return (uint32_t)(kOffKring + (wave * kSubSlots + (2 * p + s2) % kSubSlots) * kSubBytes);
 }
 
 template <int NB>
@@ -293,9 +305,9 @@ struct Acc {
 };
 
 // ---- probability pass of one phase from the fragment ring; tile loads are issued between the MFMA steps ----
-template <int NB, int GB>
-__device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const u32x4 *q2, const float *cinit,
-                                          Acc<NB> &acc, int hf, int col, const KIssue &ki)
+template <int NB, int GB, int PAR>
+__device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t cinit_ad,
+                                          Acc<NB> &acc, const KIssue &ki, int lane)
 {
     constexpr int kPerStep = kSubInstr / (NB * GB * kNS);
 #pragma unroll
@@ -304,8 +316,8 @@ __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const u3
         for (int gb = 0; gb < GB; ++gb) {
             const int blk = gb * NB + nb;
             bf16x8 qf[kKS];
-            lift_block(q2, blk * 32 + col, hf, qf);
-            const f32x16 ci = lds_load_f16(cinit + blk * 32 + hf * 16);
+            if (blk == 0) lift_at<kOffQ2 + PAR * kQTileBytes>(lc, qf); else lift_at<kOffQ2 + PAR * kQTileBytes + 4096>(lc, qf);
+            const f32x16 ci = lds_load_f16(cinit_ad + blk * 128);
 #pragma unroll
             for (int s = 0; s < kNS; ++s) {
                 f32x16 d = ci;
@@ -315,7 +327,7 @@ __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const u3
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     acc.mx[s][nb][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[s][nb][e]);
-                k_issue<kPerStep>(ki, ((nb * GB + gb) * kNS + s) * kPerStep);
+                k_issue<kPerStep>(ki, lc, lane, ((nb * GB + gb) * kNS + s) * kPerStep);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -340,16 +352,16 @@ __device__ __forceinline__ void close_layer(Acc<NB> &acc, float c)
 }
 
 // ---- statistics pass of one phase: per-wave (max, sum exp) of every row into wstats ----
-template <int NBLK>
-__device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS], const u32x4 *q1,
-                                           float2 *wstats_wave, int n_valid, int wave, int hf, int col,
-                                           const KIssue &ki)
+template <int NBLK, int PAR>
+__device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS], const LaneConst &lc,
+                                           uint32_t wstats_ad, int n_valid, int wave, int lane, const KIssue &ki)
 {
     constexpr int kPerStep = kSubInstr / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
+    const int hf = lane >> 5;
 #pragma unroll
     for (int blk = 0; blk < NBLK; ++blk) {
         bf16x8 qf[kKS];
-        lift_block(q1, blk * 32 + col, hf, qf);
+        if (blk == 0) lift_at<kOffQ1 + PAR * kQTileBytes>(lc, qf); else lift_at<kOffQ1 + PAR * kQTileBytes + 4096>(lc, qf);
         float m = neg_inf(), l = 0.f;
 #pragma unroll
         for (int s = 0; s < kNS; ++s) {
@@ -388,12 +400,12 @@ __device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS]
                     }
                 }
             }
-            k_issue<kPerStep>(ki, (blk * kNS + s) * kPerStep);
+            k_issue<kPerStep>(ki, lc, lane, (blk * kNS + s) * kPerStep);
             __builtin_amdgcn_sched_barrier(0);
         }
         const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
         lse_merge(m, l, m2, l2, c);
-        if (hf == 0) lds_store_f2(wstats_wave + blk * 32 + col, make_float2(m, l));
+        if (hf == 0) lds_store_f2(wstats_ad + blk * 256, make_float2(m, l));
     }
 }
 
@@ -404,11 +416,11 @@ __device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS]
 // chunk (2q + h) * 64 + lane holds rows 2h and 2h+1 of the block from workgroup lane + 64q.
 struct DutyBlock { uint64_t e[kDutyRows][4]; };     // [row of the block][workgroup lane + 64q]
 
-__device__ __forceinline__ DutyBlock read_duty_staging(const u32x4 *xduty, int lane)
+__device__ __forceinline__ DutyBlock read_duty_staging(uint32_t lds0, int lane)
 {
     static_assert(kDutyRows == 4, "layout of the asm block");
     typedef __attribute__((ext_vector_type(2))) uint64_t u64x2;
-    const uint32_t ad = lds_addr(xduty) + 16u * (uint32_t)lane;
+    const uint32_t ad = lds0 + kOffXduty + 16u * (uint32_t)lane;
     u64x2 r[8];
     __asm__ volatile(
         "ds_read_b128 %0, %8\n\t"
@@ -434,9 +446,9 @@ __device__ __forceinline__ DutyBlock read_duty_staging(const u32x4 *xduty, int l
     return d;
 }
 
-__device__ __forceinline__ uint64_t read_lse_staging(const u32x4 *xlse, int lane)
+__device__ __forceinline__ uint64_t read_lse_staging(uint32_t lds0, int lane)
 {
-    const uint32_t ad = lds_addr(xlse) + 8u * (uint32_t)lane;
+    const uint32_t ad = lds0 + kOffXlse + 8u * (uint32_t)lane;
     uint64_t v;
     __asm__ volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(ad) : "memory");
     return v;
@@ -447,14 +459,14 @@ constexpr int kDeviceScope = 16;          // the sc1 bit of the cache-policy ope
 
 // 64 x 16 bytes: the 16-byte pairs 0 .. 63 of a row of 8-byte entries (row 16-byte aligned) that
 // holds `pairs` pairs; lanes beyond the row repeat its last pair.
-__device__ __forceinline__ void stage_entries(u32x4 *dst, const uint64_t *row, int pairs, int lane)
+__device__ __forceinline__ void stage_entries(unsigned char *dst, const uint64_t *row, int pairs, int lane)
 {
     const uint64_t *p = row + 2 * min(lane, pairs - 1);
     __builtin_amdgcn_global_load_lds(SP_GPTR(p), SP_LPTR(dst), 16, 0, kDeviceScope);
 }
 
 // The partials of rows row0 .. row0+3 of one exchange slot from every workgroup: eight loads.
-__device__ __forceinline__ void stage_duty_block(u32x4 *xduty, const uint64_t *slot_base, int rows_pad, int n_wg,
+__device__ __forceinline__ void stage_duty_block(unsigned char *xduty, const uint64_t *slot_base, int rows_pad, int n_wg,
                                                  int row0, int lane)
 {
 #pragma unroll
@@ -462,7 +474,7 @@ __device__ __forceinline__ void stage_duty_block(u32x4 *xduty, const uint64_t *s
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const uint64_t *p = slot_base + (size_t)min(lane + 64 * q, n_wg - 1) * rows_pad + row0 + 2 * h;
-            __builtin_amdgcn_global_load_lds(SP_GPTR(p), SP_LPTR(xduty + (2 * q + h) * 64), 16, 0, kDeviceScope);
+            __builtin_amdgcn_global_load_lds(SP_GPTR(p), SP_LPTR(xduty + (2 * q + h) * 1024), 16, 0, kDeviceScope);
         }
 }
 
@@ -480,55 +492,49 @@ __device__ __forceinline__ bool duty_ready(const DutyBlock &d, uint32_t par, int
     return ok != 0;
 }
 
-// Block of kDutyRows rows of phase p that workgroup w combines (>= rows_pad / kDutyRows: none).
-// Blocks rotate over the workgroups.
-__device__ __forceinline__ int duty_block_of(const FusedArgs &a, int p, int w)
-{
-    const int first = (int)(((uint32_t)p * (uint32_t)(a.rows_pad / kDutyRows)) % (uint32_t)a.n_wg);
-    const int r = w - first;
-    return r < 0 ? r + a.n_wg : r;
-}
-
-struct Shared {
-    u32x4 *kring;                         // [8 waves][3 slots][32 rows x 8 chunks]
-    u32x4 *q1[2], *q2[2];                 // Q tiles of the statistics / probability pass, by phase parity
-    float2 (*wstats)[kFWaves][kMaxRowsF]; // [2]
-    float (*cinit)[kMaxRowsF];            // [2]
-    u32x4 *xduty, *xlse;
-    int *fail;
+// Uniform state that walks along with the steps.
+struct Walk {
+    PhaseCtr k;       // phase s + 1: next statistics pass (its K tile and Q tile are being fetched)
+    PhaseCtr l;       // phase s - 3: normalisers and Q tile of the next probability pass
+    PhaseCtr c;       // phase s - 4: this step's probability pass
+    int dfirst;       // workgroup that combines block 0 of phase s - 2; blocks rotate over the workgroups
 };
 
 // One step `s` of the software pipeline: everything between two workgroup barriers. Per wave, in
 // program order (phase numbers in brackets are skipped when out of range):
-//   mid     publish this workgroup's partials of eight rows of phase s-1 (all waves); the duty wave
-//           requests the partials of its duty row of phase s-2; every wave requests its slices of
-//           Q(s+1) for the next statistics pass and of Q(s-3) for the next probability pass
+//   mid     one wave publishes this workgroup's partials of phase s-1; the duty wave requests the
+//           partials of its duty rows of phase s-2; every wave requests its slices of Q(s+1) for
+//           the next statistics pass and of Q(s-3) for the next probability pass
 //   prob    probability pass of phase s-4 from ring slot s%4; loads of sub-tile 0 of K(s+1)
 //   lse     the normaliser wave requests the normalisers of phase s-3
 //   lift    wait for sub-tile 1 of K(s); lift K(s) into ring slot s%4
 //   stats   statistics pass of phase s; loads of sub-tile 1 of K(s+1)
-//   pre     wait for the Q slices (and the exchange data); duty wave: combine the duty row of phase
-//           s-2 and publish its normaliser; normaliser wave: seeds of the probability pass of phase s-3
+//   pre     wait for the Q slices (and the exchange data); duty wave: combine the duty rows of phase
+//           s-2 and publish their normalisers; normaliser wave: seeds of the probability pass of phase s-3
 //   barrier
-// Vector-memory operations per wave and step, oldest first: [publish store] [2 duty loads] Q, Q,
+// Vector-memory operations per wave and step, oldest first: [publish store] [8 duty loads] [Q] [Q]
 // 4 K loads (prob), [normaliser load], 4 K loads (stats); the bracketed ones exist on some waves or
 // in some steps only, so every wait counts only operations that are certainly issued behind the
 // ones it needs.
 template <int NB, int GB, int SLOT, int PAR>
 __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, int s, int n_phases, Ring &ring,
-                                     Acc<NB> &acc, const Shared &sh, int n_valid)
+                                     Acc<NB> &acc, const LaneConst &lc, Walk &wk, unsigned char *lds, uint32_t lds0,
+                                     int64_t wg_off, int n_valid)
 {
-    // Lane-derived LDS and global offsets are recomputed every step instead of being kept in
-    // registers across the whole loop (the opaque copy stops the compiler from hoisting them).
+    // Other lane-derived values are recomputed every step instead of being kept in registers across
+    // the whole loop (the opaque copy stops the compiler from hoisting them).
     int tid = threadIdx.x;
     __asm__ volatile("" : "+v"(tid));
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, hf = lane >> 5, col = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int w = blockIdx.x;
     const int pp = s - 1;                 // phase whose partials are published
     const int pc = s - 1 - kLag;          // phase of this step's probability pass
-    const int pd = s - 2;                 // phase whose duty row is combined in this step
+    const int pd = s - 2;                 // phase whose duty rows are combined in this step
     const int pl = s - kLag;              // phase whose normalisers are fetched in this step
     const bool do_stats = s < n_phases, do_prob = pc >= 0 && pc < n_phases;
+    const uint32_t stride_bytes = (uint32_t)a.k_stride_token * 2u;
+    int duty_blk = wk.dfirst <= w ? w - wk.dfirst : w - wk.dfirst + a.n_wg;
+    if (pd < 0 || pd >= n_phases || duty_blk >= a.rows_pad / kDutyRows) duty_blk = -1;
 
     // ---- mid ----
     if (wave == kPubWave) {
@@ -538,21 +544,21 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
             float pm[kFWaves], pl8[kFWaves];
             {
                 typedef __attribute__((ext_vector_type(2))) float f32x2;
-                const uint32_t ad = lds_addr(&sh.wstats[1 - PAR][0][lane]);
+                const uint32_t ad = lds0 + 8u * (uint32_t)lane;
                 f32x2 r[kFWaves];
-                static_assert(kFWaves == 8 && sizeof(float2) * kMaxRowsF == 512, "layout of the asm block");
+                static_assert(kFWaves == 8 && kMaxRowsF * 8 == 512, "layout of the asm block");
                 __asm__ volatile(
-                    "ds_read_b64 %0, %8\n\t"
-                    "ds_read_b64 %1, %8 offset:512\n\t"
-                    "ds_read_b64 %2, %8 offset:1024\n\t"
-                    "ds_read_b64 %3, %8 offset:1536\n\t"
-                    "ds_read_b64 %4, %8 offset:2048\n\t"
-                    "ds_read_b64 %5, %8 offset:2560\n\t"
-                    "ds_read_b64 %6, %8 offset:3072\n\t"
-                    "ds_read_b64 %7, %8 offset:3584\n\t"
+                    "ds_read_b64 %0, %8 offset:%9\n\t"
+                    "ds_read_b64 %1, %8 offset:%9+512\n\t"
+                    "ds_read_b64 %2, %8 offset:%9+1024\n\t"
+                    "ds_read_b64 %3, %8 offset:%9+1536\n\t"
+                    "ds_read_b64 %4, %8 offset:%9+2048\n\t"
+                    "ds_read_b64 %5, %8 offset:%9+2560\n\t"
+                    "ds_read_b64 %6, %8 offset:%9+3072\n\t"
+                    "ds_read_b64 %7, %8 offset:%9+3584\n\t"
                     "s_waitcnt lgkmcnt(0)"
                     : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7])
-                    : "v"(ad)
+                    : "v"(ad), "i"(kOffWstats + (1 - PAR) * kWstatsBytes)
                     : "memory");
 #pragma unroll
                 for (int i = 0; i < kFWaves; ++i) { pm[i] = r[i].x; pl8[i] = r[i].y; }
@@ -570,72 +576,83 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
             }
         }
     } else if (wave == kDutyWave) {
-        if (pd >= 0 && pd < n_phases) {
-            const int blk = duty_block_of(a, pd, w);
-            if (blk < a.rows_pad / kDutyRows)
-                stage_duty_block(sh.xduty, a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad, a.rows_pad, a.n_wg,
-                                 blk * kDutyRows, lane);
-        }
+        if (duty_blk >= 0)
+            stage_duty_block(lds + kOffXduty, a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad, a.rows_pad, a.n_wg,
+                             duty_blk * kDutyRows, lane);
     }
-    {
-        const PhaseId id1 = phase_of(min(s + 1, n_phases - 1), a.n_kv_heads);
-        issue_q_slice<NB>(sh.q1[1 - PAR], a, id1.layer, id1.kv, wave, lane);
-        const PhaseId id2 = phase_of(clampi(pl, 0, n_phases - 1), a.n_kv_heads);
-        issue_q_slice<NB>(sh.q2[PAR], a, id2.layer, id2.kv, wave, lane);
+    if (lc.qoff >= 0) {       // padding rows of the Q tiles stay zero
+        const char *q1src = reinterpret_cast<const char *>(a.q) +
+                            ((int64_t)wk.k.layer * a.n_q_heads + (int64_t)wk.k.kv * a.group) * a.n_q * (kD * 2);
+        const char *q2src = reinterpret_cast<const char *>(a.q) +
+                            ((int64_t)wk.l.layer * a.n_q_heads + (int64_t)wk.l.kv * a.group) * a.n_q * (kD * 2);
+        __builtin_amdgcn_global_load_lds(SP_GPTR(q1src + (uint32_t)lc.qoff),
+                                         SP_LPTR(lds + kOffQ1 + (1 - PAR) * kQTileBytes + wave * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(SP_GPTR(q2src + (uint32_t)lc.qoff),
+                                         SP_LPTR(lds + kOffQ2 + PAR * kQTileBytes + wave * 1024), 16, 0, 0);
     }
 
     // ---- probability pass of phase pc; sub-tile 0 of K(s+1) ----
+    const char *kbase = reinterpret_cast<const char *>(kp.p[wk.k.layer]) +
+                        ((int64_t)wk.k.kv * a.k_stride_head + wg_off + (int64_t)wave * 64 * a.k_stride_token) * 2;
+    const int n_next = s + 1 < n_phases ? n_valid - wave * 64 : 1;    // past the last phase: a one-row dummy keeps the count fixed
     {
-        const KIssue ki = k_issue_setup(a, kp, sh.kring, s + 1, 0, n_phases, n_valid, wave, lane);
+        KIssue ki;
+        ki.slot = lds + sub_slot_off(wave, s + 1, 0);
+        ki.base = kbase;
+        ki.stride_bytes = stride_bytes;
+        ki.n_left = n_next;
         if (do_prob) {
-            prob_pass<NB, GB>(ring.kf[SLOT], sh.q2[1 - PAR], sh.cinit[1 - PAR], acc, hf, col, ki);
-            const PhaseId idc = phase_of(pc, a.n_kv_heads);
-            if (idc.kv == a.n_kv_heads - 1 && (a.layer_agg == SP_LAYER_MEAN || idc.layer == a.n_layers - 1))
+            const uint32_t cinit_ad = lds0 + kOffCinit + (1 - PAR) * (kMaxRowsF * 4) + ((uint32_t)(lane & 32) << 1);
+            prob_pass<NB, GB, 1 - PAR>(ring.kf[SLOT], lc, cinit_ad, acc, ki, lane);
+            if (wk.c.kv == a.n_kv_heads - 1 && (a.layer_agg == SP_LAYER_MEAN || wk.c.layer == a.n_layers - 1))
                 close_layer<NB>(acc, a.c);
         } else {
-            k_issue<kSubInstr>(ki, 0);
+            k_issue<kSubInstr>(ki, lc, lane, 0);
         }
     }
     if (wave == kLseWave) {
         const int pn = clampi(pl, 0, n_phases - 1);
-        stage_entries(sh.xlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, a.rows_pad / 2, lane);
+        stage_entries(lds + kOffXlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, a.rows_pad / 2, lane);
     }
 
     // ---- lift K(s), statistics pass of phase s; sub-tile 1 of K(s+1) ----
-    vm_wait<2 + kSubInstr>();             // behind sub-tile 1 of K(s): at least Q, Q and the 4 loads of the prob part
+    vm_wait<kSubInstr>();                 // behind sub-tile 1 of K(s): at least the 4 loads of the prob part
     {
-        const KIssue ki = k_issue_setup(a, kp, sh.kring, s + 1, 1, n_phases, n_valid, wave, lane);
+        KIssue ki;
+        ki.slot = lds + sub_slot_off(wave, s + 1, 1);
+        ki.base = kbase + (int64_t)32 * stride_bytes;
+        ki.stride_bytes = stride_bytes;
+        ki.n_left = s + 1 < n_phases ? n_next - 32 : 1;
         if (do_stats) {
 #pragma unroll
-            for (int s2 = 0; s2 < kNS; ++s2) lift_block(sub_slot(sh.kring, wave, s, s2), col, hf, ring.kf[SLOT][s2]);
-            stats_pass<NB * GB>(a.c, ring.kf[SLOT], sh.q1[PAR], sh.wstats[PAR][wave], n_valid, wave, hf, col, ki);
+            for (int s2 = 0; s2 < kNS; ++s2) lift_dyn(lc, sub_slot_off(wave, s, s2), ring.kf[SLOT][s2]);
+            const uint32_t wstats_ad = lds0 + kOffWstats + PAR * kWstatsBytes + wave * (kMaxRowsF * 8) + ((uint32_t)(lane & 31) << 3);
+            stats_pass<NB * GB, PAR>(a.c, ring.kf[SLOT], lc, wstats_ad, n_valid, wave, lane, ki);
         } else {
-            k_issue<kSubInstr>(ki, 0);
+            k_issue<kSubInstr>(ki, lc, lane, 0);
         }
     }
 
     // ---- pre-barrier: exchange data in, seeds out ----
     if (wave == kLseWave) vm_wait<kSubInstr>(); else vm_wait<2 * kSubInstr>();
+    int *fail = reinterpret_cast<int *>(lds + kOffFail);
     if (wave == kDutyWave) {
-        if (pd >= 0 && pd < n_phases) {
-            const int blk = duty_block_of(a, pd, w);
+        if (duty_blk >= 0) {
             uint32_t row_mask = 0;
-            if (blk < a.rows_pad / kDutyRows) {
 #pragma unroll
-                for (int r = 0; r < kDutyRows; ++r) {
-                    int g, n;
-                    if (row_valid<NB>(a, blk * kDutyRows + r, g, n)) row_mask |= 1u << r;
-                }
+            for (int r = 0; r < kDutyRows; ++r) {
+                int g, n;
+                if (row_valid<NB>(a, duty_blk * kDutyRows + r, g, n)) row_mask |= 1u << r;
             }
             if (row_mask != 0) {
                 const uint32_t par = (uint32_t)(pd / kSlots) & 1u;
-                const uint64_t *src = a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad + blk * kDutyRows;
+                const uint64_t *src = a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad + duty_blk * kDutyRows;
                 // fast path: the partials requested at the start of this step are all there; otherwise poll (bounded)
-                DutyBlock de = read_duty_staging(sh.xduty, lane);
-                if (__any(!duty_ready(de, par, lane, a.n_wg, row_mask)) && *sh.fail == 0) {
+                DutyBlock de = read_duty_staging(lds0, lane);
+                if (__any(!duty_ready(de, par, lane, a.n_wg, row_mask)) && *fail == 0) {
                     unsigned spins = 0;
                     do {
-                        if (++spins > kSpinMax) { *sh.fail = 1; break; }
+                        if (++spins > kSpinMax) { *fail = 1; break; }
 #pragma unroll
                         for (int r = 0; r < kDutyRows; ++r)
 #pragma unroll
@@ -664,7 +681,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
                     if (lane == r) mine = v;
                 }
                 if (lane < kDutyRows && ((row_mask >> lane) & 1u))
-                    st64(a.lse + (size_t)(pd % kSlots) * a.rows_pad + blk * kDutyRows + lane,
+                    st64(a.lse + (size_t)(pd % kSlots) * a.rows_pad + duty_blk * kDutyRows + lane,
                          (uint64_t)__float_as_uint(mine) | ((uint64_t)(uint32_t)(pd + 1) << 32));
             }
         }
@@ -674,19 +691,29 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
             float v = neg_inf();
             if (row_valid<NB>(a, lane, g, n)) {
                 const uint64_t *src = a.lse + (size_t)(pl % kSlots) * a.rows_pad + lane;
-                uint64_t entry = read_lse_staging(sh.xlse, lane);
-                if ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1) && *sh.fail == 0) {
+                uint64_t entry = read_lse_staging(lds0, lane);
+                if ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1) && *fail == 0) {
                     unsigned spins = 0;
                     do {
-                        if (++spins > kSpinMax) { *sh.fail = 1; break; }
+                        if (++spins > kSpinMax) { *fail = 1; break; }
                         entry = ld64(src);
                     } while ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1));
                 }
                 v = __uint_as_float((uint32_t)entry);
             }
             const int rho = lane & 31;
-            lds_store_f32(sh.cinit[PAR] + (lane & ~31) + ((rho >> 2) & 1) * 16 + 4 * (rho >> 3) + (rho & 3), v);
+            lds_store_f32(lds0 + kOffCinit + PAR * (kMaxRowsF * 4) +
+                              4u * (uint32_t)((lane & ~31) + ((rho >> 2) & 1) * 16 + 4 * (rho >> 3) + (rho & 3)), v);
         }
+    }
+
+    // ---- walk on ----
+    phase_advance(wk.k, s + 2, n_phases, a.n_kv_heads);
+    phase_advance(wk.l, s - 2, n_phases, a.n_kv_heads);
+    phase_advance(wk.c, s - 3, n_phases, a.n_kv_heads);
+    if (s - 1 > 0 && s - 1 < n_phases) {
+        wk.dfirst += a.rows_pad / kDutyRows;
+        if (wk.dfirst >= a.n_wg) wk.dfirst -= a.n_wg;
     }
     lds_barrier();
 }
@@ -694,27 +721,41 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
 template <int NB, int GB>
 __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, LayerPtrs kp)
 {
-    __shared__ u32x4 kring[kFWaves * kSubSlots * kSubChunks];
-    __shared__ u32x4 q1a[kMaxRowsF * kCH], q1b[kMaxRowsF * kCH], q2a[kMaxRowsF * kCH], q2b[kMaxRowsF * kCH];
-    __shared__ float2 wstats[2][kFWaves][kMaxRowsF];
-    __shared__ float cinit[2][kMaxRowsF];
-    __shared__ u32x4 xduty[8 * 64];          // partials of the duty rows: 4 rows x 256 workgroups
-    __shared__ u32x4 xlse[64];               // normaliser entries of one phase (64 used, the load moves 128)
-    __shared__ int s_fail;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[kLdsBytes];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hf = lane >> 5, col = lane & 31;
     const int w = blockIdx.x;
     const int n_phases = a.n_layers * a.n_kv_heads;
     const int64_t j0 = (int64_t)w * kFTile;
     const int n_valid = (int)((a.L - j0 < kFTile) ? a.L - j0 : kFTile);
+    const uint32_t lds0 = lds_addr(lds);
+    const uint32_t stride_bytes = (uint32_t)a.k_stride_token * 2u;
 
-    Shared sh;
-    sh.kring = kring;
-    sh.q1[0] = q1a; sh.q1[1] = q1b; sh.q2[0] = q2a; sh.q2[1] = q2b;
-    sh.wstats = wstats; sh.cinit = cinit; sh.xduty = xduty; sh.xlse = xlse; sh.fail = &s_fail;
+    // zero the Q tiles (their padding rows are never loaded), seed the accumulator seeds with -inf
+    {
+        u32x4 *z = reinterpret_cast<u32x4 *>(lds + kOffQ1);
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < 4 * kQTileBytes / 16; i += kFThreads) z[i] = zero;
+        float *ci = reinterpret_cast<float *>(lds + kOffCinit);
+        if (tid < 2 * kMaxRowsF) ci[tid] = neg_inf();
+        if (tid == 0) *reinterpret_cast<int *>(lds + kOffFail) = 0;
+    }
+    __syncthreads();
 
-    if (tid < 2 * kMaxRowsF) cinit[tid / kMaxRowsF][tid % kMaxRowsF] = neg_inf();
-    if (tid == 0) s_fail = 0;
+    LaneConst lc;
+#pragma unroll
+    for (int t = 0; t < kKS; ++t) lc.ld[t] = lds0 + 16u * (uint32_t)lds_slot<kD>(col, 2 * t + hf);
+    {
+        const uint32_t rowpart = (uint32_t)(lane >> 3) * stride_bytes;
+        const uint32_t swz = (uint32_t)(lane >> 4);               // (row >> 1) & 7 of row = lane >> 3 in an even instruction
+        lc.koff[0] = rowpart + (((uint32_t)(lane & 7) ^ swz) << 4);
+        lc.koff[1] = rowpart + (((uint32_t)(lane & 7) ^ (swz | 4u)) << 4);
+        const int row = wave * 8 + (lane >> 3);
+        int g, n;
+        lc.qoff = -1;
+        if (row < a.rows_pad && row_valid<NB>(a, row, g, n))
+            lc.qoff = ((g * a.n_q + n) * kD + (((lane & 7) ^ ((row >> 1) & 7)) << 3)) * 2;
+    }
 
     Ring ring;
     Acc<NB> acc;
@@ -728,28 +769,41 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     }
 
     // prologue: this wave's slice of Q(0) and both sub-tiles of K(0); everything lands before step 0
-    issue_q_slice<NB>(q1a, a, 0, 0, wave, lane);
+    const int64_t wg_off = j0 * a.k_stride_token;
+    if (lc.qoff >= 0)
+        __builtin_amdgcn_global_load_lds(SP_GPTR(reinterpret_cast<const char *>(a.q) + (uint32_t)lc.qoff),
+                                         SP_LPTR(lds + kOffQ1 + wave * 1024), 16, 0, 0);
 #pragma unroll
     for (int s2 = 0; s2 < kNS; ++s2) {
-        const KIssue ki = k_issue_setup(a, kp, kring, 0, s2, n_phases, n_valid, wave, lane);
-        k_issue<kSubInstr>(ki, 0);
+        KIssue ki;
+        ki.slot = lds + sub_slot_off(wave, 0, s2);
+        ki.base = reinterpret_cast<const char *>(kp.p[0]) + (wg_off + (int64_t)(wave * 64 + s2 * 32) * a.k_stride_token) * 2;
+        ki.stride_bytes = stride_bytes;
+        ki.n_left = n_valid - wave * 64 - s2 * 32;
+        k_issue<kSubInstr>(ki, lc, lane, 0);
     }
     vm_wait<0>();
     lds_barrier();
+
+    Walk wk;
+    wk.k = phase_at(1, n_phases, a.n_kv_heads);
+    wk.l = phase_at(0, n_phases, a.n_kv_heads);
+    wk.c = phase_at(0, n_phases, a.n_kv_heads);
+    wk.dfirst = 0;
 
     // The body is unrolled four times so that the fragment ring slot (s % 4) and the buffer parity
     // (s % 2) are compile-time; the trip count is rounded up, surplus steps do no work but keep the
     // instruction stream uniform. The last probability pass (phase n_phases - 1) runs in step n_phases + 3.
     const int n_steps = (n_phases + kLag + 1 + 3) / 4 * 4;
     for (int s0 = 0; s0 < n_steps; s0 += 4) {
-        step<NB, GB, 0, 0>(a, kp, s0 + 0, n_phases, ring, acc, sh, n_valid);
-        step<NB, GB, 1, 1>(a, kp, s0 + 1, n_phases, ring, acc, sh, n_valid);
-        step<NB, GB, 2, 0>(a, kp, s0 + 2, n_phases, ring, acc, sh, n_valid);
-        step<NB, GB, 3, 1>(a, kp, s0 + 3, n_phases, ring, acc, sh, n_valid);
+        step<NB, GB, 0, 0>(a, kp, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wg_off, n_valid);
+        step<NB, GB, 1, 1>(a, kp, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wg_off, n_valid);
+        step<NB, GB, 2, 0>(a, kp, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wg_off, n_valid);
+        step<NB, GB, 3, 1>(a, kp, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wg_off, n_valid);
     }
     vm_wait<0>();               // no direct-to-LDS load may outlive the workgroup
     lds_barrier();
-    const bool failed = s_fail != 0;
+    const bool failed = *reinterpret_cast<int *>(lds + kOffFail) != 0;
     if (failed && tid == 0) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
     for (int s = 0; s < kNS; ++s) {
