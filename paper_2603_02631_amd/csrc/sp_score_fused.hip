@@ -79,7 +79,6 @@ constexpr int kSubBytes = 32 * kD * 2;
 constexpr int kLdsBytes = kOffKring + kFWaves * kSubSlots * kSubBytes;
 static_assert(kOffKring < 65536, "offset fields hold 16 bits");
 
-#define SP_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define SP_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 __device__ __forceinline__ uint64_t ld64(const uint64_t *p)
@@ -130,6 +129,27 @@ struct LaneConst {
 // direct-to-LDS load targets which buffer and would put a full vector-memory wait in front of
 // LDS accesses it can see. The kernel waits (vm_wait, barrier) for exactly what it is about to read.
 __device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)reinterpret_cast<uintptr_t>(SP_LPTR(p)); }
+
+// Direct-to-LDS loads of 64 lanes x 16 bytes into LDS bytes [lds_dst, lds_dst + 1024); lds_dst is
+// uniform and travels in M0, which nothing else in this kernel uses. They are asm for the same
+// reason, and so that the scalar-base form is used: a uniform 64-bit base plus a 32-bit lane offset.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ void dma_u(uint32_t lane_off, const void *base, uint32_t lds_dst)
+{
+    const uint64_t b = reinterpret_cast<uintptr_t>(base);
+    const uint64_t ub = (uint64_t)uniform32((uint32_t)b) | ((uint64_t)uniform32((uint32_t)(b >> 32)) << 32);
+    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     : : "v"(lane_off), "s"(ub), "s"(uniform32(lds_dst)) : "memory", "m0");
+}
+// Per-lane addresses, bypassing the non-coherent cache levels like the atomic loads of the retry paths do.
+__device__ __forceinline__ void dma_v_device(const void *addr, uint32_t lds_dst)
+{
+    __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off sc1"
+                     : : "v"(addr), "s"(uniform32(lds_dst)) : "memory", "m0");
+}
+#pragma clang diagnostic pop
 
 // MFMA fragments of 32 rows of a swizzled 64-wide bf16 tile at compile-time LDS offset OFF:
 // lane (col, hf) takes row col, 16-byte chunks 2t + hf.
@@ -259,43 +279,31 @@ __device__ __forceinline__ bool row_valid(const FusedArgs &a, int row, int &g, i
 }
 
 // One wave instruction moves 64 chunks = 8 key rows (1 KB, contiguous in HBM when keys are
-// contiguous); a 32-key sub-tile takes four of them. The address is a uniform base plus a 32-bit
-// per-lane byte offset.
+// contiguous); a 32-key sub-tile takes four of them: a uniform base that steps by 8 keys, plus the
+// lane's constant offset (even / odd instruction).
 struct KIssue {
-    unsigned char *slot;      // LDS sub-tile slot being refilled (this wave's)
+    uint32_t lds_dst;         // LDS byte address of the sub-tile slot being refilled (this wave's)
     const char *base;         // first key of the sub-tile in the (layer, kv head) being fetched (uniform)
-    uint32_t stride_bytes;    // bytes between consecutive keys
-    int n_left;               // valid keys from the sub-tile's first key on (>= 32: all of them)
+    uint32_t step_bytes;      // bytes between the first keys of consecutive instructions (8 keys)
 };
 
 // Issues instructions first .. first+COUNT-1 of the sub-tile (first and COUNT compile-time at call sites).
 template <int COUNT>
-__device__ __forceinline__ void k_issue(const KIssue &ki, const LaneConst &lc, int lane, int first)
+__device__ __forceinline__ void k_issue(const KIssue &ki, const uint32_t (&voff)[2], int first)
 {
-    if (ki.n_left >= 32) {
 #pragma unroll
-        for (int i = 0; i < COUNT; ++i) {
-            const int idx = first + i;
-            const char *src = ki.base + (uint32_t)(8 * idx) * ki.stride_bytes + lc.koff[idx & 1];
-            __builtin_amdgcn_global_load_lds(SP_GPTR(src), SP_LPTR(ki.slot + idx * 1024), 16, 0, 0);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < COUNT; ++i) {
-            const int idx = first + i;
-            int r = 8 * idx + (lane >> 3);                        // row within the sub-tile
-            const uint32_t chunk = (uint32_t)((lane & 7) ^ ((r >> 1) & 7));
-            r = min(r, max(ki.n_left, 1) - 1);                    // rows past the end repeat the last valid key
-            const char *src = ki.base + (uint32_t)r * ki.stride_bytes + chunk * 16u;
-            __builtin_amdgcn_global_load_lds(SP_GPTR(src), SP_LPTR(ki.slot + idx * 1024), 16, 0, 0);
-        }
+    for (int i = 0; i < COUNT; ++i) {
+        const int idx = first + i;
+        dma_u(voff[idx & 1], ki.base + (uint32_t)idx * ki.step_bytes, ki.lds_dst + idx * 1024);
     }
 }
 
-// Sub-tile s2 of phase p lives in slot (2p + s2) mod 3 of its wave's transit ring.
-__device__ __forceinline__ uint32_t sub_slot_off(int wave, int p, int s2)
+// Sub-tile s2 of phase p lives in slot (2p + s2) mod 3 of its wave's transit ring; slot0 = 2p mod 3.
+__device__ __forceinline__ uint32_t sub_slot_off(int wave, int slot0, int s2)
 {
-    return (uint32_t)(kOffKring + (wave * kSubSlots + (2 * p + s2) % kSubSlots) * kSubBytes);
+    int slot = slot0 + s2;
+    slot = slot >= kSubSlots ? slot - kSubSlots : slot;
+    return (uint32_t)(kOffKring + (wave * kSubSlots + slot) * kSubBytes);
 }
 
 template <int NB>
@@ -307,7 +315,7 @@ struct Acc {
 // ---- probability pass of one phase from the fragment ring; tile loads are issued between the MFMA steps ----
 template <int NB, int GB, int PAR>
 __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t cinit_ad,
-                                          Acc<NB> &acc, const KIssue &ki, int lane)
+                                          Acc<NB> &acc, const KIssue &ki, const uint32_t (&voff)[2])
 {
     constexpr int kPerStep = kSubInstr / (NB * GB * kNS);
 #pragma unroll
@@ -327,7 +335,7 @@ __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const La
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     acc.mx[s][nb][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[s][nb][e]);
-                k_issue<kPerStep>(ki, lc, lane, ((nb * GB + gb) * kNS + s) * kPerStep);
+                k_issue<kPerStep>(ki, voff, ((nb * GB + gb) * kNS + s) * kPerStep);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -354,7 +362,8 @@ __device__ __forceinline__ void close_layer(Acc<NB> &acc, float c)
 // ---- statistics pass of one phase: per-wave (max, sum exp) of every row into wstats ----
 template <int NBLK, int PAR>
 __device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS], const LaneConst &lc,
-                                           uint32_t wstats_ad, int n_valid, int wave, int lane, const KIssue &ki)
+                                           uint32_t wstats_ad, int r_lo, int wave, int lane, const KIssue &ki,
+                                           const uint32_t (&voff)[2])
 {
     constexpr int kPerStep = kSubInstr / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
     const int hf = lane >> 5;
@@ -369,8 +378,8 @@ __device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS]
 #pragma unroll
             for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s][t], qf[t], d, 0, 0, 0);
             // d[r]: key (wave*2+s)*32 + 8*(r/4) + 4*hf + r%4 of the tile, query row blk*32 + col
-            const int left = n_valid - (wave * kNS + s) * 32;
-            if (left >= 32) {
+            const int lo = r_lo - (wave * kNS + s) * 32;      // keys below lo belong to the previous workgroup
+            if (lo <= 0) {
                 float mn = max3(m, d[0], d[1]);      // running maximum including these 16 logits
 #pragma unroll
                 for (int r = 2; r < 16; r += 2) mn = max3(mn, d[r], d[r + 1]);
@@ -381,12 +390,12 @@ __device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS]
 #pragma unroll
                 for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(d[r], c, -mc));
                 l += sum;
-            } else if (left > 0) {
+            } else if (lo < 32) {
                 float tm = neg_inf();
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
-                    if (key < left) tm = fmaxf(tm, d[r]);
+                    if (key >= lo) tm = fmaxf(tm, d[r]);
                 }
                 if (tm > neg_inf()) {
                     const float mn = fmaxf(m, tm);
@@ -396,11 +405,11 @@ __device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS]
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
-                        if (key < left) l += fast_exp2(fmaf(d[r], c, -mc));
+                        if (key >= lo) l += fast_exp2(fmaf(d[r], c, -mc));
                     }
                 }
             }
-            k_issue<kPerStep>(ki, lc, lane, (blk * kNS + s) * kPerStep);
+            k_issue<kPerStep>(ki, voff, (blk * kNS + s) * kPerStep);
             __builtin_amdgcn_sched_barrier(0);
         }
         const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
@@ -454,28 +463,23 @@ __device__ __forceinline__ uint64_t read_lse_staging(uint32_t lds0, int lane)
     return v;
 }
 
-// Direct-to-LDS loads bypass the non-coherent cache levels like the atomic loads of the retry paths do.
-constexpr int kDeviceScope = 16;          // the sc1 bit of the cache-policy operand
-
 // 64 x 16 bytes: the 16-byte pairs 0 .. 63 of a row of 8-byte entries (row 16-byte aligned) that
 // holds `pairs` pairs; lanes beyond the row repeat its last pair.
-__device__ __forceinline__ void stage_entries(unsigned char *dst, const uint64_t *row, int pairs, int lane)
+__device__ __forceinline__ void stage_entries(uint32_t lds_dst, const uint64_t *row, int pairs, int lane)
 {
-    const uint64_t *p = row + 2 * min(lane, pairs - 1);
-    __builtin_amdgcn_global_load_lds(SP_GPTR(p), SP_LPTR(dst), 16, 0, kDeviceScope);
+    dma_v_device(row + 2 * min(lane, pairs - 1), lds_dst);
 }
 
 // The partials of rows row0 .. row0+3 of one exchange slot from every workgroup: eight loads.
-__device__ __forceinline__ void stage_duty_block(unsigned char *xduty, const uint64_t *slot_base, int rows_pad, int n_wg,
+__device__ __forceinline__ void stage_duty_block(uint32_t xduty, const uint64_t *slot_base, int rows_pad, int n_wg,
                                                  int row0, int lane)
 {
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint64_t *p = slot_base + (size_t)min(lane + 64 * q, n_wg - 1) * rows_pad + row0 + 2 * h;
-            __builtin_amdgcn_global_load_lds(SP_GPTR(p), SP_LPTR(xduty + (2 * q + h) * 1024), 16, 0, kDeviceScope);
-        }
+        for (int h = 0; h < 2; ++h)
+            dma_v_device(slot_base + (size_t)min(lane + 64 * q, n_wg - 1) * rows_pad + row0 + 2 * h,
+                         xduty + (2 * q + h) * 1024);
 }
 
 // A partial is ready when it carries the parity of this use of its slot and a non-zero sum.
@@ -494,9 +498,10 @@ __device__ __forceinline__ bool duty_ready(const DutyBlock &d, uint32_t par, int
 
 // Uniform state that walks along with the steps.
 struct Walk {
-    PhaseCtr k;       // phase s + 1: next statistics pass (its K tile and Q tile are being fetched)
-    PhaseCtr l;       // phase s - 3: normalisers and Q tile of the next probability pass
+    PhaseCtr k;       // phase s + 1: next statistics pass (its K tile is being fetched)
+    const char *kptr; // this wave's first key of that phase
     PhaseCtr c;       // phase s - 4: this step's probability pass
+    int slot0;        // transit slot of sub-tile 0 of phase s: 2s mod 3
     int dfirst;       // workgroup that combines block 0 of phase s - 2; blocks rotate over the workgroups
 };
 
@@ -519,7 +524,7 @@ struct Walk {
 template <int NB, int GB, int SLOT, int PAR>
 __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, int s, int n_phases, Ring &ring,
                                      Acc<NB> &acc, const LaneConst &lc, Walk &wk, unsigned char *lds, uint32_t lds0,
-                                     int64_t wg_off, int n_valid)
+                                     uint64_t wave_off, int r_lo)
 {
     // Other lane-derived values are recomputed every step instead of being kept in registers across
     // the whole loop (the opaque copy stops the compiler from hoisting them).
@@ -577,59 +582,57 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
         }
     } else if (wave == kDutyWave) {
         if (duty_blk >= 0)
-            stage_duty_block(lds + kOffXduty, a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad, a.rows_pad, a.n_wg,
+            stage_duty_block(lds0 + kOffXduty, a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad, a.rows_pad, a.n_wg,
                              duty_blk * kDutyRows, lane);
     }
-    if (lc.qoff >= 0) {       // padding rows of the Q tiles stay zero
-        const char *q1src = reinterpret_cast<const char *>(a.q) +
-                            ((int64_t)wk.k.layer * a.n_q_heads + (int64_t)wk.k.kv * a.group) * a.n_q * (kD * 2);
-        const char *q2src = reinterpret_cast<const char *>(a.q) +
-                            ((int64_t)wk.l.layer * a.n_q_heads + (int64_t)wk.l.kv * a.group) * a.n_q * (kD * 2);
-        __builtin_amdgcn_global_load_lds(SP_GPTR(q1src + (uint32_t)lc.qoff),
-                                         SP_LPTR(lds + kOffQ1 + (1 - PAR) * kQTileBytes + wave * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(SP_GPTR(q2src + (uint32_t)lc.qoff),
-                                         SP_LPTR(lds + kOffQ2 + PAR * kQTileBytes + wave * 1024), 16, 0, 0);
+    if (lc.qoff >= 0) {       // padding rows of the Q tiles stay zero; the Q blocks of consecutive phases are contiguous
+        const uint32_t qblock = (uint32_t)(a.group * a.n_q * kD * 2);
+        const char *q1src = reinterpret_cast<const char *>(a.q) + (uint32_t)min(s + 1, n_phases - 1) * qblock;
+        const char *q2src = reinterpret_cast<const char *>(a.q) + (uint32_t)clampi(pl, 0, n_phases - 1) * qblock;
+        dma_u((uint32_t)lc.qoff, q1src, lds0 + kOffQ1 + (1 - PAR) * kQTileBytes + wave * 1024);
+        dma_u((uint32_t)lc.qoff, q2src, lds0 + kOffQ2 + PAR * kQTileBytes + wave * 1024);
     }
 
     // ---- probability pass of phase pc; sub-tile 0 of K(s+1) ----
-    const char *kbase = reinterpret_cast<const char *>(kp.p[wk.k.layer]) +
-                        ((int64_t)wk.k.kv * a.k_stride_head + wg_off + (int64_t)wave * 64 * a.k_stride_token) * 2;
-    const int n_next = s + 1 < n_phases ? n_valid - wave * 64 : 1;    // past the last phase: a one-row dummy keeps the count fixed
+    const char *kbase = wk.kptr;
+    int slot_next = wk.slot0 + 2;         // sub-tile 0 of phase s + 1
+    slot_next = slot_next >= kSubSlots ? slot_next - kSubSlots : slot_next;
+    // past the last phase the loads shrink to one 16-byte piece per instruction: the count stays fixed
+    const uint32_t live = s + 1 < n_phases ? 0xffffffffu : 0u;
+    const uint32_t voff[2] = {lc.koff[0] & live, lc.koff[1] & live};
     {
         KIssue ki;
-        ki.slot = lds + sub_slot_off(wave, s + 1, 0);
+        ki.lds_dst = lds0 + sub_slot_off(wave, slot_next, 0);
         ki.base = kbase;
-        ki.stride_bytes = stride_bytes;
-        ki.n_left = n_next;
+        ki.step_bytes = 8u * stride_bytes;
         if (do_prob) {
             const uint32_t cinit_ad = lds0 + kOffCinit + (1 - PAR) * (kMaxRowsF * 4) + ((uint32_t)(lane & 32) << 1);
-            prob_pass<NB, GB, 1 - PAR>(ring.kf[SLOT], lc, cinit_ad, acc, ki, lane);
+            prob_pass<NB, GB, 1 - PAR>(ring.kf[SLOT], lc, cinit_ad, acc, ki, voff);
             if (wk.c.kv == a.n_kv_heads - 1 && (a.layer_agg == SP_LAYER_MEAN || wk.c.layer == a.n_layers - 1))
                 close_layer<NB>(acc, a.c);
         } else {
-            k_issue<kSubInstr>(ki, lc, lane, 0);
+            k_issue<kSubInstr>(ki, voff, 0);
         }
     }
     if (wave == kLseWave) {
         const int pn = clampi(pl, 0, n_phases - 1);
-        stage_entries(lds + kOffXlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, a.rows_pad / 2, lane);
+        stage_entries(lds0 + kOffXlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, a.rows_pad / 2, lane);
     }
 
     // ---- lift K(s), statistics pass of phase s; sub-tile 1 of K(s+1) ----
     vm_wait<kSubInstr>();                 // behind sub-tile 1 of K(s): at least the 4 loads of the prob part
     {
         KIssue ki;
-        ki.slot = lds + sub_slot_off(wave, s + 1, 1);
+        ki.lds_dst = lds0 + sub_slot_off(wave, slot_next, 1);
         ki.base = kbase + (int64_t)32 * stride_bytes;
-        ki.stride_bytes = stride_bytes;
-        ki.n_left = s + 1 < n_phases ? n_next - 32 : 1;
+        ki.step_bytes = 8u * stride_bytes;
         if (do_stats) {
 #pragma unroll
-            for (int s2 = 0; s2 < kNS; ++s2) lift_dyn(lc, sub_slot_off(wave, s, s2), ring.kf[SLOT][s2]);
+            for (int s2 = 0; s2 < kNS; ++s2) lift_dyn(lc, sub_slot_off(wave, wk.slot0, s2), ring.kf[SLOT][s2]);
             const uint32_t wstats_ad = lds0 + kOffWstats + PAR * kWstatsBytes + wave * (kMaxRowsF * 8) + ((uint32_t)(lane & 31) << 3);
-            stats_pass<NB * GB, PAR>(a.c, ring.kf[SLOT], lc, wstats_ad, n_valid, wave, lane, ki);
+            stats_pass<NB * GB, PAR>(a.c, ring.kf[SLOT], lc, wstats_ad, r_lo, wave, lane, ki, voff);
         } else {
-            k_issue<kSubInstr>(ki, lc, lane, 0);
+            k_issue<kSubInstr>(ki, voff, 0);
         }
     }
 
@@ -708,9 +711,17 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
     }
 
     // ---- walk on ----
-    phase_advance(wk.k, s + 2, n_phases, a.n_kv_heads);
-    phase_advance(wk.l, s - 2, n_phases, a.n_kv_heads);
+    if (s + 2 < n_phases) {               // K pointer of the next step's fetch
+        if (++wk.k.kv == a.n_kv_heads) {
+            wk.k.kv = 0;
+            ++wk.k.layer;
+            wk.kptr = reinterpret_cast<const char *>(kp.p[wk.k.layer]) + wave_off;
+        } else {
+            wk.kptr += (uint64_t)a.k_stride_head * 2u;
+        }
+    }
     phase_advance(wk.c, s - 3, n_phases, a.n_kv_heads);
+    wk.slot0 = slot_next;
     if (s - 1 > 0 && s - 1 < n_phases) {
         wk.dfirst += a.rows_pad / kDutyRows;
         if (wk.dfirst >= a.n_wg) wk.dfirst -= a.n_wg;
@@ -726,8 +737,10 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hf = lane >> 5, col = lane & 31;
     const int w = blockIdx.x;
     const int n_phases = a.n_layers * a.n_kv_heads;
-    const int64_t j0 = (int64_t)w * kFTile;
-    const int n_valid = (int)((a.L - j0 < kFTile) ? a.L - j0 : kFTile);
+    // The last workgroup's tile is shifted back so that it ends with the prompt (the caller guarantees
+    // L >= 512): every workgroup loads 512 real keys; rows below r_lo belong to the previous workgroup.
+    const int64_t j0 = ((int64_t)(w + 1) * kFTile <= a.L) ? (int64_t)w * kFTile : a.L - kFTile;
+    const int r_lo = (int)((int64_t)w * kFTile - j0);
     const uint32_t lds0 = lds_addr(lds);
     const uint32_t stride_bytes = (uint32_t)a.k_stride_token * 2u;
 
@@ -768,27 +781,29 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
             for (int e = 0; e < 4; ++e) acc.mx[s][b][e] = neg_inf();
     }
 
+    // byte offset of this wave's first key within a (layer, kv head): uniform, kept in scalar registers
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    uint64_t wave_off = (uint64_t)(j0 + wave_u * 64) * (uint64_t)a.k_stride_token * 2u;
+    wave_off = (uint64_t)uniform32((uint32_t)wave_off) | ((uint64_t)uniform32((uint32_t)(wave_off >> 32)) << 32);
+
     // prologue: this wave's slice of Q(0) and both sub-tiles of K(0); everything lands before step 0
-    const int64_t wg_off = j0 * a.k_stride_token;
-    if (lc.qoff >= 0)
-        __builtin_amdgcn_global_load_lds(SP_GPTR(reinterpret_cast<const char *>(a.q) + (uint32_t)lc.qoff),
-                                         SP_LPTR(lds + kOffQ1 + wave * 1024), 16, 0, 0);
+    if (lc.qoff >= 0) dma_u((uint32_t)lc.qoff, a.q, lds0 + kOffQ1 + wave_u * 1024);
 #pragma unroll
     for (int s2 = 0; s2 < kNS; ++s2) {
         KIssue ki;
-        ki.slot = lds + sub_slot_off(wave, 0, s2);
-        ki.base = reinterpret_cast<const char *>(kp.p[0]) + (wg_off + (int64_t)(wave * 64 + s2 * 32) * a.k_stride_token) * 2;
-        ki.stride_bytes = stride_bytes;
-        ki.n_left = n_valid - wave * 64 - s2 * 32;
-        k_issue<kSubInstr>(ki, lc, lane, 0);
+        ki.lds_dst = lds0 + sub_slot_off(wave_u, 0, s2);
+        ki.base = reinterpret_cast<const char *>(kp.p[0]) + wave_off + (uint64_t)(s2 * 32) * stride_bytes;
+        ki.step_bytes = 8u * stride_bytes;
+        k_issue<kSubInstr>(ki, lc.koff, 0);
     }
     vm_wait<0>();
     lds_barrier();
 
     Walk wk;
     wk.k = phase_at(1, n_phases, a.n_kv_heads);
-    wk.l = phase_at(0, n_phases, a.n_kv_heads);
+    wk.kptr = reinterpret_cast<const char *>(kp.p[wk.k.layer]) + (uint64_t)wk.k.kv * (uint64_t)a.k_stride_head * 2u + wave_off;
     wk.c = phase_at(0, n_phases, a.n_kv_heads);
+    wk.slot0 = 0;
     wk.dfirst = 0;
 
     // The body is unrolled four times so that the fragment ring slot (s % 4) and the buffer parity
@@ -796,10 +811,10 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     // instruction stream uniform. The last probability pass (phase n_phases - 1) runs in step n_phases + 3.
     const int n_steps = (n_phases + kLag + 1 + 3) / 4 * 4;
     for (int s0 = 0; s0 < n_steps; s0 += 4) {
-        step<NB, GB, 0, 0>(a, kp, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wg_off, n_valid);
-        step<NB, GB, 1, 1>(a, kp, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wg_off, n_valid);
-        step<NB, GB, 2, 0>(a, kp, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wg_off, n_valid);
-        step<NB, GB, 3, 1>(a, kp, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wg_off, n_valid);
+        step<NB, GB, 0, 0>(a, kp, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_lo);
+        step<NB, GB, 1, 1>(a, kp, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_lo);
+        step<NB, GB, 2, 0>(a, kp, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_lo);
+        step<NB, GB, 3, 1>(a, kp, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_lo);
     }
     vm_wait<0>();               // no direct-to-LDS load may outlive the workgroup
     lds_barrier();
@@ -809,7 +824,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     for (int s = 0; s < kNS; ++s) {
         const float both = acc.total[s] + __shfl_xor(acc.total[s], 32);
         const int key = (wave * kNS + s) * 32 + col;
-        if (hf == 0 && key < n_valid) a.scores[j0 + key] = failed ? __uint_as_float(0x7fc00000u) : both * a.out_scale;   // quiet NaN marks a failed call
+        if (hf == 0 && key >= r_lo) a.scores[j0 + key] = failed ? __uint_as_float(0x7fc00000u) : both * a.out_scale;   // quiet NaN marks a failed call
     }
 }
 
