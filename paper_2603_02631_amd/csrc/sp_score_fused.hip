@@ -170,24 +170,42 @@ __device__ __forceinline__ void lift_at(const LaneConst &lc, bf16x8 (&f)[kKS])
 #pragma unroll
     for (int t = 0; t < kKS; ++t) f[t] = __builtin_bit_cast(bf16x8, r[t]);
 }
-// The same at a run-time (uniform) LDS offset.
-__device__ __forceinline__ void lift_dyn(const LaneConst &lc, uint32_t off, bf16x8 (&f)[kKS])
+// Both 32-key sub-tiles of a K tile (run-time slot offsets) and one 32-row Q block (compile-time
+// offset) in one round trip to LDS.
+template <int QOFF>
+__device__ __forceinline__ void lift_k_and_q(const LaneConst &lc, uint32_t koff0, uint32_t koff1,
+                                             bf16x8 (&kf)[kNS][kKS], bf16x8 (&qf)[kKS])
 {
-    u32x4 r[kKS];
-    uint32_t ad[kKS];
+    static_assert(kKS == 4 && kNS == 2 && QOFF >= 0 && QOFF < 65536, "layout of the asm block");
+    u32x4 r[12];
+    uint32_t a0[kKS], a1[kKS];
 #pragma unroll
-    for (int t = 0; t < kKS; ++t) ad[t] = lc.ld[t] + off;
+    for (int t = 0; t < kKS; ++t) { a0[t] = lc.ld[t] + koff0; a1[t] = lc.ld[t] + koff1; }
     __asm__ volatile(
-        "ds_read_b128 %0, %4\n\t"
-        "ds_read_b128 %1, %5\n\t"
-        "ds_read_b128 %2, %6\n\t"
-        "ds_read_b128 %3, %7\n\t"
+        "ds_read_b128 %0, %12\n\t"
+        "ds_read_b128 %1, %13\n\t"
+        "ds_read_b128 %2, %14\n\t"
+        "ds_read_b128 %3, %15\n\t"
+        "ds_read_b128 %8, %20 offset:%24\n\t"
+        "ds_read_b128 %9, %21 offset:%24\n\t"
+        "ds_read_b128 %10, %22 offset:%24\n\t"
+        "ds_read_b128 %11, %23 offset:%24\n\t"
+        "ds_read_b128 %4, %16\n\t"
+        "ds_read_b128 %5, %17\n\t"
+        "ds_read_b128 %6, %18\n\t"
+        "ds_read_b128 %7, %19\n\t"
         "s_waitcnt lgkmcnt(0)"
-        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
-        : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3])
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7]),
+          "=&v"(r[8]), "=&v"(r[9]), "=&v"(r[10]), "=&v"(r[11])
+        : "v"(a0[0]), "v"(a0[1]), "v"(a0[2]), "v"(a0[3]), "v"(a1[0]), "v"(a1[1]), "v"(a1[2]), "v"(a1[3]),
+          "v"(lc.ld[0]), "v"(lc.ld[1]), "v"(lc.ld[2]), "v"(lc.ld[3]), "i"(QOFF)
         : "memory");
 #pragma unroll
-    for (int t = 0; t < kKS; ++t) f[t] = __builtin_bit_cast(bf16x8, r[t]);
+    for (int t = 0; t < kKS; ++t) {
+        kf[0][t] = __builtin_bit_cast(bf16x8, r[t]);
+        kf[1][t] = __builtin_bit_cast(bf16x8, r[4 + t]);
+        qf[t] = __builtin_bit_cast(bf16x8, r[8 + t]);
+    }
 }
 
 __device__ __forceinline__ void lds_store_f32(uint32_t ad, float v)
@@ -360,61 +378,95 @@ __device__ __forceinline__ void close_layer(Acc<NB> &acc, float c)
 }
 
 // ---- statistics pass of one phase: per-wave (max, sum exp) of every row into wstats ----
+// Logits of 32 keys (one sub-tile) against 32 query rows: d[r] is key 8*(r/4) + 4*hf + r%4 of the
+// sub-tile, query row col.
+__device__ __forceinline__ f32x16 logits32(const bf16x8 (&kf)[kKS], const bf16x8 (&qf)[kKS])
+{
+    f32x16 d = {0.f};
+#pragma unroll
+    for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], d, 0, 0, 0);
+    return d;
+}
+
+// Folds the 16 logits of a lane into its running (max, sum exp); keys below lo are not this workgroup's.
+__device__ __forceinline__ void fold_logits(const f32x16 &d, float &m, float &l, float c, int lo, int hf)
+{
+    if (lo <= 0) {
+        float mn = max3(m, d[0], d[1]);      // running maximum including these 16 logits
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) mn = max3(mn, d[r], d[r + 1]);
+        l *= fast_exp2((m - mn) * c);
+        m = mn;
+        const float mc = mn * c;
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(d[r], c, -mc));
+        l += sum;
+    } else if (lo < 32) {
+        float tm = neg_inf();
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
+            if (key >= lo) tm = fmaxf(tm, d[r]);
+        }
+        if (tm > neg_inf()) {
+            const float mn = fmaxf(m, tm);
+            l *= fast_exp2((m - mn) * c);
+            m = mn;
+            const float mc = mn * c;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
+                if (key >= lo) l += fast_exp2(fmaf(d[r], c, -mc));
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ void store_row_stats(uint32_t ad, float m, float l, float c, int hf)
+{
+    const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
+    lse_merge(m, l, m2, l2, c);
+    if (hf == 0) lds_store_f2(ad, make_float2(m, l));
+}
+
+// Lifts the K tile of the phase into kf, then runs the MFMA steps one ahead of the arithmetic on
+// their results, so that the matrix pipe works under the exponentials of the previous step. One
+// tile load is issued after each of the four steps (with one row block: two per step).
 template <int NBLK, int PAR>
-__device__ __forceinline__ void stats_pass(float c, const bf16x8 (&kf)[kNS][kKS], const LaneConst &lc,
-                                           uint32_t wstats_ad, int r_lo, int wave, int lane, const KIssue &ki,
-                                           const uint32_t (&voff)[2])
+__device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t koff0,
+                                           uint32_t koff1, uint32_t wstats_ad, int r_lo, int wave, int lane,
+                                           const KIssue &ki, const uint32_t (&voff)[2])
 {
     constexpr int kPerStep = kSubInstr / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
     const int hf = lane >> 5;
-#pragma unroll
-    for (int blk = 0; blk < NBLK; ++blk) {
-        bf16x8 qf[kKS];
-        if (blk == 0) lift_at<kOffQ1 + PAR * kQTileBytes>(lc, qf); else lift_at<kOffQ1 + PAR * kQTileBytes + 4096>(lc, qf);
-        float m = neg_inf(), l = 0.f;
-#pragma unroll
-        for (int s = 0; s < kNS; ++s) {
-            f32x16 d = {0.f};
-#pragma unroll
-            for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s][t], qf[t], d, 0, 0, 0);
-            // d[r]: key (wave*2+s)*32 + 8*(r/4) + 4*hf + r%4 of the tile, query row blk*32 + col
-            const int lo = r_lo - (wave * kNS + s) * 32;      // keys below lo belong to the previous workgroup
-            if (lo <= 0) {
-                float mn = max3(m, d[0], d[1]);      // running maximum including these 16 logits
-#pragma unroll
-                for (int r = 2; r < 16; r += 2) mn = max3(mn, d[r], d[r + 1]);
-                l *= fast_exp2((m - mn) * c);
-                m = mn;
-                const float mc = mn * c;
-                float sum = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(d[r], c, -mc));
-                l += sum;
-            } else if (lo < 32) {
-                float tm = neg_inf();
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
-                    if (key >= lo) tm = fmaxf(tm, d[r]);
-                }
-                if (tm > neg_inf()) {
-                    const float mn = fmaxf(m, tm);
-                    l *= fast_exp2((m - mn) * c);
-                    m = mn;
-                    const float mc = mn * c;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
-                        if (key >= lo) l += fast_exp2(fmaf(d[r], c, -mc));
-                    }
-                }
-            }
-            k_issue<kPerStep>(ki, voff, (blk * kNS + s) * kPerStep);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
-        lse_merge(m, l, m2, l2, c);
-        if (hf == 0) lds_store_f2(wstats_ad + blk * 256, make_float2(m, l));
+    const int lo0 = r_lo - wave * kNS * 32, lo1 = lo0 - 32;
+    bf16x8 qf[kKS];
+    lift_k_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, qf);
+    f32x16 da = logits32(kf[0], qf);
+    f32x16 db = logits32(kf[1], qf);
+    float m = neg_inf(), l = 0.f;
+    fold_logits(da, m, l, c, lo0, hf);
+    k_issue<kPerStep>(ki, voff, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (NBLK == 2) {
+        lift_at<kOffQ1 + PAR * kQTileBytes + 4096>(lc, qf);
+        da = logits32(kf[0], qf);
+    }
+    fold_logits(db, m, l, c, lo1, hf);
+    store_row_stats(wstats_ad, m, l, c, hf);
+    k_issue<kPerStep>(ki, voff, kPerStep);
+    __builtin_amdgcn_sched_barrier(0);
+    if (NBLK == 2) {
+        db = logits32(kf[1], qf);
+        m = neg_inf(); l = 0.f;
+        fold_logits(da, m, l, c, lo0, hf);
+        k_issue<kPerStep>(ki, voff, 2 * kPerStep);
+        __builtin_amdgcn_sched_barrier(0);
+        fold_logits(db, m, l, c, lo1, hf);
+        store_row_stats(wstats_ad + 256, m, l, c, hf);
+        k_issue<kPerStep>(ki, voff, 3 * kPerStep);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -627,10 +679,9 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
         ki.base = kbase + (int64_t)32 * stride_bytes;
         ki.step_bytes = 8u * stride_bytes;
         if (do_stats) {
-#pragma unroll
-            for (int s2 = 0; s2 < kNS; ++s2) lift_dyn(lc, sub_slot_off(wave, wk.slot0, s2), ring.kf[SLOT][s2]);
             const uint32_t wstats_ad = lds0 + kOffWstats + PAR * kWstatsBytes + wave * (kMaxRowsF * 8) + ((uint32_t)(lane & 31) << 3);
-            stats_pass<NB * GB, PAR>(a.c, ring.kf[SLOT], lc, wstats_ad, r_lo, wave, lane, ki, voff);
+            stats_pass<NB * GB, PAR>(a.c, ring.kf[SLOT], lc, sub_slot_off(wave, wk.slot0, 0),
+                                     sub_slot_off(wave, wk.slot0, 1), wstats_ad, r_lo, wave, lane, ki, voff);
         } else {
             k_issue<kSubInstr>(ki, voff, 0);
         }
