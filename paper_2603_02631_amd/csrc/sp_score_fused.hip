@@ -208,6 +208,34 @@ __device__ __forceinline__ void lift_k_and_q(const LaneConst &lc, uint32_t koff0
     }
 }
 
+// One 32-row Q block (compile-time offset) and the sixteen accumulator seeds at seed_ad (64-byte
+// aligned) in one round trip to LDS.
+template <int QOFF>
+__device__ __forceinline__ void lift_q_and_seed(const LaneConst &lc, uint32_t seed_ad, bf16x8 (&qf)[kKS], f32x16 &seed)
+{
+    static_assert(kKS == 4 && QOFF >= 0 && QOFF < 65536, "layout of the asm block");
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    u32x4 r[kKS];
+    f32x4 c[4];
+    __asm__ volatile(
+        "ds_read_b128 %0, %8 offset:%13\n\t"
+        "ds_read_b128 %1, %9 offset:%13\n\t"
+        "ds_read_b128 %2, %10 offset:%13\n\t"
+        "ds_read_b128 %3, %11 offset:%13\n\t"
+        "ds_read_b128 %4, %12\n\t"
+        "ds_read_b128 %5, %12 offset:16\n\t"
+        "ds_read_b128 %6, %12 offset:32\n\t"
+        "ds_read_b128 %7, %12 offset:48\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(c[0]), "=&v"(c[1]), "=&v"(c[2]), "=&v"(c[3])
+        : "v"(lc.ld[0]), "v"(lc.ld[1]), "v"(lc.ld[2]), "v"(lc.ld[3]), "v"(seed_ad), "i"(QOFF)
+        : "memory");
+#pragma unroll
+    for (int t = 0; t < kKS; ++t) qf[t] = __builtin_bit_cast(bf16x8, r[t]);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) { seed[4 * v] = c[v].x; seed[4 * v + 1] = c[v].y; seed[4 * v + 2] = c[v].z; seed[4 * v + 3] = c[v].w; }
+}
+
 __device__ __forceinline__ void lds_store_f32(uint32_t ad, float v)
 {
     __asm__ volatile("ds_write_b32 %0, %1" : : "v"(ad), "v"(v) : "memory");
@@ -216,26 +244,6 @@ __device__ __forceinline__ void lds_store_f2(uint32_t ad, float2 v)
 {
     __asm__ volatile("ds_write_b64 %0, %1" : : "v"(ad), "v"(v) : "memory");
 }
-// Sixteen consecutive floats (64-byte aligned).
-__device__ __forceinline__ f32x16 lds_load_f16(uint32_t ad)
-{
-    typedef __attribute__((ext_vector_type(4))) float f32x4;
-    f32x4 r[4];
-    __asm__ volatile(
-        "ds_read_b128 %0, %4\n\t"
-        "ds_read_b128 %1, %4 offset:16\n\t"
-        "ds_read_b128 %2, %4 offset:32\n\t"
-        "ds_read_b128 %3, %4 offset:48\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
-        : "v"(ad)
-        : "memory");
-    f32x16 o;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) { o[4 * v] = r[v].x; o[4 * v + 1] = r[v].y; o[4 * v + 2] = r[v].z; o[4 * v + 3] = r[v].w; }
-    return o;
-}
-
 // Butterfly reductions with data-parallel-primitive moves: after the three steps every lane of an
 // aligned group of 8 holds the group's result; one more step extends it to the row of 16. Every
 // lane adds the same two operands in either order, so the results are identical across lanes.
@@ -331,19 +339,23 @@ struct Acc {
 };
 
 // ---- probability pass of one phase from the fragment ring; tile loads are issued between the MFMA steps ----
+constexpr int kMidInstr = 2;              // of the four loads of sub-tile 0: issued right after the barrier ...
+constexpr int kProbInstr = kSubInstr - kMidInstr;     // ... and between the MFMA steps of the probability pass
+
 template <int NB, int GB, int PAR>
 __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t cinit_ad,
                                           Acc<NB> &acc, const KIssue &ki, const uint32_t (&voff)[2])
 {
-    constexpr int kPerStep = kSubInstr / (NB * GB * kNS);
+    static_assert(kProbInstr == 2 && (NB * GB == 1 || NB * GB == 2), "one load per row block, or one per step");
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
         for (int gb = 0; gb < GB; ++gb) {
             const int blk = gb * NB + nb;
             bf16x8 qf[kKS];
-            if (blk == 0) lift_at<kOffQ2 + PAR * kQTileBytes>(lc, qf); else lift_at<kOffQ2 + PAR * kQTileBytes + 4096>(lc, qf);
-            const f32x16 ci = lds_load_f16(cinit_ad + blk * 128);
+            f32x16 ci;
+            if (blk == 0) lift_q_and_seed<kOffQ2 + PAR * kQTileBytes>(lc, cinit_ad, qf, ci);
+            else lift_q_and_seed<kOffQ2 + PAR * kQTileBytes + 4096>(lc, cinit_ad + 128, qf, ci);
 #pragma unroll
             for (int s = 0; s < kNS; ++s) {
                 f32x16 d = ci;
@@ -353,7 +365,8 @@ __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const La
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     acc.mx[s][nb][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[s][nb][e]);
-                k_issue<kPerStep>(ki, voff, ((nb * GB + gb) * kNS + s) * kPerStep);
+                if (NB * GB == 1) k_issue<1>(ki, voff, kMidInstr + s);
+                else if (s == kNS - 1) k_issue<1>(ki, voff, kMidInstr + blk);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -637,6 +650,16 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
             stage_duty_block(lds0 + kOffXduty, a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad, a.rows_pad, a.n_wg,
                              duty_blk * kDutyRows, lane);
     }
+    const char *kbase = wk.kptr;
+    int slot_next = wk.slot0 + 2;         // sub-tile 0 of phase s + 1
+    slot_next = slot_next >= kSubSlots ? slot_next - kSubSlots : slot_next;
+    // past the last phase the loads shrink to one 16-byte piece per instruction: the count stays fixed
+    const uint32_t live = s + 1 < n_phases ? 0xffffffffu : 0u;
+    const uint32_t voff[2] = {lc.koff[0] & live, lc.koff[1] & live};
+    KIssue ki;
+    ki.lds_dst = lds0 + sub_slot_off(wave, slot_next, 0);
+    ki.base = kbase;
+    ki.step_bytes = 8u * stride_bytes;
     if (lc.qoff >= 0) {       // padding rows of the Q tiles stay zero; the Q blocks of consecutive phases are contiguous
         const uint32_t qblock = (uint32_t)(a.group * a.n_q * kD * 2);
         const char *q1src = reinterpret_cast<const char *>(a.q) + (uint32_t)min(s + 1, n_phases - 1) * qblock;
@@ -644,26 +667,17 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
         dma_u((uint32_t)lc.qoff, q1src, lds0 + kOffQ1 + (1 - PAR) * kQTileBytes + wave * 1024);
         dma_u((uint32_t)lc.qoff, q2src, lds0 + kOffQ2 + PAR * kQTileBytes + wave * 1024);
     }
+    k_issue<kMidInstr>(ki, voff, 0);
 
     // ---- probability pass of phase pc; sub-tile 0 of K(s+1) ----
-    const char *kbase = wk.kptr;
-    int slot_next = wk.slot0 + 2;         // sub-tile 0 of phase s + 1
-    slot_next = slot_next >= kSubSlots ? slot_next - kSubSlots : slot_next;
-    // past the last phase the loads shrink to one 16-byte piece per instruction: the count stays fixed
-    const uint32_t live = s + 1 < n_phases ? 0xffffffffu : 0u;
-    const uint32_t voff[2] = {lc.koff[0] & live, lc.koff[1] & live};
     {
-        KIssue ki;
-        ki.lds_dst = lds0 + sub_slot_off(wave, slot_next, 0);
-        ki.base = kbase;
-        ki.step_bytes = 8u * stride_bytes;
         if (do_prob) {
             const uint32_t cinit_ad = lds0 + kOffCinit + (1 - PAR) * (kMaxRowsF * 4) + ((uint32_t)(lane & 32) << 1);
             prob_pass<NB, GB, 1 - PAR>(ring.kf[SLOT], lc, cinit_ad, acc, ki, voff);
             if (wk.c.kv == a.n_kv_heads - 1 && (a.layer_agg == SP_LAYER_MEAN || wk.c.layer == a.n_layers - 1))
                 close_layer<NB>(acc, a.c);
         } else {
-            k_issue<kSubInstr>(ki, voff, 0);
+            k_issue<kProbInstr>(ki, voff, kMidInstr);
         }
     }
     if (wave == kLseWave) {
