@@ -390,6 +390,13 @@ __device__ __forceinline__ void close_layer(Acc<NB> &acc, float c)
     }
 }
 
+// 64 x 16 bytes: the 16-byte pairs 0 .. 63 of a row of 8-byte entries (row 16-byte aligned) that
+// holds `pairs` pairs; lanes beyond the row repeat its last pair.
+__device__ __forceinline__ void stage_entries(uint32_t lds_dst, const uint64_t *row, int pairs, int lane)
+{
+    dma_v_device(row + 2 * min(lane, pairs - 1), lds_dst);
+}
+
 // ---- statistics pass of one phase: per-wave (max, sum exp) of every row into wstats ----
 // Logits of 32 keys (one sub-tile) against 32 query rows: d[r] is key 8*(r/4) + 4*hf + r%4 of the
 // sub-tile, query row col.
@@ -445,11 +452,17 @@ __device__ __forceinline__ void store_row_stats(uint32_t ad, float m, float l, f
 
 // Lifts the K tile of the phase into kf, then runs the MFMA steps one ahead of the arithmetic on
 // their results, so that the matrix pipe works under the exponentials of the previous step. One
-// tile load is issued after each of the four steps (with one row block: two per step).
+// tile load is issued after each of the four steps (with one row block: two per step). On the
+// normaliser wave (lse_row != nullptr) the request for the normalisers follows the first step: late
+// enough for the duty workgroups' stores to be visible, early enough to land before the barrier.
+template <int NBLK>
+constexpr int kLoadsBehindLse = kSubInstr - kSubInstr / (NBLK * kNS);
+
 template <int NBLK, int PAR>
 __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t koff0,
                                            uint32_t koff1, uint32_t wstats_ad, int r_lo, int wave, int lane,
-                                           const KIssue &ki, const uint32_t (&voff)[2])
+                                           const KIssue &ki, const uint32_t (&voff)[2], const uint64_t *lse_row,
+                                           int rows_pad, uint32_t xlse_ad)
 {
     constexpr int kPerStep = kSubInstr / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
     const int hf = lane >> 5;
@@ -461,6 +474,7 @@ __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], cons
     float m = neg_inf(), l = 0.f;
     fold_logits(da, m, l, c, lo0, hf);
     k_issue<kPerStep>(ki, voff, 0);
+    if (lse_row != nullptr) stage_entries(xlse_ad, lse_row, rows_pad / 2, lane);
     __builtin_amdgcn_sched_barrier(0);
     if (NBLK == 2) {
         lift_at<kOffQ1 + PAR * kQTileBytes + 4096>(lc, qf);
@@ -528,13 +542,6 @@ __device__ __forceinline__ uint64_t read_lse_staging(uint32_t lds0, int lane)
     return v;
 }
 
-// 64 x 16 bytes: the 16-byte pairs 0 .. 63 of a row of 8-byte entries (row 16-byte aligned) that
-// holds `pairs` pairs; lanes beyond the row repeat its last pair.
-__device__ __forceinline__ void stage_entries(uint32_t lds_dst, const uint64_t *row, int pairs, int lane)
-{
-    dma_v_device(row + 2 * min(lane, pairs - 1), lds_dst);
-}
-
 // The partials of rows row0 .. row0+3 of one exchange slot from every workgroup: eight loads.
 __device__ __forceinline__ void stage_duty_block(uint32_t xduty, const uint64_t *slot_base, int rows_pad, int n_wg,
                                                  int row0, int lane)
@@ -576,9 +583,9 @@ struct Walk {
 //           partials of its duty rows of phase s-2; every wave requests its slices of Q(s+1) for
 //           the next statistics pass and of Q(s-3) for the next probability pass
 //   prob    probability pass of phase s-4 from ring slot s%4; loads of sub-tile 0 of K(s+1)
-//   lse     the normaliser wave requests the normalisers of phase s-3
 //   lift    wait for sub-tile 1 of K(s); lift K(s) into ring slot s%4
-//   stats   statistics pass of phase s; loads of sub-tile 1 of K(s+1)
+//   stats   statistics pass of phase s; loads of sub-tile 1 of K(s+1); after its first step the
+//           normaliser wave requests the normalisers of phase s-3
 //   pre     wait for the Q slices (and the exchange data); duty wave: combine the duty rows of phase
 //           s-2 and publish their normalisers; normaliser wave: seeds of the probability pass of phase s-3
 //   barrier
@@ -680,10 +687,6 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
             k_issue<kProbInstr>(ki, voff, kMidInstr);
         }
     }
-    if (wave == kLseWave) {
-        const int pn = clampi(pl, 0, n_phases - 1);
-        stage_entries(lds0 + kOffXlse, a.lse + (size_t)(pn % kSlots) * a.rows_pad, a.rows_pad / 2, lane);
-    }
 
     // ---- lift K(s), statistics pass of phase s; sub-tile 1 of K(s+1) ----
     vm_wait<kSubInstr>();                 // behind sub-tile 1 of K(s): at least the 4 loads of the prob part
@@ -692,17 +695,20 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
         ki.lds_dst = lds0 + sub_slot_off(wave, slot_next, 1);
         ki.base = kbase + (int64_t)32 * stride_bytes;
         ki.step_bytes = 8u * stride_bytes;
+        const uint64_t *lse_row = wave == kLseWave ? a.lse + (size_t)(clampi(pl, 0, n_phases - 1) % kSlots) * a.rows_pad : nullptr;
         if (do_stats) {
             const uint32_t wstats_ad = lds0 + kOffWstats + PAR * kWstatsBytes + wave * (kMaxRowsF * 8) + ((uint32_t)(lane & 31) << 3);
             stats_pass<NB * GB, PAR>(a.c, ring.kf[SLOT], lc, sub_slot_off(wave, wk.slot0, 0),
-                                     sub_slot_off(wave, wk.slot0, 1), wstats_ad, r_lo, wave, lane, ki, voff);
+                                     sub_slot_off(wave, wk.slot0, 1), wstats_ad, r_lo, wave, lane, ki, voff, lse_row,
+                                     a.rows_pad, lds0 + kOffXlse);
         } else {
+            if (lse_row != nullptr) stage_entries(lds0 + kOffXlse, lse_row, a.rows_pad / 2, lane);
             k_issue<kSubInstr>(ki, voff, 0);
         }
     }
 
     // ---- pre-barrier: exchange data in, seeds out ----
-    if (wave == kLseWave) vm_wait<kSubInstr>(); else vm_wait<2 * kSubInstr>();
+    if (wave == kLseWave) vm_wait<kLoadsBehindLse<NB * GB>>(); else vm_wait<2 * kSubInstr>();
     int *fail = reinterpret_cast<int *>(lds + kOffFail);
     if (wave == kDutyWave) {
         if (duty_blk >= 0) {
