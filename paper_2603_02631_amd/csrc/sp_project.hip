@@ -22,26 +22,57 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / 64;
 
-// first index i in [0, n) with a[i] > v   (n if none)
-__device__ __forceinline__ int64_t upper_bound(const int64_t *a, int64_t n, int64_t v)
+// Both searches of a span run side by side as 8-ary searches: each round issues seven independent
+// probes per search, so a span costs about six rounds of memory latency instead of two times
+// seventeen dependent loads.
+//   ub: first index i in [0, n) with a[i] >  v_ub  (n if none), searched in a_ub
+//   lb: first index i in [0, n) with a[i] >= v_lb  (n if none), searched in a_lb
+struct Range { int64_t lo, hi; };     // the answer lies in [lo, hi]; everything below lo fails, hi and above pass
+
+template <bool STRICT>
+__device__ __forceinline__ void kary_round(const int64_t *a, int64_t v, Range &r)
 {
-    int64_t lo = 0, hi = n;
-    while (lo < hi) {
-        const int64_t mid = lo + ((hi - lo) >> 1);
-        if (a[mid] > v) hi = mid; else lo = mid + 1;
+    constexpr int K = 8;
+    const int64_t n = r.hi - r.lo;
+    if (n <= 0) return;
+    int64_t probe[K - 1];
+    int64_t val[K - 1];
+    if (n < K) {
+#pragma unroll
+        for (int j = 0; j < K - 1; ++j) probe[j] = r.lo + (j < n ? j : n - 1);
+    } else {
+        const int64_t step = n / K;
+#pragma unroll
+        for (int j = 0; j < K - 1; ++j) probe[j] = r.lo + (j + 1) * step;
     }
-    return lo;
+#pragma unroll
+    for (int j = 0; j < K - 1; ++j) val[j] = a[probe[j]];
+    // the predicate is monotone along the probes: count the failures
+    int64_t lo = r.lo, hi = r.hi;
+#pragma unroll
+    for (int j = K - 2; j >= 0; --j) {
+        const bool pass = STRICT ? (val[j] > v) : (val[j] >= v);
+        if (pass) hi = probe[j];
+    }
+#pragma unroll
+    for (int j = 0; j < K - 1; ++j) {
+        const bool pass = STRICT ? (val[j] > v) : (val[j] >= v);
+        if (!pass && probe[j] + 1 > lo) lo = probe[j] + 1;
+    }
+    r.lo = lo;
+    r.hi = hi < lo ? lo : hi;
 }
 
-// first index i in [0, n) with a[i] >= v   (n if none)
-__device__ __forceinline__ int64_t lower_bound(const int64_t *a, int64_t n, int64_t v)
+__device__ __forceinline__ void two_searches(const int64_t *a_ub, int64_t v_ub, const int64_t *a_lb, int64_t v_lb,
+                                             int64_t n, int64_t &ub, int64_t &lb)
 {
-    int64_t lo = 0, hi = n;
-    while (lo < hi) {
-        const int64_t mid = lo + ((hi - lo) >> 1);
-        if (a[mid] >= v) hi = mid; else lo = mid + 1;
+    Range r1 = {0, n}, r2 = {0, n};
+    while (r1.lo < r1.hi || r2.lo < r2.hi) {
+        kary_round<true>(a_ub, v_ub, r1);
+        kary_round<false>(a_lb, v_lb, r2);
     }
-    return lo;
+    ub = r1.lo;
+    lb = r2.lo;
 }
 
 struct ScanSmem {
@@ -99,8 +130,8 @@ __global__ __launch_bounds__(kThreads) void sp_project_spans_kernel(
             a = a < 0 ? 0 : (a > L ? L : a);
             b = b < 0 ? 0 : (b > L ? L : b);
             const int64_t cs = draft_off[a], ce = draft_off[b];
-            lo = upper_bound(target_off + 1, M, cs);      // first t with target_off[t+1] > cs
-            hi = lower_bound(target_off, M, ce);          // first t with target_off[t] >= ce  (M if none)
+            // lo: first t with target_off[t+1] > cs;  hi: first t with target_off[t] >= ce  (M if none)
+            two_searches(target_off + 1, cs, target_off, ce, M, lo, hi);
             nonempty = lo < hi;
         }
         // exclusive running maximum of the ends of earlier non-empty ranges

@@ -125,15 +125,16 @@ __global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__re
             if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
         }
         __syncthreads();
-        if (tid == 0) {
-            int64_t above = 0;
-            int b = 255;
-            for (; b > 0; --b) {
-                if (above + hist[b] >= need) break;
-                above += hist[b];
+        {
+            // thread t looks at bucket 255 - t: an inclusive scan gives the number of candidates in
+            // this bucket and above; the bucket where that count first reaches `need` holds the k-th
+            const int h = tid < 256 ? hist[255 - tid] : 0;
+            int total;
+            const int incl = block_scan_incl(h, wave_tot, total);
+            if (tid < 256 && (int64_t)(incl - h) < need && (int64_t)incl >= need) {
+                s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+                s_need = need - (incl - h);
             }
-            s_prefix = prefix | ((uint32_t)b << shift);
-            s_need = need - above;
         }
         __syncthreads();
         prefix = s_prefix;
