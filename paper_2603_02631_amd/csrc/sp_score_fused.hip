@@ -136,12 +136,15 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)r
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ uint32_t uniform32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
-__device__ __forceinline__ void dma_u(uint32_t lane_off, const void *base, uint32_t lds_dst)
+// The LDS destination is lds_base + LDS_IMM: call sites that differ only in the constant share one
+// scalar register for the base.
+template <int LDS_IMM>
+__device__ __forceinline__ void dma_u(uint32_t lane_off, const void *base, uint32_t lds_base)
 {
     const uint64_t b = reinterpret_cast<uintptr_t>(base);
     const uint64_t ub = (uint64_t)uniform32((uint32_t)b) | ((uint64_t)uniform32((uint32_t)(b >> 32)) << 32);
-    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                     : : "v"(lane_off), "s"(ub), "s"(uniform32(lds_dst)) : "memory", "m0");
+    __asm__ volatile("s_add_i32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     : : "v"(lane_off), "s"(ub), "s"(uniform32(lds_base)), "i"(LDS_IMM) : "memory", "m0", "scc");
 }
 // Per-lane addresses, bypassing the non-coherent cache levels like the atomic loads of the retry paths do.
 __device__ __forceinline__ void dma_v_device(const void *addr, uint32_t lds_dst)
@@ -314,13 +317,23 @@ struct KIssue {
 };
 
 // Issues instructions first .. first+COUNT-1 of the sub-tile (first and COUNT compile-time at call sites).
+template <int IDX>
+__device__ __forceinline__ void k_issue_one(const KIssue &ki, const uint32_t (&voff)[2])
+{
+    dma_u<IDX * 1024>(voff[IDX & 1], ki.base + (uint32_t)IDX * ki.step_bytes, ki.lds_dst);
+}
 template <int COUNT>
 __device__ __forceinline__ void k_issue(const KIssue &ki, const uint32_t (&voff)[2], int first)
 {
+    static_assert(kSubInstr == 4, "instruction indices 0..3");
 #pragma unroll
     for (int i = 0; i < COUNT; ++i) {
-        const int idx = first + i;
-        dma_u(voff[idx & 1], ki.base + (uint32_t)idx * ki.step_bytes, ki.lds_dst + idx * 1024);
+        switch (first + i) {          // compile-time after unrolling
+        case 0: k_issue_one<0>(ki, voff); break;
+        case 1: k_issue_one<1>(ki, voff); break;
+        case 2: k_issue_one<2>(ki, voff); break;
+        default: k_issue_one<3>(ki, voff); break;
+        }
     }
 }
 
@@ -671,8 +684,8 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
         const uint32_t qblock = (uint32_t)(a.group * a.n_q * kD * 2);
         const char *q1src = reinterpret_cast<const char *>(a.q) + (uint32_t)min(s + 1, n_phases - 1) * qblock;
         const char *q2src = reinterpret_cast<const char *>(a.q) + (uint32_t)clampi(pl, 0, n_phases - 1) * qblock;
-        dma_u((uint32_t)lc.qoff, q1src, lds0 + kOffQ1 + (1 - PAR) * kQTileBytes + wave * 1024);
-        dma_u((uint32_t)lc.qoff, q2src, lds0 + kOffQ2 + PAR * kQTileBytes + wave * 1024);
+        dma_u<kOffQ1 + (1 - PAR) * kQTileBytes>((uint32_t)lc.qoff, q1src, lds0 + wave * 1024);
+        dma_u<kOffQ2 + PAR * kQTileBytes>((uint32_t)lc.qoff, q2src, lds0 + wave * 1024);
     }
     k_issue<kMidInstr>(ki, voff, 0);
 
@@ -858,7 +871,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     wave_off = (uint64_t)uniform32((uint32_t)wave_off) | ((uint64_t)uniform32((uint32_t)(wave_off >> 32)) << 32);
 
     // prologue: this wave's slice of Q(0) and both sub-tiles of K(0); everything lands before step 0
-    if (lc.qoff >= 0) dma_u((uint32_t)lc.qoff, a.q, lds0 + kOffQ1 + wave_u * 1024);
+    if (lc.qoff >= 0) dma_u<kOffQ1>((uint32_t)lc.qoff, a.q, lds0 + wave_u * 1024);
 #pragma unroll
     for (int s2 = 0; s2 < kNS; ++s2) {
         KIssue ki;
