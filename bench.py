@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0
 # It is reported only while the kernel sources are the ones the counters were taken on.
 TRAFFIC = {
     "workload": "long-128k",
-    "sources_sha256": "591acec30fadf6a21f6f0cd870fa12356d3d9bea8a249da51fe5802049c2a0c3",
-    "fetch_bytes": 1090800.6 * 2048,      # FETCH_SIZE 1090800.6 per dispatch; the 1 GiB copy reads 524288 -> 2 KiB per count
+    "sources_sha256": "1844e227a3e32bc01fbb88458b7985cddc51ba0136fc3406488c54b212435af3",
+    "fetch_bytes": 1090918.9 * 2048,      # FETCH_SIZE 1090918.9 per dispatch; the 1 GiB copy reads 524288 -> 2 KiB per count
     "write_bytes": 16960.0 * 1024,        # WRITE_SIZE 16960.0 per dispatch; the 1 GiB copy writes 1048576 -> 1 KiB per count
 }
 KERNEL_SOURCES = ["sp_score_fused.hip", "sp_score_fused.hpp", "sp_score_dev.hpp", "sp_score.hip"]
