@@ -11,8 +11,10 @@
 // so ranges that overlap or touch are merged with an exclusive running maximum
 // of the range ends and a prefix sum of "starts a new range" flags.
 //
-//   sp_project_spans_kernel  one workgroup: searches, scans, merged target
-//                            ranges, their count and the kept-token total.
+//   sp_project_search_kernel one wave per (span, end): 64-ary search of the
+//                            target offsets, three rounds of memory latency.
+//   sp_project_spans_kernel  one workgroup: scans, merged target ranges,
+//                            their count and the kept-token total.
 //   sp_project_mask_kernel   one thread per target token: binary search of the
 //                            merged ranges, writes the 0/1 keep mask.
 #include "sp_common.hpp"
@@ -22,57 +24,31 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / 64;
 
-// Both searches of a span run side by side as 8-ary searches: each round issues seven independent
-// probes per search, so a span costs about six rounds of memory latency instead of two times
-// seventeen dependent loads.
-//   ub: first index i in [0, n) with a[i] >  v_ub  (n if none), searched in a_ub
-//   lb: first index i in [0, n) with a[i] >= v_lb  (n if none), searched in a_lb
-struct Range { int64_t lo, hi; };     // the answer lies in [lo, hi]; everything below lo fails, hi and above pass
-
+// 64-ary search by one wave: first index i in [0, n) with a[i] > v (STRICT) or a[i] >= v, n if
+// none. Each round every lane probes one position; the predicate is monotone along the lanes, so
+// a ballot gives the sub-interval. 64^3 > 2.6e5 positions take three rounds.
 template <bool STRICT>
-__device__ __forceinline__ void kary_round(const int64_t *a, int64_t v, Range &r)
+__device__ __forceinline__ int64_t wave_search(const int64_t *a, int64_t n, int64_t v, int lane)
 {
-    constexpr int K = 8;
-    const int64_t n = r.hi - r.lo;
-    if (n <= 0) return;
-    int64_t probe[K - 1];
-    int64_t val[K - 1];
-    if (n < K) {
-#pragma unroll
-        for (int j = 0; j < K - 1; ++j) probe[j] = r.lo + (j < n ? j : n - 1);
-    } else {
-        const int64_t step = n / K;
-#pragma unroll
-        for (int j = 0; j < K - 1; ++j) probe[j] = r.lo + (j + 1) * step;
+    int64_t lo = 0, hi = n;                     // the answer lies in [lo, hi]
+    while (lo < hi) {
+        const int64_t cnt = hi - lo;
+        const int64_t step = (cnt + 63) / 64;   // >= 1
+        int64_t p = lo + (lane + 1) * step - 1;
+        p = p < hi - 1 ? p : hi - 1;
+        const int64_t val = a[p];
+        const bool pass = STRICT ? (val > v) : (val >= v);
+        const unsigned long long m = __ballot(pass);
+        if (m == 0ull) { lo = hi; break; }      // the last lane probed hi - 1
+        const int f = __ffsll((long long)m) - 1;
+        int64_t pf = lo + (int64_t)(f + 1) * step - 1;
+        pf = pf < hi - 1 ? pf : hi - 1;
+        int64_t pprev = lo + (int64_t)f * step - 1;       // probe of lane f - 1 (fails); lo - 1 for f = 0
+        pprev = pprev < hi - 1 ? pprev : hi - 1;
+        hi = pf;
+        lo = pprev + 1;
     }
-#pragma unroll
-    for (int j = 0; j < K - 1; ++j) val[j] = a[probe[j]];
-    // the predicate is monotone along the probes: count the failures
-    int64_t lo = r.lo, hi = r.hi;
-#pragma unroll
-    for (int j = K - 2; j >= 0; --j) {
-        const bool pass = STRICT ? (val[j] > v) : (val[j] >= v);
-        if (pass) hi = probe[j];
-    }
-#pragma unroll
-    for (int j = 0; j < K - 1; ++j) {
-        const bool pass = STRICT ? (val[j] > v) : (val[j] >= v);
-        if (!pass && probe[j] + 1 > lo) lo = probe[j] + 1;
-    }
-    r.lo = lo;
-    r.hi = hi < lo ? lo : hi;
-}
-
-__device__ __forceinline__ void two_searches(const int64_t *a_ub, int64_t v_ub, const int64_t *a_lb, int64_t v_lb,
-                                             int64_t n, int64_t &ub, int64_t &lb)
-{
-    Range r1 = {0, n}, r2 = {0, n};
-    while (r1.lo < r1.hi || r2.lo < r2.hi) {
-        kary_round<true>(a_ub, v_ub, r1);
-        kary_round<false>(a_lb, v_lb, r2);
-    }
-    ub = r1.lo;
-    lb = r2.lo;
+    return lo;
 }
 
 struct ScanSmem {
@@ -107,10 +83,27 @@ __device__ __forceinline__ void block_scan(int64_t &mx, int &sum, ScanSmem &sm, 
     sum += bs;
 }
 
-__global__ __launch_bounds__(kThreads) void sp_project_spans_kernel(
+// Raw target range of every span: tspans[2s] = first t with target_off[t+1] > cs,
+// tspans[2s+1] = first t with target_off[t] >= ce (M if none).
+__global__ __launch_bounds__(kThreads) void sp_project_search_kernel(
     const int64_t *__restrict__ draft_off, int64_t L, const int64_t *__restrict__ target_off, int64_t M,
-    const int64_t *__restrict__ spans, const int32_t *__restrict__ n_spans_p, int max_spans, int64_t *tspans,
-    int32_t *n_tspans, int64_t *n_kept)
+    const int64_t *__restrict__ spans, const int32_t *__restrict__ n_spans_p, int max_spans, int64_t *tspans)
+{
+    const int lane = threadIdx.x & 63;
+    const int gw = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const int s = gw >> 1, end = gw & 1;
+    int n_spans = *n_spans_p;
+    if (n_spans > max_spans) n_spans = max_spans;
+    if (s >= n_spans) return;
+    int64_t tok = spans[2 * s + end];
+    tok = tok < 0 ? 0 : (tok > L ? L : tok);
+    const int64_t ch = draft_off[tok];
+    const int64_t r = end == 0 ? wave_search<true>(target_off + 1, M, ch, lane) : wave_search<false>(target_off, M, ch, lane);
+    if (lane == 0) tspans[2 * s + end] = r;
+}
+
+__global__ __launch_bounds__(kThreads) void sp_project_spans_kernel(
+    const int32_t *__restrict__ n_spans_p, int max_spans, int64_t *tspans, int32_t *n_tspans, int64_t *n_kept)
 {
     __shared__ ScanSmem sm;
     __shared__ int64_t red[kWavesPerBlock];
@@ -125,13 +118,9 @@ __global__ __launch_bounds__(kThreads) void sp_project_spans_kernel(
         const int s = base + tid;
         int64_t lo = 0, hi = 0;
         bool nonempty = false;
-        if (s < n_spans) {
-            int64_t a = spans[2 * s], b = spans[2 * s + 1];
-            a = a < 0 ? 0 : (a > L ? L : a);
-            b = b < 0 ? 0 : (b > L ? L : b);
-            const int64_t cs = draft_off[a], ce = draft_off[b];
-            // lo: first t with target_off[t+1] > cs;  hi: first t with target_off[t] >= ce  (M if none)
-            two_searches(target_off + 1, cs, target_off, ce, M, lo, hi);
+        if (s < n_spans) {          // raw range from the search kernel; merged ranges are written back in place
+            lo = tspans[2 * s];     // (an entry is overwritten only after its segment has been read: r <= s)
+            hi = tspans[2 * s + 1];
             nonempty = lo < hi;
         }
         // exclusive running maximum of the ends of earlier non-empty ranges
@@ -207,8 +196,12 @@ extern "C" sp_status sp_project(const int64_t *draft_off_dev, int64_t L, const i
     if (max_spans < 1 || max_spans > (1 << 24))
         return sp::fail(SP_ERR_INVALID_ARG, "max_spans = %d outside 1..2^24", max_spans);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    hipLaunchKernelGGL(sp_project_spans_kernel, dim3(1), dim3(kThreads), 0, st, draft_off_dev, L, target_off_dev, M,
-                       spans_dev, n_spans_dev, (int)max_spans, tspans_dev, n_tspans_dev, n_kept_dev);
+    const unsigned search_grid = (unsigned)((2 * (int64_t)max_spans + kWavesPerBlock - 1) / kWavesPerBlock);
+    hipLaunchKernelGGL(sp_project_search_kernel, dim3(search_grid), dim3(kThreads), 0, st, draft_off_dev, L,
+                       target_off_dev, M, spans_dev, n_spans_dev, (int)max_spans, tspans_dev);
+    SP_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(sp_project_spans_kernel, dim3(1), dim3(kThreads), 0, st, n_spans_dev, (int)max_spans,
+                       tspans_dev, n_tspans_dev, n_kept_dev);
     SP_HIP_CHECK(hipGetLastError());
     if (keep_mask_dev) {
         const unsigned grid = (unsigned)((M + kThreads - 1) / kThreads);
