@@ -419,7 +419,7 @@ bool fused_shape_ok(const Plan &p) { return p.D == 64 && p.rows_pad <= sp_fused:
 
 int fused_workgroups(int64_t L) { return (int)((L + sp_fused::kTileKeys - 1) / sp_fused::kTileKeys); }
 
-bool fused_applies(const Plan &p, int64_t L);
+bool fused_applies(const Plan &p, int64_t L, int64_t k_stride_token);
 
 // Compute units of the current device (0 if it cannot be queried); the fused kernel needs one per workgroup.
 int device_compute_units()
@@ -438,9 +438,10 @@ int device_compute_units()
 }
 
 // The fused kernel runs one workgroup of 512 keys per compute unit: long single prompts only.
-bool fused_applies(const Plan &p, int64_t L)
+bool fused_applies(const Plan &p, int64_t L, int64_t k_stride_token)
 {
     if (!fused_shape_ok(p)) return false;
+    if (k_stride_token > (int64_t(1) << 20)) return false;       // lane offsets within a tile are 32-bit
     const int n_wg = fused_workgroups(L);
     return n_wg >= sp_fused::kMinWorkgroups && n_wg <= 256 && n_wg <= device_compute_units();
 }
@@ -550,7 +551,7 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
     a.inv_c = 1.0f / a.c;
     a.out_scale = (desc->layer_agg == SP_LAYER_MAX) ? 1.0f / (float)desc->n_q
                                                    : 1.0f / ((float)desc->n_q * (float)desc->n_layers);
-    if (!batch && fused_applies(p, total)) {
+    if (!batch && fused_applies(p, total, desc->k_stride_token)) {
         const int n_wg = fused_workgroups(total);
         {
             sp_fused::FusedArgs f;
@@ -602,7 +603,7 @@ extern "C" int32_t sp_score_is_fused(const sp_score_desc *desc, int64_t L)
 {
     Plan p;
     if (make_plan(desc, p) != SP_OK) return -1;
-    return fused_applies(p, L) ? 1 : 0;
+    return fused_applies(p, L, desc->k_stride_token) ? 1 : 0;
 }
 
 extern "C" sp_status sp_score(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
