@@ -58,6 +58,7 @@ def _load():
     lib.sp_oracle_topk.argtypes = [P, c.c_int64, c.c_int64, P]
     lib.sp_oracle_merge.argtypes = [P, c.c_int64, c.c_int, c.c_int64, P]
     lib.sp_oracle_merge.restype = c.c_int64
+    lib.sp_oracle_assemble.argtypes = [P, c.c_int64, P, c.c_int64, P, c.c_int64, P, P, P, P]
     lib.sp_oracle_project.argtypes = [P, c.c_int64, P, c.c_int64, P, c.c_int64, P, P, P, P]
     _lib = lib
     return lib
@@ -194,6 +195,24 @@ def project(draft_off: np.ndarray, target_off: np.ndarray, spans: np.ndarray):
     _check(_load().sp_oracle_project(_ptr(draft_off), L, _ptr(target_off), M, _ptr(spans), spans.shape[0],
                                      _ptr(mask), _ptr(tspans), _ptr(n_t), _ptr(n_k)), "project")
     return tspans[: int(n_t[0])].copy(), mask[:M], int(n_k[0])
+
+
+def assemble(target_ids: np.ndarray, tspans: np.ndarray, delim_ids: np.ndarray):
+    """Returns (out_ids int32[n], out_pos int32[n], out_src int64[n]) of the compressed target prompt."""
+    target_ids = np.ascontiguousarray(target_ids, dtype=np.int32)
+    tspans = np.ascontiguousarray(tspans, dtype=np.int64).reshape(-1, 2)
+    delim_ids = np.ascontiguousarray(delim_ids, dtype=np.int32)
+    cap = int(np.sum(tspans[:, 1] - tspans[:, 0])) + max(tspans.shape[0] - 1, 0) * delim_ids.size if tspans.size else 0
+    cap = max(cap, 1)
+    ids = np.empty(cap, dtype=np.int32)
+    pos = np.empty(cap, dtype=np.int32)
+    src = np.empty(cap, dtype=np.int64)
+    n = np.zeros(1, dtype=np.int64)
+    _check(_load().sp_oracle_assemble(_ptr(target_ids), target_ids.size, _ptr(tspans) if tspans.size else None,
+                                      tspans.shape[0], _ptr(delim_ids) if delim_ids.size else None, delim_ids.size,
+                                      _ptr(ids), _ptr(pos), _ptr(src), _ptr(n)), "assemble")
+    k = int(n[0])
+    return ids[:k].copy(), pos[:k].copy(), src[:k].copy()
 
 
 def select(I: np.ndarray, w: int, c: int, k: int):

@@ -331,3 +331,42 @@ int sp_oracle_project(const int64_t *draft_off, int64_t L,
     if (!mask) free(mk);
     return 0;
 }
+
+/*
+ * Compressed target prompt in token-id form (paper: Algorithm 1, "ConcatWithDelim", the target
+ * tokenisation of the compressed text and the new contiguous position ids; Section 3.2;
+ * Appendix A.3 for the delimiters used). With the target tokenisation of the original text given
+ * as ids, the kept ranges [b, e) of target tokens are copied in order and the delimiter's ids are
+ * put between consecutive ranges (not before the first, not after the last). out_src[i] is the
+ * original target index of output token i, -1 for delimiter tokens; out_pos[i] = i.
+ * Buffers must hold sum(e - b) + (n_tspans - 1) * n_delim entries. Returns 0, or 1 on bad arguments.
+ */
+int sp_oracle_assemble(const int32_t *target_ids, int64_t M, const int64_t *tspans, int64_t n_tspans,
+                       const int32_t *delim, int64_t n_delim,
+                       int32_t *out_ids, int32_t *out_pos, int64_t *out_src, int64_t *out_len)
+{
+    if (!target_ids || M <= 0 || n_tspans < 0 || n_delim < 0 || !out_len ||
+        (n_tspans > 0 && !tspans) || (n_delim > 0 && !delim))
+        return 1;
+    int64_t n = 0;
+    for (int64_t r = 0; r < n_tspans; ++r) {
+        const int64_t b = tspans[2 * r], e = tspans[2 * r + 1];
+        if (b < 0 || e > M || b > e) return 1;
+        if (r > 0) {
+            for (int64_t j = 0; j < n_delim; ++j) {
+                if (out_ids) out_ids[n] = delim[j];
+                if (out_src) out_src[n] = -1;
+                if (out_pos) out_pos[n] = (int32_t)n;
+                ++n;
+            }
+        }
+        for (int64_t t = b; t < e; ++t) {
+            if (out_ids) out_ids[n] = target_ids[t];
+            if (out_src) out_src[n] = t;
+            if (out_pos) out_pos[n] = (int32_t)n;
+            ++n;
+        }
+    }
+    *out_len = n;
+    return 0;
+}

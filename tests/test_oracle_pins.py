@@ -532,6 +532,52 @@ def test_projection_boundary_token_is_kept_once():
 
 
 # --------------------------------------------------------------------------
+# compressed-prompt assembly (Algorithm 1: ConcatWithDelim, new position ids; Section 3.2)
+# --------------------------------------------------------------------------
+
+def test_assemble_worked_example_and_special_cases():
+    ids = np.arange(100, 120, dtype=np.int32)
+    out, pos, src = oracle.assemble(ids, np.array([[2, 5], [9, 11], [19, 20]]), np.array([7, 8]))
+    assert out.tolist() == [102, 103, 104, 7, 8, 109, 110, 7, 8, 119]          # written out by hand
+    assert pos.tolist() == list(range(10))                                      # contiguous position ids
+    assert src.tolist() == [2, 3, 4, -1, -1, 9, 10, -1, -1, 19]
+    # keep-all: the prompt itself, no delimiter anywhere
+    out, pos, src = oracle.assemble(ids, np.array([[0, 20]]), np.array([7, 8]))
+    assert out.tolist() == ids.tolist() and src.tolist() == list(range(20))
+    # nothing kept; empty delimiter = plain concatenation
+    assert oracle.assemble(ids, np.zeros((0, 2)), np.array([7]))[0].size == 0
+    out, _, _ = oracle.assemble(ids, np.array([[0, 2], [4, 6]]), np.zeros(0))
+    assert out.tolist() == [100, 101, 104, 105]
+
+
+def test_assemble_against_list_concatenation_and_projection_mask():
+    """Brute force on small random inputs; without its delimiters the output is exactly the target
+    tokens the projection keeps (its mask), and the length is n_kept + (ranges - 1) * |delim|."""
+    rng = np.random.default_rng(11)
+    w = synth.get_config("tiny")
+    for trial in range(20):
+        L = int(rng.integers(40, 200))
+        doff, toff = synth.gen_char_offsets(w, L, prompt=trial)
+        M = toff.size - 1
+        kept = np.sort(rng.choice(L // 8, size=int(rng.integers(1, L // 8)), replace=False))
+        spans = oracle.merge(kept, 8, L)
+        ts, mask, n_kept = oracle.project(doff, toff, spans)
+        ids = rng.integers(0, 50000, size=M).astype(np.int32)
+        delim = rng.integers(50000, 50010, size=int(rng.integers(0, 4))).astype(np.int32)
+        out, pos, src = oracle.assemble(ids, ts, delim)
+        want = []
+        for r, (b, e) in enumerate(ts.tolist()):
+            if r > 0:
+                want += delim.tolist()
+            want += ids[b:e].tolist()
+        assert out.tolist() == want
+        assert out.size == n_kept + max(len(ts) - 1, 0) * delim.size
+        assert out[src >= 0].tolist() == ids[mask.astype(bool)].tolist()
+        assert (ids[src[src >= 0]] == out[src >= 0]).all() and (np.diff(src[src >= 0]) > 0).all()
+        assert pos.tolist() == list(range(out.size))
+
+
+# --------------------------------------------------------------------------
 # generator sanity (no arithmetic of the method involved)
 # --------------------------------------------------------------------------
 
