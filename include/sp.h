@@ -6,8 +6,9 @@
  * the paper "Cross-Family Speculative Prefill": attention of the lookahead
  * queries over the prompt's keys in every draft layer, max/mean aggregation to
  * one score per prompt token, average pooling, chunk means, top-k chunk
- * selection, merging into spans, and projection of those spans through
- * character offsets onto another tokenisation (Algorithm 1; Appendix A.1).
+ * selection, merging into spans, projection of those spans through character
+ * offsets onto another tokenisation, and assembly of the compressed prompt's
+ * token and position ids (Algorithm 1; Appendix A.1).
  *
  * Conventions shared by every call
  *  - Pointers named *_dev point to device memory of the current HIP device and
@@ -171,6 +172,37 @@ sp_status sp_project(const int64_t *draft_off_dev, int64_t L,
                      int32_t max_spans, int64_t *tspans_dev,
                      int32_t *n_tspans_dev, uint8_t *keep_mask_dev,
                      int64_t *n_kept_dev, void *hip_stream);
+
+/* Bytes of workspace sp_assemble needs for up to max_spans kept ranges. */
+sp_status sp_assemble_workspace(int32_t max_spans, size_t *bytes);
+
+/*
+ * Compressed target prompt in token-id form (Algorithm 1: ConcatWithDelim, the
+ * target tokenisation of the compressed text and the new contiguous position
+ * ids; Section 3.2; Appendix A.3 names the delimiters). target_ids_dev[M] is
+ * the target tokenisation of the original text; tspans_dev holds
+ * *n_tspans_dev (at most max_spans) ascending, disjoint ranges [begin, end) of
+ * kept target tokens, as written by sp_project; delim_ids_dev[n_delim] is the
+ * delimiter's own tokenisation (n_delim may be 0, then the pointer may be NULL).
+ * The output is the kept ranges in order with the delimiter's ids between
+ * consecutive ranges (none before the first or after the last):
+ *  - *out_len_dev = kept tokens + (ranges - 1) * n_delim  (0 for no range),
+ *    the full length even when it exceeds out_capacity;
+ *  - the first min(out_len, out_capacity) entries are written of
+ *    out_ids_dev (token ids), out_pos_dev (position ids 0, 1, 2, ...: the
+ *    compressed prompt is renumbered, original positions are not restored) and
+ *    the optional out_src_dev (original target index of each output token, -1
+ *    for delimiter tokens; may be NULL).
+ * Requires M >= 1, 1 <= max_spans <= 2^24, 0 <= n_delim <= 1024,
+ * 1 <= out_capacity < 2^31. Range bounds are not checked beyond clamping to [0, M].
+ */
+sp_status sp_assemble(const int32_t *target_ids_dev, int64_t M,
+                      const int64_t *tspans_dev, const int32_t *n_tspans_dev,
+                      int32_t max_spans, const int32_t *delim_ids_dev,
+                      int32_t n_delim, int64_t out_capacity,
+                      int32_t *out_ids_dev, int32_t *out_pos_dev,
+                      int64_t *out_src_dev, int64_t *out_len_dev,
+                      void *ws_dev, size_t ws_bytes, void *hip_stream);
 
 /* Description of the last error raised on the calling thread ("" if none).
  * The string lives in thread-local storage owned by the library. */

@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     ScoreDesc,
     library_path,
     load_library,
+    sp_assemble,
+    sp_assemble_workspace,
     sp_keep_count,
     sp_last_error,
     sp_project,

@@ -21,7 +21,7 @@ _LIB_PATH = os.path.join(_PKG_DIR, "libsp_amd.so")
 
 EXPORTS = (
     "sp_score_workspace", "sp_score", "sp_score_is_fused", "sp_score_batch", "sp_keep_count", "sp_select_workspace",
-    "sp_select", "sp_project", "sp_last_error", "sp_version",
+    "sp_select", "sp_project", "sp_assemble_workspace", "sp_assemble", "sp_last_error", "sp_version",
 )
 
 
@@ -77,10 +77,12 @@ def load_library():
     lib.sp_select_workspace.argtypes = [c.c_int64, c.c_int32, c.POINTER(c.c_size_t)]
     lib.sp_select.argtypes = [P, c.c_int64, c.c_int32, c.c_int32, c.c_int64, P, P, P, P, P, c.c_size_t, P]
     lib.sp_project.argtypes = [P, c.c_int64, P, c.c_int64, P, P, c.c_int32, P, P, P, P, P]
+    lib.sp_assemble_workspace.argtypes = [c.c_int32, c.POINTER(c.c_size_t)]
+    lib.sp_assemble.argtypes = [P, c.c_int64, P, P, c.c_int32, P, c.c_int32, c.c_int64, P, P, P, P, P, c.c_size_t, P]
     lib.sp_last_error.restype = c.c_char_p
     lib.sp_version.restype = c.c_char_p
     for name in ("sp_score_workspace", "sp_score", "sp_score_is_fused", "sp_score_batch", "sp_select_workspace", "sp_select",
-                 "sp_project"):
+                 "sp_project", "sp_assemble_workspace", "sp_assemble"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -172,3 +174,17 @@ def sp_project(draft_off, L: int, target_off, M: int, spans, n_spans, max_spans:
                n_kept, stream=None) -> None:
     _check(load_library().sp_project(_ptr(draft_off), L, _ptr(target_off), M, _ptr(spans), _ptr(n_spans), max_spans,
                                      _ptr(tspans), _ptr(n_tspans), _ptr(keep_mask), _ptr(n_kept), _stream(stream)))
+
+
+def sp_assemble_workspace(max_spans: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().sp_assemble_workspace(max_spans, ctypes.byref(n)))
+    return int(n.value)
+
+
+def sp_assemble(target_ids, M: int, tspans, n_tspans, max_spans: int, delim_ids, n_delim: int, out_capacity: int,
+                out_ids, out_pos, out_src, out_len, ws, ws_bytes: Optional[int] = None, stream=None) -> None:
+    nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
+    _check(load_library().sp_assemble(_ptr(target_ids), M, _ptr(tspans), _ptr(n_tspans), max_spans, _ptr(delim_ids),
+                                      n_delim, out_capacity, _ptr(out_ids), _ptr(out_pos), _ptr(out_src),
+                                      _ptr(out_len), _ptr(ws), nbytes, _stream(stream)))

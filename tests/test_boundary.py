@@ -159,3 +159,23 @@ def test_project_argument_errors():
         with pytest.raises(sp.SpError) as e:
             call(**kw)
         assert e.value.status == 1, kw
+
+
+def test_assemble_argument_errors():
+    fake = 0x1000
+    n = sp.sp_assemble_workspace(100)
+    assert n >= 101 * 8 and n % 256 == 0
+    with pytest.raises(sp.SpError):
+        sp.sp_assemble_workspace(0)
+
+    def call(ids=fake, M=12, tsp=fake, nt=fake, cap=100, delim=fake, nd=2, ocap=50, oi=fake, op=fake, ol=fake, ws=fake,
+             wsb=n):
+        sp.sp_assemble(ids, M, tsp, nt, cap, delim, nd, ocap, oi, op, None, ol, ws, wsb, stream=0)
+
+    for kw, status in [(dict(ids=None), 1), (dict(tsp=None), 1), (dict(nt=None), 1), (dict(oi=None), 1),
+                       (dict(op=None), 1), (dict(ol=None), 1), (dict(M=0), 1), (dict(cap=0), 1), (dict(nd=-1), 1),
+                       (dict(nd=2000), 1), (dict(delim=None), 1), (dict(ocap=0), 1), (dict(ocap=1 << 31), 1),
+                       (dict(ws=None, wsb=0), 3), (dict(wsb=8), 3), (dict(ws=fake + 8), 3)]:
+        with pytest.raises(sp.SpError) as e:
+            call(**kw)
+        assert e.value.status == status, kw

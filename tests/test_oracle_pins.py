@@ -532,6 +532,28 @@ def test_projection_boundary_token_is_kept_once():
 
 
 # --------------------------------------------------------------------------
+# keep rate from a target-side budget (Section 3.1: rho = L_hat_target / L_target, per sample)
+# --------------------------------------------------------------------------
+
+def test_keep_rate_from_target_budget_lands_near_the_budget():
+    """With rho = L_hat / M applied to the draft chunks, the projected target-side length comes out
+    close to L_hat (slightly above: chunk rounding up, and tokens straddling a span boundary)."""
+    w = synth.get_config("llama1b-8k")
+    doff, toff = synth.gen_char_offsets(w, w.L)
+    M = toff.size - 1
+    rng = np.random.default_rng(5)
+    I = rng.random(w.L)
+    C = (w.L + w.chunk - 1) // w.chunk
+    for budget in (1024, 2048, 4096):
+        k = oracle.keep_count(C, budget, M)
+        assert k == -(-C * budget // M)                              # ceil(rho * C) in integers
+        _, spans, _ = oracle.select(I, w.pool, w.chunk, k)
+        _, _, n_kept = oracle.project(doff, toff, spans)
+        assert budget <= n_kept <= budget * 1.08 + 2 * len(spans), (budget, n_kept)
+    assert oracle.keep_count(C, 2 * M, M) == C and oracle.keep_count(C, 0, M) == 1   # clamped to [1, C]
+
+
+# --------------------------------------------------------------------------
 # compressed-prompt assembly (Algorithm 1: ConcatWithDelim, new position ids; Section 3.2)
 # --------------------------------------------------------------------------
 
