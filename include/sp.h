@@ -91,6 +91,11 @@ sp_status sp_score_workspace(const sp_score_desc *desc, int64_t total_tokens,
  * device pointers. scores_dev: float[L]. L == 0 is a no-op returning SP_OK.
  * The softmax is exact (row maximum and sum over all L keys, fp32); the result
  * is deterministic: the same inputs give bit-identical scores.
+ * The single-launch kernel (see sp_score_is_fused) needs all its workgroups
+ * resident at once, which an otherwise idle device guarantees; if other work
+ * occupies the device, its waits on other workgroups are bounded (about a
+ * second), after which every score of the call is NaN: it never hangs, and a
+ * NaN score means "run again", never a wrong value.
  */
 sp_status sp_score(const sp_score_desc *desc, const void *q_dev,
                    const void *const *k_layers_host, int64_t L,
