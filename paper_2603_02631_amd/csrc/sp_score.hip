@@ -115,10 +115,9 @@ __device__ __forceinline__ void stage_k(u32x4 *ks, const uint16_t *kb, int64_t s
         const int idx = tid + i * kThreads;
         const int row = idx / CH, ch = idx % CH;
         const int64_t j = j0 + row;
-        if (j < end)
-            v[i] = *reinterpret_cast<const u32x4 *>(kb + j * stride_token + ch * 8);
-        else
-            v[i] = u32x4{0u, 0u, 0u, 0u};
+        // rows past the end repeat the last key (every consumer masks them): unconditional loads keep
+        // the register count a third of what per-load branches cost
+        v[i] = *reinterpret_cast<const u32x4 *>(kb + (j < end ? j : end - 1) * stride_token + ch * 8);
     }
 #pragma unroll
     for (int i = 0; i < N; ++i) {
@@ -132,7 +131,7 @@ __device__ __forceinline__ void stage_k(u32x4 *ks, const uint16_t *kb, int64_t s
 // over one key tile.
 // ---------------------------------------------------------------------------
 template <int D, int NS>
-__global__ __launch_bounds__(kThreads, 2) void sp_stats_kernel(ScoreArgs a, LayerPtrs kp)
+__global__ __launch_bounds__(kThreads, 4) void sp_stats_kernel(ScoreArgs a, LayerPtrs kp)
 {
     constexpr int KS = D / 16;
     constexpr int TILE = kWaves * NS * 32;
@@ -255,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void sp_merge_kernel(ScoreArgs a)
 // the attention probability.
 // ---------------------------------------------------------------------------
 template <int D, int NS, int NB>
-__global__ __launch_bounds__(kThreads) void sp_prob_kernel(ScoreArgs a, LayerPtrs kp)
+__global__ __launch_bounds__(kThreads, 4) void sp_prob_kernel(ScoreArgs a, LayerPtrs kp)
 {
     constexpr int KS = D / 16;
     constexpr int TILE = kWaves * NS * 32;
