@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void sp_merge_kernel(ScoreArgs a)
 // the attention probability.
 // ---------------------------------------------------------------------------
 template <int D, int NS, int NB>
-__global__ __launch_bounds__(kThreads, 4) void sp_prob_kernel(ScoreArgs a, LayerPtrs kp)
+__global__ __launch_bounds__(kThreads, 3) void sp_prob_kernel(ScoreArgs a, LayerPtrs kp)
 {
     constexpr int KS = D / 16;
     constexpr int TILE = kWaves * NS * 32;
