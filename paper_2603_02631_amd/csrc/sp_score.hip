@@ -8,12 +8,16 @@
 //           (max, sum of exp) kept per lane, one partial per (row, tile);
 //   merge   log-sum-exp combination of the partials of each row in a fixed
 //           order (deterministic), giving the row's normaliser;
-//   prob    one workgroup per key tile, looping over layers and kv heads:
+//   prob    one workgroup per (key tile, layer range), looping over its layers
+//           and the kv heads:
 //           logits again with the normaliser folded into the MFMA's C operand,
 //           maximum over heads taken on logits (exp is monotone, so
 //           max_h softmax_h = exp(max_h(logit_h - lse_h))), one exp per
 //           (lookahead row, key), sum over lookahead rows and layers in
-//           registers, a single store per key.
+//           registers, a single store per key. Long inputs give every
+//           workgroup all layers; short ones split the layers over several
+//           workgroups per tile, which leave per-range results that a fourth
+//           kernel (reduce) combines in a fixed order.
 //
 // Register/lane layout facts used throughout (v_mfma_f32_32x32x16_bf16):
 //   A operand: lane i holds row i%32, eight consecutive k-values of half i/32
@@ -36,6 +40,7 @@ constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kMaxPrompts = 4096;
 constexpr size_t kLdsBudget = 64 * 1024;
+constexpr int kProbTargetWgs = 1024;   // the prob pass splits layers until it has about this many workgroups
 
 struct TileInfo {
     int64_t j0;          // first key of the tile (index into the packed token axis)
@@ -53,6 +58,9 @@ struct ScoreArgs {
     float2 *part;             // [n_phases][n_tiles][rows_pad]
     float *lse_neg;           // [B][n_phases][rows_pad]  (-lse in raw-logit units, permuted)
     float *scores;
+    float *split_buf;         // layer-split results: MEAN [n_splits][n_tiles][TILE],
+                              //                      MAX  [n_splits][8*n_nblk][n_tiles][TILE]
+    int32_t n_splits, layers_per_split;
     int32_t n_tiles, n_prompts;
     int32_t n_layers, n_q_heads, n_kv_heads, group, n_q;
     int32_t n_nblk, n_gblk, rows_pad;   // blocks of 8 lookahead rows / 4 group heads
@@ -263,10 +271,13 @@ __global__ __launch_bounds__(kThreads, 3) void sp_prob_kernel(ScoreArgs a, Layer
     u32x4 *qs = lds + TILE * (D / 8);
     float *ci = reinterpret_cast<float *>(qs + a.rows_pad * (D / 8));   // rows_pad floats
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hf = lane >> 5, col = lane & 31;
-    const int tile = blockIdx.x;
+    const int tile = blockIdx.x, split = blockIdx.y;
     const TileInfo ti = get_tile(a, tile, TILE);
     const int n_phases = a.n_layers * a.n_kv_heads;
     const float c = a.c;
+    const int layer_lo = split * a.layers_per_split;
+    const int layer_hi = min(layer_lo + a.layers_per_split, a.n_layers);
+    const bool whole = a.n_splits == 1;
 
     float mx[NS][NB][4];
     float total[NS];
@@ -279,7 +290,7 @@ __global__ __launch_bounds__(kThreads, 3) void sp_prob_kernel(ScoreArgs a, Layer
             for (int e = 0; e < 4; ++e) mx[s][b][e] = neg_inf();
     }
 
-    for (int layer = 0; layer < a.n_layers; ++layer) {
+    for (int layer = layer_lo; layer < layer_hi; ++layer) {
         for (int kv = 0; kv < a.n_kv_heads; ++kv) {
             const int phase = layer * a.n_kv_heads + kv;
             __syncthreads();
@@ -323,7 +334,7 @@ __global__ __launch_bounds__(kThreads, 3) void sp_prob_kernel(ScoreArgs a, Layer
                 }
             }
         }
-        if (a.layer_agg == SP_LAYER_MEAN || layer == a.n_layers - 1) {
+        if (a.layer_agg == SP_LAYER_MEAN || (whole && layer == a.n_layers - 1)) {
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 float sum = 0.f;
@@ -338,12 +349,58 @@ __global__ __launch_bounds__(kThreads, 3) void sp_prob_kernel(ScoreArgs a, Layer
             }
         }
     }
+    if (!whole && a.layer_agg == SP_LAYER_MAX) {
+        // probabilities of this layer range's head-and-layer maxima, one per (lookahead row, key);
+        // exp is monotone, so the maximum over ranges can be taken after it
+        const int n_rows = 8 * NB;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int n = 8 * b + 4 * hf + e;
+                    a.split_buf[(((int64_t)split * n_rows + n) * a.n_tiles + tile) * TILE + (wave * NS + s) * 32 + col] =
+                        fast_exp2(mx[s][b][e] * c);
+                }
+        return;
+    }
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         const float both = total[s] + __shfl_xor(total[s], 32);
-        const int64_t j = ti.j0 + (wave * NS + s) * 32 + col;
-        if (hf == 0 && j < ti.end) a.scores[j] = both * a.out_scale;
+        const int local = (wave * NS + s) * 32 + col;
+        const int64_t j = ti.j0 + local;
+        if (hf != 0) continue;
+        if (!whole) a.split_buf[((int64_t)split * a.n_tiles + tile) * TILE + local] = both;
+        else if (j < ti.end) a.scores[j] = both * a.out_scale;
     }
+}
+
+// ---------------------------------------------------------------------------
+// reduce: combines the layer ranges of a split prob pass, one thread per key,
+// ranges in ascending order. MEAN adds the ranges' sums; MAX takes, per
+// lookahead row, the largest probability over the ranges and adds the rows.
+// ---------------------------------------------------------------------------
+template <int TILE>
+__global__ __launch_bounds__(TILE) void sp_prob_reduce_kernel(ScoreArgs a)
+{
+    const int tile = blockIdx.x, local = threadIdx.x;
+    const TileInfo ti = get_tile(a, tile, TILE);
+    const int64_t j = ti.j0 + local;
+    if (j >= ti.end) return;
+    float sum = 0.f;
+    if (a.layer_agg == SP_LAYER_MEAN) {
+        for (int s = 0; s < a.n_splits; ++s) sum += a.split_buf[((int64_t)s * a.n_tiles + tile) * TILE + local];
+    } else {
+        const int n_rows = 8 * a.n_nblk;
+        for (int n = 0; n < n_rows; ++n) {
+            float m = 0.f;
+            for (int s = 0; s < a.n_splits; ++s)
+                m = fmaxf(m, a.split_buf[(((int64_t)s * n_rows + n) * a.n_tiles + tile) * TILE + local]);
+            sum += m;
+        }
+    }
+    a.scores[j] = sum * a.out_scale;
 }
 
 // Tile table of a ragged batch: tiles never straddle prompts.
@@ -369,9 +426,34 @@ __global__ void sp_tiles_kernel(const int64_t *offsets, int n_prompts, int tile_
 // host side
 // ---------------------------------------------------------------------------
 struct Plan {
-    int D, NS, NB, n_gblk, rows_pad, tile_keys, n_phases;
+    int D, NS, NB, n_gblk, rows_pad, tile_keys, n_phases, n_layers, layer_agg;
     size_t lds_bytes;
 };
+
+// Layers per workgroup of the prob pass: all of them once the tiles alone fill the device.
+int prob_layers_per_split(const Plan &p, int64_t n_tiles)
+{
+    int64_t want = (kProbTargetWgs + n_tiles - 1) / n_tiles;
+    if (want < 1) want = 1;
+    if (want > p.n_layers) want = p.n_layers;
+    return (int)((p.n_layers + want - 1) / want);
+}
+
+int prob_splits(const Plan &p, int64_t n_tiles)
+{
+    const int lps = prob_layers_per_split(p, n_tiles);
+    return (p.n_layers + lps - 1) / lps;
+}
+
+// Floats of the layer-split buffer, bounded over every tile count up to n_tiles (the workspace query
+// rounds the tile count up): splits * tiles never exceeds either term of the minimum.
+size_t split_buf_floats(const Plan &p, int64_t n_tiles)
+{
+    int64_t blocks = (int64_t)p.n_layers * n_tiles;
+    if (blocks > kProbTargetWgs + n_tiles) blocks = kProbTargetWgs + n_tiles;
+    const int per_key = (p.layer_agg == SP_LAYER_MAX) ? 8 * p.NB : 1;
+    return (size_t)blocks * p.tile_keys * per_key;
+}
 
 sp_status make_plan(const sp_score_desc *d, Plan &p)
 {
@@ -402,6 +484,8 @@ sp_status make_plan(const sp_score_desc *d, Plan &p)
     p.rows_pad = p.NB * p.n_gblk * 32;
     p.tile_keys = kWaves * p.NS * 32;
     p.n_phases = d->n_layers * d->n_kv_heads;
+    p.n_layers = d->n_layers;
+    p.layer_agg = d->layer_agg;
     p.lds_bytes = (size_t)p.tile_keys * p.D * 2 + (size_t)p.rows_pad * p.D * 2 + (size_t)p.rows_pad * 4;
     if (p.lds_bytes > kLdsBudget)
         return sp::fail(SP_ERR_UNSUPPORTED, "desc: query group of %d heads x %d rows at head_dim %d exceeds on-chip staging",
@@ -410,7 +494,7 @@ sp_status make_plan(const sp_score_desc *d, Plan &p)
 }
 
 struct WsLayout {
-    size_t part, lse, tiles, prompt_tiles, fused, total;
+    size_t part, lse, tiles, prompt_tiles, split, fused, total;
 };
 
 // Shapes the fused single-launch kernel can hold on chip (any L; the length test is separate).
@@ -453,6 +537,7 @@ WsLayout ws_layout(const Plan &p, int64_t n_tiles, int n_prompts)
     w.lse = off;   off = sp::align_up(off + sizeof(float) * (size_t)n_prompts * p.n_phases * p.rows_pad, 256);
     w.tiles = off; off = sp::align_up(off + sizeof(TileInfo) * (size_t)n_tiles, 256);
     w.prompt_tiles = off; off = sp::align_up(off + sizeof(int32_t) * (size_t)(n_prompts + 1), 256);
+    w.split = off; off = sp::align_up(off + sizeof(float) * split_buf_floats(p, n_tiles), 256);
     w.fused = off;
     if (fused_shape_ok(p) && n_prompts == 1) {
         int64_t n_wg = n_tiles * p.tile_keys / sp_fused::kTileKeys + 1;
@@ -471,11 +556,17 @@ sp_status launch_all(const Plan &p, const ScoreArgs &a, const LayerPtrs &kp, hip
     SP_HIP_CHECK(hipGetLastError());
     hipLaunchKernelGGL(sp_merge_kernel, dim3(p.rows_pad / 32, p.n_phases, a.n_prompts), block, 0, st, a);
     SP_HIP_CHECK(hipGetLastError());
+    const dim3 grid(a.n_tiles, a.n_splits);
     if (p.NB == 1)
-        hipLaunchKernelGGL((sp_prob_kernel<D, NS, 1>), dim3(a.n_tiles), block, p.lds_bytes, st, a, kp);
+        hipLaunchKernelGGL((sp_prob_kernel<D, NS, 1>), grid, block, p.lds_bytes, st, a, kp);
     else
-        hipLaunchKernelGGL((sp_prob_kernel<D, NS, 2>), dim3(a.n_tiles), block, p.lds_bytes, st, a, kp);
+        hipLaunchKernelGGL((sp_prob_kernel<D, NS, 2>), grid, block, p.lds_bytes, st, a, kp);
     SP_HIP_CHECK(hipGetLastError());
+    if (a.n_splits > 1) {
+        constexpr int TILE = kWaves * NS * 32;
+        hipLaunchKernelGGL((sp_prob_reduce_kernel<TILE>), dim3(a.n_tiles), dim3(TILE), 0, st, a);
+        SP_HIP_CHECK(hipGetLastError());
+    }
     return SP_OK;
 }
 
@@ -535,6 +626,9 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
     a.part = reinterpret_cast<float2 *>(ws + w.part);
     a.lse_neg = reinterpret_cast<float *>(ws + w.lse);
     a.scores = scores_dev;
+    a.split_buf = reinterpret_cast<float *>(ws + w.split);
+    a.layers_per_split = prob_layers_per_split(p, n_tiles);
+    a.n_splits = prob_splits(p, n_tiles);
     a.n_tiles = (int32_t)n_tiles;
     a.n_prompts = B;
     a.n_layers = desc->n_layers;

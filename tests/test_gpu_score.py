@@ -39,6 +39,9 @@ SHAPES = [
     ("exact_tile", 2, 4, 2, 64, 8, 256),
     ("tile_plus_one", 2, 4, 2, 64, 8, 257),
     ("sub_tile_d128", 2, 4, 2, 128, 8, 31),
+    # general path with the layers of the prob pass in ranges of 2 + 1, and with enough tiles for no split
+    ("uneven_split_d128", 3, 2, 1, 128, 4, 70001),
+    ("unsplit_d128", 2, 2, 1, 128, 4, 131072 + 77),
 ]
 
 
