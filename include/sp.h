@@ -102,6 +102,25 @@ sp_status sp_score(const sp_score_desc *desc, const void *q_dev,
                    float *scores_dev, void *ws_dev, size_t ws_bytes,
                    void *hip_stream);
 
+/*
+ * sp_score with the lookahead tokens' own keys in the softmax (Algorithm 1, the
+ * ForwardWithAttn loop: the forward pass of lookahead step i also attends to
+ * the tokens generated in steps 1 .. i-1). Row n (0-based) of every head is
+ * normalised over the L prompt keys and the lookahead keys 0 .. n-1, plus key n
+ * itself when look_self is 1 (0 or 1; anything else is SP_ERR_INVALID_ARG):
+ *   p[l,h,n,j] = exp(s[l,h,n,j]) / ( sum_{j'<L} exp(s[l,h,n,j'])
+ *                                    + sum_{m visible} exp(scale*<Q[l,h,n,:], Klook[l,h/G,m,:]>) )
+ * Only prompt tokens are scored; aggregation as in sp_score.
+ * k_look_dev: device, bf16, dense [n_layers][n_kv_heads][n_q][head_dim],
+ * 16-byte aligned, not null, only read. Everything else as in sp_score (same
+ * workspace size, same kernels, same determinism and failure behaviour).
+ */
+sp_status sp_score_look(const sp_score_desc *desc, const void *q_dev,
+                        const void *const *k_layers_host, int64_t L,
+                        const void *k_look_dev, int32_t look_self,
+                        float *scores_dev, void *ws_dev, size_t ws_bytes,
+                        void *hip_stream);
+
 /* Which implementation sp_score picks for this shape and length on the current
  * device: 1 = the single-launch kernel that keeps K on chip and reads it from
  * HBM once (long prompts of head_dim 64 whose query group fits 64 padded rows),

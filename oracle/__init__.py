@@ -51,6 +51,8 @@ def _load():
     lib.sp_oracle_softmax_rows.argtypes = [P, c.c_int64, c.c_int64, P, P]
     lib.sp_oracle_score.argtypes = [P, P, c.c_int64, c.c_int64, c.c_int, c.c_int, c.c_int, c.c_int,
                                     c.c_int, c.c_int64, c.c_double, c.c_int, P]
+    lib.sp_oracle_score_look.argtypes = [P, P, c.c_int64, c.c_int64, c.c_int, c.c_int, c.c_int, c.c_int,
+                                         c.c_int, c.c_int64, c.c_double, c.c_int, P, c.c_int, P]
     lib.sp_oracle_pool.argtypes = [P, c.c_int64, c.c_int, P]
     lib.sp_oracle_chunk_mean.argtypes = [P, c.c_int64, c.c_int, P]
     lib.sp_oracle_keep_count.argtypes = [c.c_int64, c.c_int64, c.c_int64]
@@ -137,6 +139,30 @@ def score(q: np.ndarray, k_layers: Sequence[np.ndarray], scale: float, layer_agg
     out = np.empty(L, dtype=np.float64)
     _check(_load().sp_oracle_score(_ptr(q), ctypes.cast(ptrs, ctypes.c_void_p), st, sh, Lyr, H, hkv, n_q,
                                    d, L, float(scale), int(layer_agg), _ptr(out)), "score")
+    return out
+
+
+def score_look(q: np.ndarray, k_layers: Sequence[np.ndarray], k_look: np.ndarray, look_self: int, scale: float,
+               layer_agg: int = LAYER_MEAN, layout: str = "HND") -> np.ndarray:
+    """Token importance with the lookahead keys in every row's normaliser. k_look: uint16 [Lyr][Hkv][n_q][d];
+    row n sees lookahead keys 0..n-1, and key n too when look_self is 1."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    Lyr, H, n_q, d = q.shape
+    if len(k_layers) != Lyr:
+        raise ValueError("need one K array per layer")
+    ks = [np.ascontiguousarray(k, dtype=np.uint16) for k in k_layers]
+    st, sh, hkv, L, dk = _k_strides(ks[0], layout)
+    for k in ks:
+        if k.shape != ks[0].shape:
+            raise ValueError("K layers must share a shape")
+    k_look = np.ascontiguousarray(k_look, dtype=np.uint16)
+    if dk != d or k_look.shape != (Lyr, hkv, n_q, d):
+        raise ValueError("head_dim or k_look shape mismatch")
+    ptrs = (ctypes.c_void_p * Lyr)(*[k.ctypes.data for k in ks])
+    out = np.empty(L, dtype=np.float64)
+    _check(_load().sp_oracle_score_look(_ptr(q), ctypes.cast(ptrs, ctypes.c_void_p), st, sh, Lyr, H, hkv, n_q,
+                                        d, L, float(scale), int(layer_agg), _ptr(k_look), int(look_self),
+                                        _ptr(out)), "score_look")
     return out
 
 

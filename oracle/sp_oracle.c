@@ -124,31 +124,79 @@ int sp_oracle_softmax_rows(double *s, int64_t rows, int64_t L, double *row_max, 
 }
 
 /*
+ * Row softmax with the lookahead tokens' own keys in the normaliser
+ * (Algorithm 1, the ForwardWithAttn loop: the pass of lookahead step i runs
+ * after i-1 generated tokens, whose keys a causal decoder also attends to; the
+ * paper does not say whether they count, so this is the second reading next to
+ * sp_oracle_softmax_rows). Rows are ordered [head][n]; row (h, n) is the
+ * concatenation of its L prompt logits s and its visible lookahead logits
+ * sl[h][n][m], m < n + look_self (capped at n_q): softmax over that whole row,
+ * of which only the prompt part is kept in s.
+ */
+int sp_oracle_softmax_rows_look(double *s, const double *sl, int64_t rows, int64_t L, int n_q, int look_self)
+{
+    if (!s || !sl || rows <= 0 || L <= 0 || n_q <= 0 || rows % n_q != 0 || (look_self != 0 && look_self != 1))
+        return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        double *x = s + r * L;
+        const double *y = sl + r * n_q;
+        int n_vis = (int)(r % n_q) + look_self;
+        if (n_vis > n_q) n_vis = n_q;
+        double m = x[0];
+        for (int64_t j = 1; j < L; ++j)
+            if (x[j] > m) m = x[j];
+        for (int t = 0; t < n_vis; ++t)
+            if (y[t] > m) m = y[t];
+        double l = 0.0;
+        for (int64_t j = 0; j < L; ++j) {
+            x[j] = exp(x[j] - m);
+            l += x[j];
+        }
+        for (int t = 0; t < n_vis; ++t) l += exp(y[t] - m);
+        for (int64_t j = 0; j < L; ++j) x[j] /= l;
+    }
+    return 0;
+}
+
+/*
  * Token importance I[j] (Algorithm 1 "AggregateMaxMean"; Appendix A.1.1).
  *   layer_agg == 1 (the paper's statement): max over layers and heads, then
  *       mean over the lookahead rows:  I[j] = (1/N) sum_n max_{l,h} p[l][h][n][j]
  *   layer_agg == 0 (variant): max over heads, mean over lookahead rows and
  *       layers:  I[j] = (1/(Lyr*N)) sum_l sum_n max_h p[l][h][n][j]
  * q is dense [Lyr][H][n_q][d]; k_layers[l] points at layer l's keys.
+ * k_look == NULL: rows are normalised over the prompt keys only
+ * (sp_oracle_softmax_rows). Otherwise k_look is dense [Lyr][Hkv][n_q][d], the
+ * keys of the lookahead tokens, and rows are normalised as
+ * sp_oracle_softmax_rows_look describes.
  */
-int sp_oracle_score(const uint16_t *q, const uint16_t *const *k_layers,
-                    int64_t k_stride_token, int64_t k_stride_head,
-                    int Lyr, int H, int Hkv, int n_q, int d, int64_t L,
-                    double scale, int layer_agg, double *I)
+int sp_oracle_score_look(const uint16_t *q, const uint16_t *const *k_layers,
+                         int64_t k_stride_token, int64_t k_stride_head,
+                         int Lyr, int H, int Hkv, int n_q, int d, int64_t L,
+                         double scale, int layer_agg,
+                         const uint16_t *k_look, int look_self, double *I)
 {
     if (!q || !k_layers || !I || Lyr <= 0 || (layer_agg != 0 && layer_agg != 1)) return 1;
     const int64_t rows = (int64_t)H * n_q;
     double *p = (double *)malloc(sizeof(double) * rows * L);
     double *acc = (double *)malloc(sizeof(double) * (int64_t)n_q * L); /* per (n, j) */
-    if (!p || !acc) { free(p); free(acc); return 2; }
+    double *sl = (double *)malloc(sizeof(double) * rows * n_q);        /* lookahead logits */
+    if (!p || !acc || !sl) { free(p); free(acc); free(sl); return 2; }
     for (int64_t i = 0; i < (int64_t)n_q * L; ++i) acc[i] = 0.0;
 
     for (int l = 0; l < Lyr; ++l) {
         int rc = sp_oracle_logits_layer(q + (int64_t)l * rows * d, k_layers[l],
                                         k_stride_token, k_stride_head,
                                         H, Hkv, n_q, d, L, scale, p);
-        if (!rc) rc = sp_oracle_softmax_rows(p, rows, L, NULL, NULL);
-        if (rc) { free(p); free(acc); return rc; }
+        if (!rc && !k_look) rc = sp_oracle_softmax_rows(p, rows, L, NULL, NULL);
+        if (!rc && k_look) {
+            /* the lookahead keys of this layer as a key array of n_q tokens, [Hkv][n_q][d] */
+            rc = sp_oracle_logits_layer(q + (int64_t)l * rows * d, k_look + (int64_t)l * Hkv * n_q * d,
+                                        d, (int64_t)n_q * d, H, Hkv, n_q, d, n_q, scale, sl);
+            if (!rc) rc = sp_oracle_softmax_rows_look(p, sl, rows, L, n_q, look_self);
+        }
+        if (rc) { free(p); free(acc); free(sl); return rc; }
 #pragma omp parallel for schedule(static)
         for (int n = 0; n < n_q; ++n) {
             for (int64_t j = 0; j < L; ++j) {
@@ -171,7 +219,17 @@ int sp_oracle_score(const uint16_t *q, const uint16_t *const *k_layers,
     }
     free(p);
     free(acc);
+    free(sl);
     return 0;
+}
+
+int sp_oracle_score(const uint16_t *q, const uint16_t *const *k_layers,
+                    int64_t k_stride_token, int64_t k_stride_head,
+                    int Lyr, int H, int Hkv, int n_q, int d, int64_t L,
+                    double scale, int layer_agg, double *I)
+{
+    return sp_oracle_score_look(q, k_layers, k_stride_token, k_stride_head, Lyr, H, Hkv, n_q, d, L, scale,
+                                layer_agg, NULL, 0, I);
 }
 
 /*

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     sp_project,
     sp_score,
     sp_score_batch,
+    sp_score_look,
     sp_score_is_fused,
     sp_score_workspace,
     sp_select,

@@ -58,6 +58,7 @@ struct ScoreArgs {
     float2 *part;             // [n_phases][n_tiles][rows_pad]
     float *lse_neg;           // [B][n_phases][rows_pad]  (-lse in raw-logit units, permuted)
     float *scores;
+    const float *look;        // [n_phases][rows_pad] lookahead-key term of each row's normaliser, or null
     float *split_buf;         // layer-split results: MEAN [n_splits][n_tiles][TILE],
                               //                      MAX  [n_splits][8*n_nblk][n_tiles][TILE]
     int32_t n_splits, layers_per_split;
@@ -251,10 +252,47 @@ __global__ __launch_bounds__(kThreads) void sp_merge_kernel(ScoreArgs a)
         for (int s = 1; s < 8; ++s) lse_merge(m, l, red[s][rho].x, red[s][rho].y, a.c);
         int g, n;
         const bool valid = row_to_gn(a, row, g, n) && l > 0.f;
-        const float v = valid ? -(m + fast_log2(l) * a.inv_c) : neg_inf();
+        float v = valid ? -(m + fast_log2(l) * a.inv_c) : neg_inf();
+        if (valid && a.look != nullptr) {
+            // the softmax also runs over the row's visible lookahead keys: log-sum-exp of both parts
+            const float lp = -v, lk = a.look[(int64_t)phase * a.rows_pad + row], top = fmaxf(lp, lk);
+            v = -(top + fast_log2(fast_exp2((lp - top) * a.c) + fast_exp2((lk - top) * a.c)) * a.inv_c);
+        }
         const int pos = ((rho >> 2) & 1) * 16 + 4 * (rho >> 3) + (rho & 3);
         a.lse_neg[((int64_t)prompt * n_phases + phase) * a.rows_pad + blk * 32 + pos] = v;
     }
+}
+
+// ---------------------------------------------------------------------------
+// look: log-sum-exp (raw-logit units) of every query row over the lookahead
+// keys it sees, one workgroup per (layer, kv head), one thread per padded row.
+// Lookahead row n sees the keys of rows 0 .. n-1, and its own with look_self
+// (a decode step attends to the tokens generated before it; Algorithm 1's
+// ForwardWithAttn with lookahead = i). Rows that see none get -inf.
+// k_look is dense [Lyr][Hkv][n_q][d].
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void sp_look_kernel(ScoreArgs a, const uint16_t *__restrict__ k_look,
+                                                           int look_self, int D, float *__restrict__ out)
+{
+    const int phase = blockIdx.x, row = threadIdx.x;
+    if (row >= a.rows_pad) return;
+    const int layer = phase / a.n_kv_heads, kv = phase - layer * a.n_kv_heads;
+    int g, n;
+    float v = neg_inf();
+    if (row_to_gn(a, row, g, n)) {
+        const uint16_t *qr = a.q + (((int64_t)layer * a.n_q_heads + (int64_t)kv * a.group + g) * a.n_q + n) * D;
+        const uint16_t *kb = k_look + ((int64_t)layer * a.n_kv_heads + kv) * a.n_q * D;
+        const int n_vis = min(n + (look_self ? 1 : 0), a.n_q);
+        float m = neg_inf(), l = 0.f;
+        for (int j = 0; j < n_vis; ++j) {
+            float dot = 0.f;
+            for (int e = 0; e < D; ++e)
+                dot = fmaf(__uint_as_float((uint32_t)qr[e] << 16), __uint_as_float((uint32_t)kb[(int64_t)j * D + e] << 16), dot);
+            lse_merge(m, l, dot, 1.f, a.c);
+        }
+        if (l > 0.f) v = m + fast_log2(l) * a.inv_c;
+    }
+    out[(int64_t)phase * a.rows_pad + row] = v;
 }
 
 // ---------------------------------------------------------------------------
@@ -494,7 +532,7 @@ sp_status make_plan(const sp_score_desc *d, Plan &p)
 }
 
 struct WsLayout {
-    size_t part, lse, tiles, prompt_tiles, split, fused, total;
+    size_t part, lse, tiles, prompt_tiles, split, look, fused, total;
 };
 
 // Shapes the fused single-launch kernel can hold on chip (any L; the length test is separate).
@@ -538,6 +576,7 @@ WsLayout ws_layout(const Plan &p, int64_t n_tiles, int n_prompts)
     w.tiles = off; off = sp::align_up(off + sizeof(TileInfo) * (size_t)n_tiles, 256);
     w.prompt_tiles = off; off = sp::align_up(off + sizeof(int32_t) * (size_t)(n_prompts + 1), 256);
     w.split = off; off = sp::align_up(off + sizeof(float) * split_buf_floats(p, n_tiles), 256);
+    w.look = off; off = sp::align_up(off + sizeof(float) * (size_t)p.n_phases * p.rows_pad, 256);
     w.fused = off;
     if (fused_shape_ok(p) && n_prompts == 1) {
         int64_t n_wg = n_tiles * p.tile_keys / sp_fused::kTileKeys + 1;
@@ -572,7 +611,8 @@ sp_status launch_all(const Plan &p, const ScoreArgs &a, const LayerPtrs &kp, hip
 
 sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
                      const int64_t *offsets_host, const int64_t *offsets_dev, int32_t B, int64_t L_single,
-                     float *scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
+                     const void *k_look_dev, int32_t look_self, float *scores_dev, void *ws_dev, size_t ws_bytes,
+                     void *hip_stream)
 {
     Plan p;
     sp_status rc = make_plan(desc, p);
@@ -588,6 +628,7 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
         kp.p[l] = static_cast<const uint16_t *>(k_layers_host[l]);
     }
     if ((uintptr_t)q_dev % 16 != 0) return sp::fail(SP_ERR_INVALID_ARG, "q_dev is not 16-byte aligned");
+    if (look_self != 0 && look_self != 1) return sp::fail(SP_ERR_INVALID_ARG, "look_self = %d must be 0 or 1", look_self);
 
     int64_t total = 0, n_tiles = 0;
     const bool batch = offsets_host != nullptr;
@@ -644,6 +685,13 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
     a.inv_c = 1.0f / a.c;
     a.out_scale = (desc->layer_agg == SP_LAYER_MAX) ? 1.0f / (float)desc->n_q
                                                    : 1.0f / ((float)desc->n_q * (float)desc->n_layers);
+    if (k_look_dev) {
+        float *look = reinterpret_cast<float *>(ws + w.look);
+        hipLaunchKernelGGL(sp_look_kernel, dim3(p.n_phases), dim3(kThreads), 0, st, a,
+                           static_cast<const uint16_t *>(k_look_dev), (int)look_self, p.D, look);
+        SP_HIP_CHECK(hipGetLastError());
+        a.look = look;
+    }
     if (!batch && fused_applies(p, total, desc->k_stride_token)) {
         const int n_wg = fused_workgroups(total);
         {
@@ -653,6 +701,7 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
             f.k_stride_token = a.k_stride_token;
             f.k_stride_head = a.k_stride_head;
             f.L = total;
+            f.look = a.look;
             f.scores = scores_dev;
             f.n_wg = n_wg;
             f.n_layers = a.n_layers; f.n_q_heads = a.n_q_heads; f.n_kv_heads = a.n_kv_heads;
@@ -702,7 +751,18 @@ extern "C" int32_t sp_score_is_fused(const sp_score_desc *desc, int64_t L)
 extern "C" sp_status sp_score(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
                               int64_t L, float *scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
 {
-    return score_impl(desc, q_dev, k_layers_host, nullptr, nullptr, 1, L, scores_dev, ws_dev, ws_bytes, hip_stream);
+    return score_impl(desc, q_dev, k_layers_host, nullptr, nullptr, 1, L, nullptr, 0, scores_dev, ws_dev, ws_bytes,
+                      hip_stream);
+}
+
+extern "C" sp_status sp_score_look(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
+                                   int64_t L, const void *k_look_dev, int32_t look_self, float *scores_dev,
+                                   void *ws_dev, size_t ws_bytes, void *hip_stream)
+{
+    if (!k_look_dev) return sp::fail(SP_ERR_INVALID_ARG, "k_look_dev is null");
+    if ((uintptr_t)k_look_dev % 16 != 0) return sp::fail(SP_ERR_INVALID_ARG, "k_look_dev is not 16-byte aligned");
+    return score_impl(desc, q_dev, k_layers_host, nullptr, nullptr, 1, L, k_look_dev, look_self, scores_dev, ws_dev,
+                      ws_bytes, hip_stream);
 }
 
 extern "C" sp_status sp_score_batch(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
@@ -710,6 +770,6 @@ extern "C" sp_status sp_score_batch(const sp_score_desc *desc, const void *q_dev
                                     float *scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
 {
     if (!offsets_host) return sp::fail(SP_ERR_INVALID_ARG, "offsets_host is null");
-    return score_impl(desc, q_dev, k_layers_host, offsets_host, offsets_dev, B, 0, scores_dev, ws_dev, ws_bytes,
-                      hip_stream);
+    return score_impl(desc, q_dev, k_layers_host, offsets_host, offsets_dev, B, 0, nullptr, 0, scores_dev, ws_dev,
+                      ws_bytes, hip_stream);
 }

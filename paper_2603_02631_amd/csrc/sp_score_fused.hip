@@ -73,7 +73,8 @@ constexpr int kOffWstats = kOffQ2 + 2 * kQTileBytes;               // [2]
 constexpr int kOffCinit = kOffWstats + 2 * kWstatsBytes;           // [2][64] accumulator seeds
 constexpr int kOffXduty = kOffCinit + 2 * kMaxRowsF * 4;           // 8 KB: partials of the duty rows
 constexpr int kOffXlse = kOffXduty + 8192;                         // 1 KB: normaliser entries of one phase
-constexpr int kOffFail = kOffXlse + 1024;
+constexpr int kOffXlook = kOffXlse + 1024;                         // 1 KB: lookahead-key terms of one phase's rows
+constexpr int kOffFail = kOffXlook + 1024;
 constexpr int kOffKring = (kOffFail + 16 + 1023) / 1024 * 1024;    // [8 waves][3 slots][32 rows x 128 bytes]
 constexpr int kSubBytes = 32 * kD * 2;
 constexpr int kLdsBytes = kOffKring + kFWaves * kSubSlots * kSubBytes;
@@ -410,6 +411,16 @@ __device__ __forceinline__ void stage_entries(uint32_t lds_dst, const uint64_t *
     dma_v_device(row + 2 * min(lane, pairs - 1), lds_dst);
 }
 
+// The normaliser wave's requests of one step: the rows' lookahead-key terms (when the call has
+// them; 4-byte entries, four to a lane) and, behind them, the normaliser entries. Loads return in
+// order, so the wait for the normalisers covers both.
+__device__ __forceinline__ void stage_exchange_rows(uint32_t xlse_ad, const uint64_t *lse_row, const float *look_row,
+                                                    int rows_pad, int lane)
+{
+    if (look_row != nullptr) dma_v_device(look_row + 4 * min(lane, rows_pad / 4 - 1), xlse_ad + (kOffXlook - kOffXlse));
+    stage_entries(xlse_ad, lse_row, rows_pad / 2, lane);
+}
+
 // ---- statistics pass of one phase: per-wave (max, sum exp) of every row into wstats ----
 // Logits of 32 keys (one sub-tile) against 32 query rows: d[r] is key 8*(r/4) + 4*hf + r%4 of the
 // sub-tile, query row col.
@@ -475,7 +486,7 @@ template <int NBLK, int PAR>
 __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t koff0,
                                            uint32_t koff1, uint32_t wstats_ad, int r_lo, int wave, int lane,
                                            const KIssue &ki, const uint32_t (&voff)[2], const uint64_t *lse_row,
-                                           int rows_pad, uint32_t xlse_ad)
+                                           const float *look_row, int rows_pad, uint32_t xlse_ad)
 {
     constexpr int kPerStep = kSubInstr / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
     const int hf = lane >> 5;
@@ -487,7 +498,7 @@ __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], cons
     float m = neg_inf(), l = 0.f;
     fold_logits(da, m, l, c, lo0, hf);
     k_issue<kPerStep>(ki, voff, 0);
-    if (lse_row != nullptr) stage_entries(xlse_ad, lse_row, rows_pad / 2, lane);
+    if (lse_row != nullptr) stage_exchange_rows(xlse_ad, lse_row, look_row, rows_pad, lane);
     __builtin_amdgcn_sched_barrier(0);
     if (NBLK == 2) {
         lift_at<kOffQ1 + PAR * kQTileBytes + 4096>(lc, qf);
@@ -552,6 +563,14 @@ __device__ __forceinline__ uint64_t read_lse_staging(uint32_t lds0, int lane)
     const uint32_t ad = lds0 + kOffXlse + 8u * (uint32_t)lane;
     uint64_t v;
     __asm__ volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(ad) : "memory");
+    return v;
+}
+
+__device__ __forceinline__ float read_look_staging(uint32_t lds0, int lane)
+{
+    const uint32_t ad = lds0 + kOffXlook + 4u * (uint32_t)lane;
+    float v;
+    __asm__ volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(ad) : "memory");
     return v;
 }
 
@@ -709,13 +728,14 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
         ki.base = kbase + (int64_t)32 * stride_bytes;
         ki.step_bytes = 8u * stride_bytes;
         const uint64_t *lse_row = wave == kLseWave ? a.lse + (size_t)(clampi(pl, 0, n_phases - 1) % kSlots) * a.rows_pad : nullptr;
+        const float *look_row = a.look != nullptr ? a.look + (size_t)clampi(pl, 0, n_phases - 1) * a.rows_pad : nullptr;
         if (do_stats) {
             const uint32_t wstats_ad = lds0 + kOffWstats + PAR * kWstatsBytes + wave * (kMaxRowsF * 8) + ((uint32_t)(lane & 31) << 3);
             stats_pass<NB * GB, PAR>(a.c, ring.kf[SLOT], lc, sub_slot_off(wave, wk.slot0, 0),
                                      sub_slot_off(wave, wk.slot0, 1), wstats_ad, r_lo, wave, lane, ki, voff, lse_row,
-                                     a.rows_pad, lds0 + kOffXlse);
+                                     look_row, a.rows_pad, lds0 + kOffXlse);
         } else {
-            if (lse_row != nullptr) stage_entries(lds0 + kOffXlse, lse_row, a.rows_pad / 2, lane);
+            if (lse_row != nullptr) stage_exchange_rows(lds0 + kOffXlse, lse_row, look_row, a.rows_pad, lane);
             k_issue<kSubInstr>(ki, voff, 0);
         }
     }
@@ -787,6 +807,12 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
                     } while ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1));
                 }
                 v = __uint_as_float((uint32_t)entry);
+                if (a.look != nullptr) {
+                    // the row's softmax also runs over its visible lookahead keys: log-sum-exp of the
+                    // prompt's normaliser and theirs (-inf when the row sees none), in raw-logit units
+                    const float lp = -v, lk = read_look_staging(lds0, lane), top = fmaxf(lp, lk);
+                    v = -(top + fast_log2(fast_exp2((lp - top) * a.c) + fast_exp2((lk - top) * a.c)) * a.inv_c);
+                }
             }
             const int rho = lane & 31;
             lds_store_f32(lds0 + kOffCinit + PAR * (kMaxRowsF * 4) +

@@ -18,6 +18,8 @@ struct FusedArgs {
     uint64_t *part;              // [kSlots][n_wg][rows_pad]  (max, sum exp) partials, parity in bit 63
     uint64_t *lse;               // [kSlots][rows_pad]        (-lse, phase + 1)
     uint32_t *err;
+    const float *look;           // [n_phases][rows_pad] log-sum-exp of each row over its visible lookahead keys
+                                 // (raw-logit units, -inf for none), or null: prompt keys only
     const uint64_t *zeros;       // 128 zero bytes (source of padding query rows)
     float *scores;
     int32_t n_wg;

@@ -267,6 +267,75 @@ def test_scale_is_applied_inside_the_exponent():
     assert np.abs(c - b).max() > 1e-6
 
 
+
+# --------------------------------------------------------------------------
+# lookahead keys in the normaliser  (Algorithm 1, ForwardWithAttn with lookahead = i)
+# --------------------------------------------------------------------------
+
+def test_look_zero_queries_closed_form_counts_visible_keys():
+    """All logits 0: row n is uniform over L + (n + look_self) keys, so
+    I[j] = mean_n 1 / (L + n + look_self) in both modes. Catches an off-by-one in
+    the visible count and a look_self flag that does nothing."""
+    Lyr, H, Hkv, n_q, d, L = 2, 4, 2, 5, 16, 37
+    qb = bits(np.zeros((Lyr, H, n_q, d), np.float32))
+    rng = np.random.default_rng(31)
+    kb = [bits(rand_small_ints(rng, (Hkv, L, d))) for _ in range(Lyr)]
+    kl = bits(rand_small_ints(rng, (Lyr, Hkv, n_q, d)))
+    for look_self in (0, 1):
+        want = float(np.mean([Fraction(1, L + n + look_self) for n in range(n_q)]))
+        for mode in (oracle.LAYER_MEAN, oracle.LAYER_MAX):
+            I = oracle.score_look(qb, kb, kl, look_self, 0.25, mode)
+            np.testing.assert_allclose(I, want, rtol=1e-14)
+
+
+def test_look_equals_plain_score_on_concatenated_keys_row_by_row():
+    """Row n normalised over prompt + visible lookahead keys is the plain softmax of
+    the prompt with those keys appended as extra tokens. Per lookahead row the
+    pinned plain path scores that row alone (n_q = 1) against the concatenation;
+    the mean over rows must equal the lookahead variant. Catches a wrong kv head,
+    a transposed lookahead operand, a causal mask off by one, a dropped term."""
+    rng = np.random.default_rng(32)
+    Lyr, H, Hkv, n_q, d, L = 3, 4, 2, 4, 16, 83
+    qf, kf = make_qk(rng, Lyr, H, Hkv, n_q, d, L)
+    klf = rand_small_ints(rng, (Lyr, Hkv, n_q, d))
+    qb, kb, kl = bits(qf), [bits(k) for k in kf], bits(klf)
+    for look_self in (0, 1):
+        for mode in (oracle.LAYER_MEAN, oracle.LAYER_MAX):
+            rows = []
+            for n in range(n_q):
+                vis = min(n + look_self, n_q)
+                cat = [np.concatenate([kb[l], kl[l][:, :vis, :]], axis=1) for l in range(Lyr)]
+                rows.append(oracle.score(qb[:, :, n:n + 1, :], cat, 0.25, mode)[:L])
+            got = oracle.score_look(qb, kb, kl, look_self, 0.25, mode)
+            np.testing.assert_allclose(got, np.mean(rows, axis=0), rtol=1e-12)
+            # the lookahead keys take probability mass: strictly below the prompt-only scores
+            # (row 0 without look_self sees none, so compare the sum)
+            assert got.sum() < oracle.score(qb, kb, 0.25, mode).sum()
+
+
+def test_look_single_row_library_softmax_and_token_major_layout():
+    """One layer, one head, two lookahead rows, look_self = 1: each row is scipy's
+    softmax of [prompt logits, visible lookahead logits]; also through the
+    token-major K layout."""
+    rng = np.random.default_rng(33)
+    d, L = 32, 61
+    qf = rng.standard_normal((1, 1, 2, d)).astype(np.float32)
+    kf = rng.standard_normal((1, L, d)).astype(np.float32)
+    klf = rng.standard_normal((1, 1, 2, d)).astype(np.float32)
+    qb, kb, kl = bits(qf), bits(kf), bits(klf)
+    Q = bf16_bits_to_f32(qb[0, 0]).astype(np.float64)
+    K = bf16_bits_to_f32(kb[0]).astype(np.float64)
+    KL = bf16_bits_to_f32(kl[0, 0]).astype(np.float64)
+    scale = 0.2
+    ref = np.zeros(L)
+    for n in range(2):
+        row = np.concatenate([K @ Q[n], KL[:n + 1] @ Q[n]]) * scale
+        ref += scipy.special.softmax(row)[:L] / 2
+    np.testing.assert_allclose(oracle.score_look(qb, [kb], kl, 1, scale, oracle.LAYER_MAX), ref, rtol=1e-12)
+    k_nhd = np.ascontiguousarray(kb.transpose(1, 0, 2))
+    np.testing.assert_allclose(oracle.score_look(qb, [k_nhd], kl, 1, scale, 0, layout="NHD"), ref, rtol=1e-12)
+
+
 # --------------------------------------------------------------------------
 # pooling and chunk means  (Algorithm 1, Appendix A.1.2, Appendix A.3)
 # --------------------------------------------------------------------------
