@@ -13,6 +13,7 @@ from .gen import (
     f32_to_bf16_bits,
     gen_char_offsets,
     gen_k_layer,
+    gen_look_keys,
     gen_prompt_lengths,
     gen_q,
     heavy_hitter_positions,
@@ -28,6 +29,7 @@ __all__ = [
     "f32_to_bf16_bits",
     "gen_char_offsets",
     "gen_k_layer",
+    "gen_look_keys",
     "gen_prompt_lengths",
     "gen_q",
     "heavy_hitter_positions",

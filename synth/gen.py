@@ -21,6 +21,7 @@ _STREAM_Q = 0
 _STREAM_HH = 1
 _STREAM_LEN = 2
 _STREAM_CHARS = 3
+_STREAM_LOOK = 4
 _STREAM_K0 = 16        # layer l draws from stream _STREAM_K0 + l
 
 
@@ -82,6 +83,16 @@ def gen_q(w: Workload, n_prompts: int = 1) -> np.ndarray:
     rng = _rng(w.cfg_id, _STREAM_Q)
     x = rng.standard_normal((n_prompts, w.n_layers, w.n_q_heads, w.n_q, w.head_dim), dtype=np.float32)
     return f32_to_bf16_bits(x)
+
+
+def gen_look_keys(w: Workload, q_bits: np.ndarray, self_gain: float = 1.0) -> np.ndarray:
+    """Keys of the lookahead tokens of prompt 0 as bf16 bits, [n_layers][n_kv_heads][n_q][head_dim]:
+    N(0,1) plus ``self_gain`` times the query vector of the same lookahead row (first head of the kv
+    head's group), so that a row attends to its own token's key about as strongly as decoders do."""
+    rng = _rng(w.cfg_id, _STREAM_LOOK)
+    x = rng.standard_normal((w.n_layers, w.n_kv_heads, w.n_q, w.head_dim), dtype=np.float32)
+    qv = bf16_bits_to_f32(q_bits[0][:, ::w.group, :, :])
+    return f32_to_bf16_bits(x + np.float32(self_gain) * qv)
 
 
 def gen_k_layer(w: Workload, layer: int, q_bits: np.ndarray, lengths: Sequence[int],

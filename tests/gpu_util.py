@@ -50,6 +50,26 @@ def gpu_score(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], scale: float, 
     return scores[:L].cpu().numpy()
 
 
+def gpu_score_look(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], k_look: np.ndarray, look_self: int,
+                   scale: float, layer_agg: int = 0, layout: str = "HND",
+                   k_dev: Optional[List[torch.Tensor]] = None) -> np.ndarray:
+    """gpu_score with the lookahead keys k_look (uint16 [Lyr][Hkv][n_q][d]) in the normaliser."""
+    Lyr, H, n_q, d = q_bits.shape
+    if layout == "HND":
+        Hkv, L, _ = k_layers[0].shape
+    else:
+        L, Hkv, _ = k_layers[0].shape
+    desc = make_desc(Lyr, H, Hkv, d, n_q, scale, layer_agg, layout, L)
+    qd = dev_bits(q_bits)
+    kd = k_dev if k_dev is not None else [dev_bits(k) for k in k_layers]
+    kl = dev_bits(k_look)
+    ws = workspace(sp.sp_score_workspace(desc, L, 1))
+    scores = torch.full((max(L, 1),), float("nan"), dtype=torch.float32, device=DEV)
+    sp.sp_score_look(desc, qd, kd, L, kl, look_self, scores, ws)
+    torch.cuda.synchronize()
+    return scores[:L].cpu().numpy()
+
+
 def gpu_score_batch(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], offsets: np.ndarray, scale: float,
                     layer_agg: int = 0, layout: str = "HND") -> np.ndarray:
     """q_bits: uint16 [B][Lyr][H][n_q][d]; k_layers packed along tokens."""

@@ -105,6 +105,16 @@ def test_score_workspace_and_argument_errors():
     with pytest.raises(sp.SpError):             # wrong number of layers (caught by the binding)
         sp.sp_score(d, fake, [fake], 1024, fake, fake, n, stream=0)
     sp.sp_score(d, fake, layers, 0, fake, None, 0, stream=0)   # empty prompt: no-op, SP_OK
+    with pytest.raises(sp.SpError) as e:        # lookahead variant: null lookahead keys
+        sp.sp_score_look(d, fake, layers, 1024, None, 0, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:        # misaligned lookahead keys
+        sp.sp_score_look(d, fake, layers, 1024, fake + 4, 0, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:        # look_self outside {0, 1}
+        sp.sp_score_look(d, fake, layers, 1024, fake, 2, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    sp.sp_score_look(d, fake, layers, 0, fake, 1, fake, None, 0, stream=0)   # empty prompt: no-op
 
 
 def test_score_batch_argument_errors():

@@ -183,3 +183,42 @@ def test_fused_score_matches_oracle(shape):
     nhd = [np.ascontiguousarray(k.transpose(1, 0, 2)) for k in inp["k"]]
     got_nhd = gpu_score(inp["q"][0], nhd, w.scale, 1, layout="NHD")
     assert got_nhd.tobytes() == got.tobytes()        # same keys through token-major strides
+
+
+LOOK_SHAPES = [
+    # name, Lyr, H, Hkv, d, n_q, L   (general path: short prompts, head_dim 128; fused path: long prompts)
+    ("look_g4_nq16_d64", 3, 8, 2, 64, 16, 1500),
+    ("look_g2_nq8_d128", 2, 4, 2, 128, 8, 777),
+    ("look_g3_nq5_d64", 2, 6, 2, 64, 5, 333),
+    ("look_nq1_d64", 2, 4, 2, 64, 1, 300),
+    ("look_fused_g4_nq16", 3, 8, 2, 64, 16, 33000),
+    ("look_fused_g3_nq5_padding", 2, 6, 2, 64, 5, 35000),
+]
+
+
+@pytest.mark.parametrize("shape", LOOK_SHAPES, ids=[s[0] for s in LOOK_SHAPES])
+def test_score_with_lookahead_keys_matches_oracle(shape):
+    """sp_score_look: the rows' normalisers include their visible lookahead keys
+    (Algorithm 1, ForwardWithAttn at lookahead = i); both visibility settings and
+    both aggregation modes, on both kernels."""
+    import paper_2603_02631_amd as sp
+    from gpu_util import assert_scores_close, gpu_score, gpu_score_look, make_desc
+    name, Lyr, H, Hkv, d, n_q, L = shape
+    say(f"[score-look] {name} Lyr={Lyr} H={H} Hkv={Hkv} d={d} n_q={n_q} L={L}")
+    w = small_workload(name, Lyr, H, Hkv, d, n_q, L, cfg_id=300 + LOOK_SHAPES.index(shape), hh=(1, 1000))
+    fused = sp.sp_score_is_fused(make_desc(Lyr, H, Hkv, d, n_q, w.scale, 0, "HND", L), L)
+    assert fused == (1 if "fused" in name else 0)
+    inp = synth.make_score_inputs(w)
+    q = inp["q"][0]
+    kl = synth.gen_look_keys(w, inp["q"])
+    plain = oracle.score(q, inp["k"], w.scale, 0)
+    for look_self in (0, 1):
+        for mode in (0, 1):
+            want = oracle.score_look(q, inp["k"], kl, look_self, w.scale, mode)
+            got = gpu_score_look(q, inp["k"], kl, look_self, w.scale, mode)
+            assert_scores_close(got, want)
+            say(f"  self {look_self} mode {mode}: max rel err {np.max(np.abs(got - want) / want):.2e}")
+    # the term matters on these inputs, well above the tolerance (a test that passes without it would prove nothing)
+    assert np.max(np.abs(oracle.score_look(q, inp["k"], kl, 1, w.scale, 0) - plain) / plain) > 5e-3
+    # and a call without lookahead keys afterwards is the plain result again (no state left behind)
+    assert_scores_close(gpu_score(q, inp["k"], w.scale, 0), plain)
