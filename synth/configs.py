@@ -1,9 +1,10 @@
-"""Workload table: the five draft-model-shaped configurations.
+"""Workload table: the draft-model-shaped configurations.
 
 Shapes follow small draft models of the kind the paper uses (a 16-layer
 32-query/8-kv-head model with head_dim 64, and a 28-layer 16/8-head model with
 head_dim 128; Table 1 of the paper names drafts of these families), with the
-paper's hyper-parameters (lookahead 8, pool 13, chunk 32; Appendix A.3).
+paper's hyper-parameters (lookahead 8, pool 13, chunk 32, and chunk 128 for the
+code-debugging setting; Appendix A.3).
 """
 from __future__ import annotations
 
@@ -55,6 +56,11 @@ CONFIGS = {
     "llama1b-8k": Workload("llama1b-8k", 2, 16, 32, 8, 64, 8, 8192, keep_num=20),
     "qwen06b-32k": Workload("qwen06b-32k", 3, 28, 16, 8, 128, 8, 32768, keep_num=15),
     "long-128k": Workload("long-128k", 4, 16, 32, 8, 64, 16, 131072, chunk=64,
+                          keep_num=10, hh_frac_num=1, hh_frac_den=1000,
+                          hh_bands=8, hh_band_len=512),
+    # the longest prompts of the paper's suites (a quarter of a million tokens) with the chunk size of
+    # its code-debugging setting
+    "long-256k": Workload("long-256k", 6, 16, 32, 8, 64, 8, 262144, chunk=128,
                           keep_num=10, hh_frac_num=1, hh_frac_den=1000,
                           hh_bands=8, hh_band_len=512),
     "ragged-16": Workload("ragged-16", 5, 16, 32, 8, 64, 8, 0, keep_num=20, batch=16),

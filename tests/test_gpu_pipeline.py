@@ -123,6 +123,36 @@ def test_pipeline_full_size_benchmark_workload():
 
 
 @pytest.mark.timeout(400)
+def test_pipeline_full_size_quarter_million_tokens_chunk_128():
+    """262144 tokens, chunk 128 (the code-debugging setting of Appendix A.3): too long for the
+    single-launch kernel, so the general score path at full size with no layer split, then selection
+    and projection; and the same prompt scored with the lookahead keys in the normaliser."""
+    import paper_2603_02631_amd as sp
+    from gpu_util import assert_scores_close, dev_bits, gpu_score_look, make_desc
+    w = synth.get_config("long-256k")
+    say(f"[pipeline] {w.name}: generating {w.k_bytes_per_token * w.L / 2**30:.2f} GiB of keys")
+    inp = synth.make_score_inputs(w)
+    doff, toff = synth.gen_char_offsets(w, w.L)
+    assert sp.sp_score_is_fused(make_desc(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_q, w.scale, 0,
+                                          "HND", w.L), w.L) == 0
+    k_dev = [dev_bits(k) for k in inp["k"]]
+    t0 = time.time()
+    I = oracle.score(inp["q"][0], inp["k"], w.scale, oracle.LAYER_MEAN)
+    say(f"[pipeline] {w.name} mean: oracle {time.time() - t0:.1f}s")
+    out = run_pipeline_gpu(w, inp["q"][0], k_dev, w.L, doff, toff, oracle.LAYER_MEAN)
+    diff = check_pipeline(w, out, I, doff, toff)
+    say(f"[pipeline] {w.name} mean: ok, max rel err {np.max(np.abs(out['scores'] - I) / I):.2e}, selection differs "
+        f"from oracle in {diff} chunks, kept {out['n_kept']} of {toff.size - 1} target tokens")
+    kl = synth.gen_look_keys(w, inp["q"])
+    t0 = time.time()
+    I = oracle.score_look(inp["q"][0], inp["k"], kl, 1, w.scale, oracle.LAYER_MAX)
+    say(f"[pipeline] {w.name} lookahead keys, max: oracle {time.time() - t0:.1f}s")
+    got = gpu_score_look(inp["q"][0], inp["k"], kl, 1, w.scale, oracle.LAYER_MAX, k_dev=k_dev)
+    assert_scores_close(got, I)
+    say(f"[pipeline] {w.name} lookahead keys, max: ok, max rel err {np.max(np.abs(got - I) / I):.2e}")
+
+
+@pytest.mark.timeout(400)
 def test_score_batch_full_size_ragged_workload():
     """The 16-prompt ragged batch (2K to 64K tokens, 332K in all) at full size: every prompt's
     scores against the oracle run on that prompt alone."""
