@@ -246,3 +246,22 @@ def select(I: np.ndarray, w: int, c: int, k: int):
     cs = chunk_mean(pool(I, w), c)
     sel = topk(cs, k)
     return sel, merge(sel, c, I.size), cs
+
+
+def budget_keep(cs: np.ndarray, c: int, draft_off: np.ndarray, target_off: np.ndarray, budget: int):
+    """Budget-targeted keep (Section 3.1: the compressed prompt is to have a fixed target-side length,
+    a multiple of the KV block size): the largest k in 1..C for which the top-k chunks, merged and
+    projected onto the target tokenisation, keep at most `budget` target tokens; 1 if even one chunk
+    keeps more. Plain search: every k is tried with the same steps the pipeline uses (topk, merge,
+    project). Returns (k, n_kept at that k). For small inputs: the cost is C full projections."""
+    cs = np.ascontiguousarray(cs, dtype=np.float64)
+    L = int(np.asarray(draft_off).size) - 1
+    best_k, best_kept = 1, None
+    for k in range(1, cs.size + 1):
+        _, _, n_kept = project(draft_off, target_off, merge(topk(cs, k), c, L))
+        if k == 1:
+            best_kept = n_kept
+        if n_kept <= int(budget):
+            best_k, best_kept = k, n_kept
+    return best_k, best_kept
+

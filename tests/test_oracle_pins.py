@@ -622,6 +622,57 @@ def test_keep_rate_from_target_budget_lands_near_the_budget():
     assert oracle.keep_count(C, 2 * M, M) == C and oracle.keep_count(C, 0, M) == 1   # clamped to [1, C]
 
 
+def test_budget_keep_worked_example_and_identity_tokenisation():
+    """Budget-targeted keep. Hand-worked: 4 one-token chunks of 2 characters, target tokens
+    [0,3) [3,5) [5,8), chunk scores .1 .9 .5 .2. Top-1 (chunk 1, chars [2,4)) touches tokens 0 and 1;
+    from top-2 on all three tokens are kept. With one-character tokens in both tokenisations and full
+    chunks, k chunks keep exactly k*c tokens, so k = floor(budget / c), clamped to [1, C]."""
+    doff = np.array([0, 2, 4, 6, 8])
+    toff = np.array([0, 3, 5, 8])
+    cs = np.array([0.1, 0.9, 0.5, 0.2])
+    assert oracle.budget_keep(cs, 1, doff, toff, 2) == (1, 2)
+    assert oracle.budget_keep(cs, 1, doff, toff, 3) == (4, 3)      # every k >= 2 keeps 3: the largest wins
+    assert oracle.budget_keep(cs, 1, doff, toff, 1) == (1, 2)      # even one chunk exceeds the budget: k = 1
+    rng = np.random.default_rng(41)
+    c, C = 8, 12
+    off = np.arange(c * C + 1)
+    cs = rng.random(C)
+    for budget in (0, 7, 8, 9, 31, 32, 95, 96, 1000):
+        k, kept = oracle.budget_keep(cs, c, off, off, budget)
+        assert k == min(C, max(1, budget // c)) and kept == k * c
+
+
+def test_budget_keep_against_character_coverage_brute_force():
+    """Tiny random tokenisations: per k, the chunks are ranked with Python's sort (score descending,
+    index ascending), the characters of the first k chunks are put in a set, and a target token counts
+    as kept iff one of its characters is in it; the answer is the largest k within the budget.
+    Independent of the oracle's own top-k, merge and projection."""
+    rng = np.random.default_rng(42)
+    for trial in range(30):
+        L = int(rng.integers(5, 40))
+        c = int(rng.integers(1, 6))
+        dlen = rng.integers(1, 6, size=L)
+        doff = np.concatenate([[0], np.cumsum(dlen)])
+        total = int(doff[-1])
+        cuts = np.sort(rng.choice(np.arange(1, total), size=int(rng.integers(1, max(2, total // 3))), replace=False))
+        toff = np.concatenate([[0], cuts, [total]])
+        C = -(-L // c)
+        cs = rng.integers(0, 4, size=C).astype(np.float64)          # many exact ties
+        order = sorted(range(C), key=lambda j: (-cs[j], j))
+        kept_at = []
+        for k in range(1, C + 1):
+            chars = set()
+            for j in order[:k]:
+                chars.update(range(int(doff[j * c]), int(doff[min((j + 1) * c, L)])))
+            kept_at.append(sum(1 for t in range(toff.size - 1)
+                               if any(x in chars for x in range(int(toff[t]), int(toff[t + 1])))))
+        assert kept_at == sorted(kept_at)                           # more chunks never keep fewer tokens
+        for budget in (0, kept_at[0], kept_at[C // 2], kept_at[C // 2] - 1, kept_at[-1], kept_at[-1] + 5):
+            within = [k for k in range(1, C + 1) if kept_at[k - 1] <= budget]
+            want_k = max(within) if within else 1
+            assert oracle.budget_keep(cs, c, doff, toff, budget) == (want_k, kept_at[want_k - 1]), (trial, budget)
+
+
 # --------------------------------------------------------------------------
 # compressed-prompt assembly (Algorithm 1: ConcatWithDelim, new position ids; Section 3.2)
 # --------------------------------------------------------------------------
