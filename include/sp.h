@@ -173,6 +173,37 @@ sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_w,
                     float *chunk_scores_dev, void *ws_dev, size_t ws_bytes,
                     void *hip_stream);
 
+/* Bytes of workspace sp_select_budget needs (SP_ERR_UNSUPPORTED beyond 65536 chunks). */
+sp_status sp_select_budget_workspace(int64_t L, int32_t chunk, size_t *bytes);
+
+/*
+ * Chunk selection for a fixed target-side length (Section 3.1: compressed
+ * prompts of 8k .. 32k target tokens, multiples of the KV block size; the
+ * paper derives the keep rate from that length and notes that the result only
+ * lands near it). Here k is searched on the device: the largest k in 1..C such
+ * that the top-k chunks, merged into spans and projected onto the target
+ * tokenisation exactly as sp_project does, keep at most `budget` target
+ * tokens; k = 1 if a single chunk already keeps more. Pooling, chunk scores,
+ * ranking and tie-breaking are those of sp_select, and the outputs are what
+ * sp_select would write for that k, except that the buffers must hold the
+ * worst case: sel_chunks_dev[C], spans_dev[C][2] (C = ceil(L/chunk) <= 65536).
+ *  - draft_off_dev[L+1], target_off_dev[M+1]: character offsets as in sp_project;
+ *  - *k_dev: the chosen k (also the number of entries of sel_chunks_dev written);
+ *  - *n_kept_dev: optional, the target tokens kept at that k (what sp_project
+ *    reports for the written spans);
+ *  - chunk_scores_dev: optional float[C].
+ * Requires L >= 1, 1 <= M < 2^31, budget >= 0. Integer work after the chunk
+ * scores: exact and deterministic.
+ */
+sp_status sp_select_budget(const float *scores_dev, int64_t L, int32_t pool_w,
+                           int32_t chunk, const int64_t *draft_off_dev,
+                           const int64_t *target_off_dev, int64_t M,
+                           int64_t budget, int32_t *sel_chunks_dev,
+                           int64_t *spans_dev, int32_t *n_spans_dev,
+                           int64_t *k_dev, int64_t *n_kept_dev,
+                           float *chunk_scores_dev, void *ws_dev,
+                           size_t ws_bytes, void *hip_stream);
+
 /*
  * Projection of kept draft-token spans onto the target model's tokenisation
  * (Algorithm 1: MapDraftChunksToTextSpans and the target tokenisation of the

@@ -23,6 +23,8 @@ from .binding import (  # noqa: F401
     sp_score_is_fused,
     sp_score_workspace,
     sp_select,
+    sp_select_budget,
+    sp_select_budget_workspace,
     sp_select_workspace,
     sp_version,
 )

@@ -16,6 +16,24 @@
 //                    scans then emit the kept indices in ascending order and
 //                    the merged spans.
 // Everything is integer or fixed-order fp32 work, so results are deterministic.
+//
+// sp_select_budget (Section 3.1: a fixed target-side length of the compressed
+// prompt) finds k on the device instead of taking it from the host. With
+// rank[j] = position of chunk j in the order (score descending, index
+// ascending), the top-k chunks are those of rank < k, and whether target token t
+// is kept by the top-k chunks depends on k only through one number r(t): a token
+// with at least one character is kept iff some chunk whose character interval it
+// overlaps is selected, r(t) = the smallest rank among those chunks; a token
+// without characters is kept iff it lies strictly inside a merged span, i.e.
+// inside one chunk or on a boundary whose chunks on both sides are all selected,
+// r(t) = the largest rank among them. Kept tokens at k = #{t : r(t) < k}: a
+// histogram of r and a prefix sum give the count for every k at once.
+//   sp_rank_kernel        rank of every chunk by counting (C^2 / 2 comparisons
+//                         spread over the device), clears the histogram;
+//   sp_token_rank_kernel  one thread per target token: binary searches of the
+//                         chunk boundaries' character offsets, r(t), histogram;
+//   sp_budget_kernel      one workgroup: prefix sum, largest k within the budget;
+//   sp_topk_kernel        as above, reading k from device memory.
 #include "sp_common.hpp"
 
 namespace {
@@ -103,12 +121,16 @@ __device__ __forceinline__ int block_scan_incl(int v, int *wave_tot /*[16]*/, in
 }
 
 __global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__restrict__ cs, int64_t n_chunks,
-                                                               int64_t k, int chunk, int64_t L,
-                                                               int32_t *sel,
+                                                               int64_t k, const int64_t *__restrict__ k_dev,
+                                                               int chunk, int64_t L, int32_t *sel,
                                                                int64_t *__restrict__ spans,
                                                                int32_t *__restrict__ n_spans)
 {
     __shared__ int hist[256];
+    if (k_dev) {                             // k chosen on the device (budget search); always within 1..n_chunks
+        k = *k_dev;
+        k = k < 1 ? 1 : (k > n_chunks ? n_chunks : k);
+    }
     __shared__ int wave_tot[kTopkThreads / 64];
     __shared__ uint32_t s_prefix;
     __shared__ int64_t s_need;
@@ -189,6 +211,146 @@ __global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__re
     if (tid == 0) *n_spans = (int32_t)span_base;
 }
 
+// ---------------------------------------------------------------------------
+// budget search
+// ---------------------------------------------------------------------------
+constexpr int kRankThreads = 256;
+constexpr int kMaxBudgetChunks = 1 << 16;
+
+// rank[j] = number of chunks that come before chunk j in the order (score descending, index
+// ascending). Also clears the C + 1 histogram bins.
+__global__ __launch_bounds__(kRankThreads) void sp_rank_kernel(const float *__restrict__ cs, int n_chunks,
+                                                               int32_t *__restrict__ rank,
+                                                               int32_t *__restrict__ hist)
+{
+    __shared__ uint32_t tile[kRankThreads];
+    const int j = blockIdx.x * kRankThreads + threadIdx.x;
+    const uint32_t mine = j < n_chunks ? order_key(cs[j]) : 0u;
+    int before = 0;
+    for (int base = 0; base < n_chunks; base += kRankThreads) {
+        const int i = base + threadIdx.x;
+        __syncthreads();
+        tile[threadIdx.x] = i < n_chunks ? order_key(cs[i]) : 0u;
+        __syncthreads();
+        const int n = min(kRankThreads, n_chunks - base);
+        for (int t = 0; t < n; ++t) {
+            const uint32_t other = tile[t];
+            before += (other > mine) || (other == mine && base + t < j);
+        }
+    }
+    if (j < n_chunks) {
+        rank[j] = before;
+        hist[j] = 0;
+    }
+    if (j == 0) hist[n_chunks] = 0;
+}
+
+// Character offset of chunk boundary m (0 .. C): boundary C is the end of the text.
+__device__ __forceinline__ int64_t boundary(const int64_t *__restrict__ doff, int64_t L, int chunk, int m)
+{
+    const int64_t tok = (int64_t)m * chunk;
+    return doff[tok < L ? tok : L];
+}
+
+// First boundary index in [lo, hi] whose offset is > x (STRICT) or >= x; hi + 1 if none.
+template <bool STRICT>
+__device__ __forceinline__ int first_boundary(const int64_t *__restrict__ doff, int64_t L, int chunk, int lo, int hi,
+                                              int64_t x)
+{
+    int a = lo, b = hi + 1;
+    while (a < b) {
+        const int mid = a + ((b - a) >> 1);
+        const int64_t e = boundary(doff, L, chunk, mid);
+        if (STRICT ? (e > x) : (e >= x)) b = mid; else a = mid + 1;
+    }
+    return a;
+}
+
+__global__ __launch_bounds__(kRankThreads) void sp_token_rank_kernel(const int64_t *__restrict__ doff, int64_t L,
+                                                                     int chunk, int n_chunks,
+                                                                     const int64_t *__restrict__ toff, int64_t M,
+                                                                     const int32_t *__restrict__ rank,
+                                                                     int32_t *__restrict__ hist)
+{
+    const int64_t t = (int64_t)blockIdx.x * kRankThreads + threadIdx.x;
+    if (t >= M) return;
+    const int64_t a = toff[t], b = toff[t + 1];
+    const int C = n_chunks;
+    int r = C;                                   // bin C: kept by no selection
+    if (b > a) {
+        // chunks j with a < e[j+1] and b > e[j]: a contiguous range
+        const int j_lo = first_boundary<true>(doff, L, chunk, 1, C, a) - 1;        // first j with e[j+1] > a
+        const int j_hi = first_boundary<false>(doff, L, chunk, 0, C - 1, b) - 1;   // last j with e[j] < b
+        if (j_lo < C && j_hi >= 0)
+            for (int j = j_lo; j <= j_hi; ++j) r = min(r, rank[j]);
+    } else {
+        const int m1 = first_boundary<false>(doff, L, chunk, 0, C, a);             // first boundary >= a
+        if (m1 <= C && m1 >= 1) {
+            if (boundary(doff, L, chunk, m1) != a) {
+                r = rank[m1 - 1];                                                   // strictly inside chunk m1 - 1
+            } else {
+                const int m2 = first_boundary<true>(doff, L, chunk, m1, C, a) - 1;  // last boundary == a
+                if (m2 < C) {                    // chunks m1-1 .. m2 all have to be selected
+                    int worst = 0;
+                    for (int j = m1 - 1; j <= m2; ++j) worst = max(worst, rank[j]);
+                    r = worst;
+                }
+            }
+        }
+    }
+    atomicAdd(&hist[r], 1);
+}
+
+// kept(k) = hist[0] + .. + hist[k-1]; writes the largest k in 1..C with kept(k) <= budget (1 if none)
+// and kept at that k.
+__global__ __launch_bounds__(kTopkThreads) void sp_budget_kernel(const int32_t *__restrict__ hist, int n_chunks,
+                                                                 int64_t budget, int64_t *__restrict__ k_out,
+                                                                 int64_t *__restrict__ kept_out)
+{
+    __shared__ int wave_tot[kTopkThreads / 64];
+    __shared__ int s_first;
+    const int tid = threadIdx.x;
+    int64_t carry = 0, within = 0, kept_within = 0;
+    for (int base = 0; base < n_chunks; base += kTopkThreads) {
+        const int i = base + tid;
+        if (base == 0 && tid == 0) s_first = hist[0];
+        const int h = i < n_chunks ? hist[i] : 0;
+        int total;
+        const int64_t incl = carry + block_scan_incl(h, wave_tot, total);   // kept(i + 1)
+        const int ok = (i < n_chunks && incl <= budget) ? 1 : 0;             // a prefix of the k's: kept is monotone
+        int ok_total;
+        block_scan_incl(ok, wave_tot, ok_total);
+        within += ok_total;
+        carry += total;
+        // kept at the last k within the budget: the largest incl that is <= budget
+        int64_t cand = ok ? incl : 0;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const int64_t o = __shfl_xor(cand, off);
+            cand = o > cand ? o : cand;
+        }
+        __shared__ int64_t wave_best[kTopkThreads / 64];
+        __syncthreads();
+        if ((tid & 63) == 0) wave_best[tid >> 6] = cand;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kTopkThreads / 64; ++w) kept_within = wave_best[w] > kept_within ? wave_best[w] : kept_within;
+    }
+    if (tid == 0) {
+        *k_out = within >= 1 ? within : 1;
+        if (kept_out) *kept_out = within >= 1 ? kept_within : (int64_t)s_first;
+    }
+}
+
+size_t budget_ws_layout(int64_t C, size_t &off_rank, size_t &off_hist, size_t &off_k)
+{
+    size_t off = sp::align_up(sizeof(float) * (size_t)C, 256);
+    off_rank = off; off = sp::align_up(off + sizeof(int32_t) * (size_t)C, 256);
+    off_hist = off; off = sp::align_up(off + sizeof(int32_t) * ((size_t)C + 1), 256);
+    off_k = off;    off = sp::align_up(off + sizeof(int64_t), 256);
+    return off;
+}
+
 }  // namespace
 
 extern "C" sp_status sp_select_workspace(int64_t L, int32_t chunk, size_t *bytes)
@@ -225,8 +387,67 @@ extern "C" sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_
     hipLaunchKernelGGL(sp_chunk_kernel, dim3(grid), dim3(kChunkThreads), 0, st, scores_dev, L, (int)pool_w,
                        (int)chunk, C, cs, chunk_scores_dev);
     SP_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(sp_topk_kernel, dim3(1), dim3(kTopkThreads), 0, st, (const float *)cs, C, k, (int)chunk, L,
-                       sel_chunks_dev, spans_dev, n_spans_dev);
+    hipLaunchKernelGGL(sp_topk_kernel, dim3(1), dim3(kTopkThreads), 0, st, (const float *)cs, C, k,
+                       (const int64_t *)nullptr, (int)chunk, L, sel_chunks_dev, spans_dev, n_spans_dev);
+    SP_HIP_CHECK(hipGetLastError());
+    return SP_OK;
+}
+
+extern "C" sp_status sp_select_budget_workspace(int64_t L, int32_t chunk, size_t *bytes)
+{
+    if (!bytes) return sp::fail(SP_ERR_INVALID_ARG, "bytes is null");
+    if (L < 1 || chunk < 1) return sp::fail(SP_ERR_INVALID_ARG, "L and chunk must be >= 1");
+    const int64_t C = (L + chunk - 1) / chunk;
+    if (C > kMaxBudgetChunks)
+        return sp::fail(SP_ERR_UNSUPPORTED, "%lld chunks (the budget search supports <= %d)", (long long)C, kMaxBudgetChunks);
+    size_t a, b, c;
+    *bytes = budget_ws_layout(C, a, b, c);
+    return SP_OK;
+}
+
+extern "C" sp_status sp_select_budget(const float *scores_dev, int64_t L, int32_t pool_w, int32_t chunk,
+                                      const int64_t *draft_off_dev, const int64_t *target_off_dev, int64_t M,
+                                      int64_t budget, int32_t *sel_chunks_dev, int64_t *spans_dev,
+                                      int32_t *n_spans_dev, int64_t *k_dev, int64_t *n_kept_dev,
+                                      float *chunk_scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
+{
+    if (!scores_dev || !draft_off_dev || !target_off_dev || !sel_chunks_dev || !spans_dev || !n_spans_dev || !k_dev)
+        return sp::fail(SP_ERR_INVALID_ARG, "only n_kept_dev and chunk_scores_dev may be null");
+    if (L < 1 || M < 1) return sp::fail(SP_ERR_INVALID_ARG, "L = %lld and M = %lld must be >= 1", (long long)L, (long long)M);
+    if (chunk < 1) return sp::fail(SP_ERR_INVALID_ARG, "chunk = %d must be >= 1", chunk);
+    if (pool_w < 1 || pool_w % 2 == 0) return sp::fail(SP_ERR_INVALID_ARG, "pool_w = %d must be odd and >= 1", pool_w);
+    if (pool_w > kMaxPool) return sp::fail(SP_ERR_UNSUPPORTED, "pool_w = %d (supported: <= %d)", pool_w, kMaxPool);
+    if (budget < 0) return sp::fail(SP_ERR_INVALID_ARG, "budget = %lld is negative", (long long)budget);
+    if (M >= (int64_t(1) << 31)) return sp::fail(SP_ERR_UNSUPPORTED, "M = %lld (supported: < 2^31)", (long long)M);
+    const int64_t C = (L + chunk - 1) / chunk;
+    if (C > kMaxBudgetChunks)
+        return sp::fail(SP_ERR_UNSUPPORTED, "%lld chunks (the budget search supports <= %d)", (long long)C, kMaxBudgetChunks);
+    size_t off_rank, off_hist, off_k;
+    const size_t need = budget_ws_layout(C, off_rank, off_hist, off_k);
+    if (!ws_dev) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is null (%zu bytes needed)", need);
+    if ((uintptr_t)ws_dev % 256 != 0) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is not 256-byte aligned");
+    if (ws_bytes < need) return sp::fail(SP_ERR_WORKSPACE, "workspace too small: %zu < %zu", ws_bytes, need);
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(ws_dev);
+    float *cs = reinterpret_cast<float *>(ws);
+    int32_t *rank = reinterpret_cast<int32_t *>(ws + off_rank);
+    int32_t *hist = reinterpret_cast<int32_t *>(ws + off_hist);
+    const int waves_per_block = kChunkThreads / 64;
+    hipLaunchKernelGGL(sp_chunk_kernel, dim3((unsigned)((C + waves_per_block - 1) / waves_per_block)),
+                       dim3(kChunkThreads), 0, st, scores_dev, L, (int)pool_w, (int)chunk, C, cs, chunk_scores_dev);
+    SP_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(sp_rank_kernel, dim3((unsigned)((C + kRankThreads - 1) / kRankThreads)), dim3(kRankThreads), 0, st,
+                       (const float *)cs, (int)C, rank, hist);
+    SP_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(sp_token_rank_kernel, dim3((unsigned)((M + kRankThreads - 1) / kRankThreads)), dim3(kRankThreads),
+                       0, st, draft_off_dev, L, (int)chunk, (int)C, target_off_dev, M, (const int32_t *)rank, hist);
+    SP_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(sp_budget_kernel, dim3(1), dim3(kTopkThreads), 0, st, (const int32_t *)hist, (int)C, budget, k_dev,
+                       n_kept_dev);
+    SP_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(sp_topk_kernel, dim3(1), dim3(kTopkThreads), 0, st, (const float *)cs, C, (int64_t)1,
+                       (const int64_t *)k_dev, (int)chunk, L, sel_chunks_dev, spans_dev, n_spans_dev);
     SP_HIP_CHECK(hipGetLastError());
     return SP_OK;
 }

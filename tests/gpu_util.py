@@ -103,6 +103,29 @@ def gpu_select(scores: np.ndarray, pool_w: int, chunk: int, k: int, want_chunk_s
     return sel.cpu().numpy(), spans[:n].cpu().numpy(), (cs.cpu().numpy() if cs is not None else None)
 
 
+def gpu_select_budget(scores: np.ndarray, pool_w: int, chunk: int, draft_off: np.ndarray, target_off: np.ndarray,
+                      budget: int):
+    """Returns (k, n_kept, sel int32[k], spans int64[n][2], chunk_scores float32[C])."""
+    L, M = scores.size, target_off.size - 1
+    C = (L + chunk - 1) // chunk
+    sd = torch.from_numpy(np.ascontiguousarray(scores, dtype=np.float32)).to(DEV)
+    dd = torch.from_numpy(np.ascontiguousarray(draft_off, dtype=np.int64)).to(DEV)
+    td = torch.from_numpy(np.ascontiguousarray(target_off, dtype=np.int64)).to(DEV)
+    sel = torch.full((C,), -1, dtype=torch.int32, device=DEV)
+    spans = torch.full((C, 2), -1, dtype=torch.int64, device=DEV)
+    n_spans = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    k_out = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    n_kept = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    cs = torch.full((C,), float("nan"), dtype=torch.float32, device=DEV)
+    ws = workspace(sp.sp_select_budget_workspace(L, chunk))
+    sp.sp_select_budget(sd, L, pool_w, chunk, dd, td, M, int(budget), sel, spans, n_spans, k_out, n_kept, cs, ws)
+    torch.cuda.synchronize()
+    k, n = int(k_out.item()), int(n_spans.item())
+    assert 1 <= k <= C and 1 <= n <= k
+    assert (sel[k:] == -1).all() and (spans[n:] == -1).all()      # nothing written beyond the k chosen
+    return k, int(n_kept.item()), sel[:k].cpu().numpy(), spans[:n].cpu().numpy(), cs.cpu().numpy()
+
+
 def gpu_project(draft_off: np.ndarray, target_off: np.ndarray, spans: np.ndarray, want_mask: bool = True,
                 max_spans: Optional[int] = None):
     """Returns (tspans int64[n][2], mask uint8[M] or None, n_kept)."""

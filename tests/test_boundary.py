@@ -189,3 +189,24 @@ def test_assemble_argument_errors():
         with pytest.raises(sp.SpError) as e:
             call(**kw)
         assert e.value.status == status, kw
+
+
+def test_select_budget_argument_errors():
+    fake = 0x1000
+    n = sp.sp_select_budget_workspace(4096, 32)
+    assert n % 256 == 0 and n >= 128 * 4 * 3
+    with pytest.raises(sp.SpError) as e:                   # more chunks than the rank kernel is sized for
+        sp.sp_select_budget_workspace(1 << 22, 32)
+    assert e.value.status == 2
+
+    def call(sc=fake, L=4096, w=13, c=32, do=fake, to=fake, M=5000, budget=1024, sel=fake, spans=fake, ns=fake,
+             k=fake, ws=fake, wsb=n):
+        sp.sp_select_budget(sc, L, w, c, do, to, M, budget, sel, spans, ns, k, None, None, ws, wsb, stream=0)
+
+    for kw, status in [(dict(sc=None), 1), (dict(do=None), 1), (dict(to=None), 1), (dict(sel=None), 1),
+                       (dict(spans=None), 1), (dict(ns=None), 1), (dict(k=None), 1), (dict(L=0), 1), (dict(M=0), 1),
+                       (dict(c=0), 1), (dict(w=4), 1), (dict(w=131), 2), (dict(budget=-1), 1), (dict(M=1 << 31), 2),
+                       (dict(L=1 << 22), 2), (dict(ws=None, wsb=0), 3), (dict(wsb=256), 3), (dict(ws=fake + 8), 3)]:
+        with pytest.raises(sp.SpError) as e:
+            call(**kw)
+        assert e.value.status == status, kw
