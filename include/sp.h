@@ -121,6 +121,27 @@ sp_status sp_score_look(const sp_score_desc *desc, const void *q_dev,
                         float *scores_dev, void *ws_dev, size_t ws_bytes,
                         void *hip_stream);
 
+/*
+ * sp_score over a paged key cache (Section 3.1 describes KV caches kept in
+ * fixed-size blocks of 4k tokens). Token j of layer l lives in page
+ * block_table_dev[j / page_tokens] of that layer's pool k_pools_host[l]:
+ *   K[l, kv, j, e] = pool_l[ page * page_stride + kv * k_stride_head
+ *                            + (j % page_tokens) * k_stride_token + e ]
+ * with desc's strides now describing one page (e.g. head-major pages:
+ * k_stride_token = head_dim, k_stride_head = page_tokens * head_dim,
+ * page_stride = n_kv_heads * page_tokens * head_dim). One block table serves all
+ * layers, as in paged decoders. block_table_dev: device, int32,
+ * ceil(L / page_tokens) entries, only read. page_tokens: a positive multiple of
+ * 512; page_stride: elements, a multiple of 8; every page is allocated whole
+ * (rows of the last page beyond L may be read, their contents are ignored).
+ * Same result as sp_score on the gathered keys, same kernels, same workspace.
+ */
+sp_status sp_score_paged(const sp_score_desc *desc, const void *q_dev,
+                         const void *const *k_pools_host,
+                         const int32_t *block_table_dev, int64_t page_tokens,
+                         int64_t page_stride, int64_t L, float *scores_dev,
+                         void *ws_dev, size_t ws_bytes, void *hip_stream);
+
 /* Which implementation sp_score picks for this shape and length on the current
  * device: 1 = the single-launch kernel that keeps K on chip and reads it from
  * HBM once (long prompts of head_dim 64 whose query group fits 64 padded rows),

@@ -166,6 +166,19 @@ def score_look(q: np.ndarray, k_layers: Sequence[np.ndarray], k_look: np.ndarray
     return out
 
 
+def gather_pages(pool_l: np.ndarray, block_table: np.ndarray, L: int, layout: str = "HND") -> np.ndarray:
+    """Contiguous keys of one layer from a paged cache (Section 3.1: KV caches kept in fixed-size
+    blocks): token j is row j % P of page block_table[j // P]. pool_l: [pages][Hkv][P][d] ("HND") or
+    [pages][P][Hkv][d] ("NHD"); returns [Hkv][L][d] or [L][Hkv][d]. Paging is addressing only: the
+    paged score is the plain score of the gathered keys."""
+    P = pool_l.shape[2] if layout == "HND" else pool_l.shape[1]
+    j = np.arange(L)
+    page, row = np.asarray(block_table)[j // P], j % P
+    if layout == "HND":
+        return np.ascontiguousarray(pool_l[page, :, row, :].transpose(1, 0, 2))
+    return np.ascontiguousarray(pool_l[page, row, :, :])
+
+
 def pool(I: np.ndarray, w: int) -> np.ndarray:
     I = np.ascontiguousarray(I, dtype=np.float64)
     out = np.empty_like(I)

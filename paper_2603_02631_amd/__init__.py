@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     sp_score,
     sp_score_batch,
     sp_score_look,
+    sp_score_paged,
     sp_score_is_fused,
     sp_score_workspace,
     sp_select,

@@ -20,7 +20,7 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG_DIR, "libsp_amd.so")
 
 EXPORTS = (
-    "sp_score_workspace", "sp_score", "sp_score_look", "sp_score_is_fused", "sp_score_batch", "sp_keep_count", "sp_select_workspace",
+    "sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_is_fused", "sp_score_batch", "sp_keep_count", "sp_select_workspace",
     "sp_select", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble", "sp_last_error", "sp_version",
 )
 
@@ -70,6 +70,7 @@ def load_library():
     lib.sp_score_workspace.argtypes = [D, c.c_int64, c.c_int32, c.POINTER(c.c_size_t)]
     lib.sp_score.argtypes = [D, P, c.POINTER(P), c.c_int64, P, P, c.c_size_t, P]
     lib.sp_score_look.argtypes = [D, P, c.POINTER(P), c.c_int64, P, c.c_int32, P, P, c.c_size_t, P]
+    lib.sp_score_paged.argtypes = [D, P, c.POINTER(P), P, c.c_int64, c.c_int64, c.c_int64, P, P, c.c_size_t, P]
     lib.sp_score_batch.argtypes = [D, P, c.POINTER(P), c.POINTER(c.c_int64), P, c.c_int32, P, P, c.c_size_t, P]
     lib.sp_score_is_fused.argtypes = [D, c.c_int64]
     lib.sp_score_is_fused.restype = c.c_int32
@@ -85,7 +86,7 @@ def load_library():
     lib.sp_assemble.argtypes = [P, c.c_int64, P, P, c.c_int32, P, c.c_int32, c.c_int64, P, P, P, P, P, c.c_size_t, P]
     lib.sp_last_error.restype = c.c_char_p
     lib.sp_version.restype = c.c_char_p
-    for name in ("sp_score_workspace", "sp_score", "sp_score_look", "sp_score_is_fused", "sp_score_batch", "sp_select_workspace", "sp_select",
+    for name in ("sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_is_fused", "sp_score_batch", "sp_select_workspace", "sp_select",
                  "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
@@ -157,6 +158,16 @@ def sp_score_look(desc: ScoreDesc, q, k_layers: Sequence, L: int, k_look, look_s
     nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
     _check(load_library().sp_score_look(ctypes.byref(desc), _ptr(q), _layer_array(k_layers), L, _ptr(k_look),
                                         int(look_self), _ptr(scores), _ptr(ws), nbytes, _stream(stream)))
+
+
+def sp_score_paged(desc: ScoreDesc, q, k_pools: Sequence, block_table, page_tokens: int, page_stride: int, L: int,
+                   scores, ws, ws_bytes: Optional[int] = None, stream=None) -> None:
+    if len(k_pools) != desc.n_layers:
+        raise SpError(1, f"k_pools has {len(k_pools)} entries, desc.n_layers is {desc.n_layers}")
+    nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
+    _check(load_library().sp_score_paged(ctypes.byref(desc), _ptr(q), _layer_array(k_pools), _ptr(block_table),
+                                         int(page_tokens), int(page_stride), L, _ptr(scores), _ptr(ws), nbytes,
+                                         _stream(stream)))
 
 
 def sp_score_batch(desc: ScoreDesc, q, k_layers: Sequence, offsets_host: Sequence[int], offsets_dev, scores, ws,

@@ -58,6 +58,9 @@ struct ScoreArgs {
     float2 *part;             // [n_phases][n_tiles][rows_pad]
     float *lse_neg;           // [B][n_phases][rows_pad]  (-lse in raw-logit units, permuted)
     float *scores;
+    const int32_t *block_table;   // paged keys (single prompt): token j lives in page block_table[j / page_tokens]
+    int64_t page_tokens;          // of its layer's pool, page p at element offset p * page_stride; null: contiguous
+    int64_t page_stride;
     const float *look;        // [n_phases][rows_pad] lookahead-key term of each row's normaliser, or null
     float *split_buf;         // layer-split results: MEAN [n_splits][n_tiles][TILE],
                               //                      MAX  [n_splits][8*n_nblk][n_tiles][TILE]
@@ -80,6 +83,20 @@ __device__ __forceinline__ TileInfo get_tile(const ScoreArgs &a, int tile, int t
     t.prompt = 0;
     t.first_tile = 0;
     return t;
+}
+
+// Address of key 0 of the tile's address space in (layer, kv head): the layer's buffer for contiguous
+// keys; for paged keys the tile's page, moved back by the page's first token so that the absolute key
+// index still applies (tiles never straddle pages: a page holds a multiple of the tile size).
+__device__ __forceinline__ const uint16_t *key_base(const ScoreArgs &a, const LayerPtrs &kp, int layer, int kv,
+                                                    const TileInfo &ti)
+{
+    const uint16_t *b = kp.p[layer] + (int64_t)kv * a.k_stride_head;
+    if (a.block_table) {
+        const int64_t page = ti.j0 / a.page_tokens;
+        b += (int64_t)a.block_table[page] * a.page_stride - page * a.page_tokens * a.k_stride_token;
+    }
+    return b;
 }
 
 // Padded query-row order of one kv head's group: row = blk*32 + rho with
@@ -153,7 +170,7 @@ __global__ __launch_bounds__(kThreads, 4) void sp_stats_kernel(ScoreArgs a, Laye
     const TileInfo ti = get_tile(a, tile, TILE);
 
     stage_q<D>(qs, a, ti.prompt, layer, kv, tid);
-    stage_k<D, NS>(ks, kp.p[layer] + (int64_t)kv * a.k_stride_head, a.k_stride_token, ti.j0, ti.end, tid);
+    stage_k<D, NS>(ks, key_base(a, kp, layer, kv, ti), a.k_stride_token, ti.j0, ti.end, tid);
     __syncthreads();
 
     bf16x8 kf[NS][KS];
@@ -333,7 +350,7 @@ __global__ __launch_bounds__(kThreads, 3) void sp_prob_kernel(ScoreArgs a, Layer
             const int phase = layer * a.n_kv_heads + kv;
             __syncthreads();
             stage_q<D>(qs, a, ti.prompt, layer, kv, tid);
-            stage_k<D, NS>(ks, kp.p[layer] + (int64_t)kv * a.k_stride_head, a.k_stride_token, ti.j0, ti.end, tid);
+            stage_k<D, NS>(ks, key_base(a, kp, layer, kv, ti), a.k_stride_token, ti.j0, ti.end, tid);
             for (int i = tid; i < a.rows_pad; i += kThreads)
                 ci[i] = a.lse_neg[((int64_t)ti.prompt * n_phases + phase) * a.rows_pad + i];
             __syncthreads();
@@ -609,10 +626,17 @@ sp_status launch_all(const Plan &p, const ScoreArgs &a, const LayerPtrs &kp, hip
     return SP_OK;
 }
 
+// What the variants of sp_score add to the plain call.
+struct ScoreOptions {
+    const void *k_look = nullptr;            // lookahead keys in the normaliser
+    int32_t look_self = 0;
+    const int32_t *block_table = nullptr;    // paged keys
+    int64_t page_tokens = 0, page_stride = 0;
+};
+
 sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
                      const int64_t *offsets_host, const int64_t *offsets_dev, int32_t B, int64_t L_single,
-                     const void *k_look_dev, int32_t look_self, float *scores_dev, void *ws_dev, size_t ws_bytes,
-                     void *hip_stream)
+                     const ScoreOptions &opt, float *scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
 {
     Plan p;
     sp_status rc = make_plan(desc, p);
@@ -628,7 +652,17 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
         kp.p[l] = static_cast<const uint16_t *>(k_layers_host[l]);
     }
     if ((uintptr_t)q_dev % 16 != 0) return sp::fail(SP_ERR_INVALID_ARG, "q_dev is not 16-byte aligned");
-    if (look_self != 0 && look_self != 1) return sp::fail(SP_ERR_INVALID_ARG, "look_self = %d must be 0 or 1", look_self);
+    if (opt.look_self != 0 && opt.look_self != 1)
+        return sp::fail(SP_ERR_INVALID_ARG, "look_self = %d must be 0 or 1", opt.look_self);
+    if (opt.block_table) {
+        // a page holds whole tiles of either score path, and its rows are addressed with the desc's strides
+        if (opt.page_tokens < sp_fused::kTileKeys || opt.page_tokens % sp_fused::kTileKeys != 0)
+            return sp::fail(SP_ERR_INVALID_ARG, "page_tokens = %lld must be a positive multiple of %d",
+                            (long long)opt.page_tokens, sp_fused::kTileKeys);
+        if (opt.page_stride < 0 || opt.page_stride % 8 != 0)
+            return sp::fail(SP_ERR_INVALID_ARG, "page_stride = %lld must be a non-negative multiple of 8 elements",
+                            (long long)opt.page_stride);
+    }
 
     int64_t total = 0, n_tiles = 0;
     const bool batch = offsets_host != nullptr;
@@ -685,10 +719,13 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
     a.inv_c = 1.0f / a.c;
     a.out_scale = (desc->layer_agg == SP_LAYER_MAX) ? 1.0f / (float)desc->n_q
                                                    : 1.0f / ((float)desc->n_q * (float)desc->n_layers);
-    if (k_look_dev) {
+    a.block_table = opt.block_table;
+    a.page_tokens = opt.page_tokens;
+    a.page_stride = opt.page_stride;
+    if (opt.k_look) {
         float *look = reinterpret_cast<float *>(ws + w.look);
         hipLaunchKernelGGL(sp_look_kernel, dim3(p.n_phases), dim3(kThreads), 0, st, a,
-                           static_cast<const uint16_t *>(k_look_dev), (int)look_self, p.D, look);
+                           static_cast<const uint16_t *>(opt.k_look), (int)opt.look_self, p.D, look);
         SP_HIP_CHECK(hipGetLastError());
         a.look = look;
     }
@@ -702,6 +739,9 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
             f.k_stride_head = a.k_stride_head;
             f.L = total;
             f.look = a.look;
+            f.block_table = a.block_table;
+            f.page_tokens = a.page_tokens;
+            f.page_stride = a.page_stride;
             f.scores = scores_dev;
             f.n_wg = n_wg;
             f.n_layers = a.n_layers; f.n_q_heads = a.n_q_heads; f.n_kv_heads = a.n_kv_heads;
@@ -751,7 +791,7 @@ extern "C" int32_t sp_score_is_fused(const sp_score_desc *desc, int64_t L)
 extern "C" sp_status sp_score(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
                               int64_t L, float *scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
 {
-    return score_impl(desc, q_dev, k_layers_host, nullptr, nullptr, 1, L, nullptr, 0, scores_dev, ws_dev, ws_bytes,
+    return score_impl(desc, q_dev, k_layers_host, nullptr, nullptr, 1, L, ScoreOptions(), scores_dev, ws_dev, ws_bytes,
                       hip_stream);
 }
 
@@ -761,8 +801,22 @@ extern "C" sp_status sp_score_look(const sp_score_desc *desc, const void *q_dev,
 {
     if (!k_look_dev) return sp::fail(SP_ERR_INVALID_ARG, "k_look_dev is null");
     if ((uintptr_t)k_look_dev % 16 != 0) return sp::fail(SP_ERR_INVALID_ARG, "k_look_dev is not 16-byte aligned");
-    return score_impl(desc, q_dev, k_layers_host, nullptr, nullptr, 1, L, k_look_dev, look_self, scores_dev, ws_dev,
-                      ws_bytes, hip_stream);
+    ScoreOptions opt;
+    opt.k_look = k_look_dev;
+    opt.look_self = look_self;
+    return score_impl(desc, q_dev, k_layers_host, nullptr, nullptr, 1, L, opt, scores_dev, ws_dev, ws_bytes, hip_stream);
+}
+
+extern "C" sp_status sp_score_paged(const sp_score_desc *desc, const void *q_dev, const void *const *k_pools_host,
+                                    const int32_t *block_table_dev, int64_t page_tokens, int64_t page_stride, int64_t L,
+                                    float *scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
+{
+    if (!block_table_dev) return sp::fail(SP_ERR_INVALID_ARG, "block_table_dev is null");
+    ScoreOptions opt;
+    opt.block_table = block_table_dev;
+    opt.page_tokens = page_tokens;
+    opt.page_stride = page_stride;
+    return score_impl(desc, q_dev, k_pools_host, nullptr, nullptr, 1, L, opt, scores_dev, ws_dev, ws_bytes, hip_stream);
 }
 
 extern "C" sp_status sp_score_batch(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
@@ -770,6 +824,6 @@ extern "C" sp_status sp_score_batch(const sp_score_desc *desc, const void *q_dev
                                     float *scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
 {
     if (!offsets_host) return sp::fail(SP_ERR_INVALID_ARG, "offsets_host is null");
-    return score_impl(desc, q_dev, k_layers_host, offsets_host, offsets_dev, B, 0, nullptr, 0, scores_dev, ws_dev,
+    return score_impl(desc, q_dev, k_layers_host, offsets_host, offsets_dev, B, 0, ScoreOptions(), scores_dev, ws_dev,
                       ws_bytes, hip_stream);
 }

@@ -432,10 +432,11 @@ __device__ __forceinline__ f32x16 logits32(const bf16x8 (&kf)[kKS], const bf16x8
     return d;
 }
 
-// Folds the 16 logits of a lane into its running (max, sum exp); keys below lo are not this workgroup's.
-__device__ __forceinline__ void fold_logits(const f32x16 &d, float &m, float &l, float c, int lo, int hf)
+// Folds the 16 logits of a lane into its running (max, sum exp); only keys lo <= key < hi of the
+// sub-tile are this workgroup's (all 32 except in the prompt's last tile).
+__device__ __forceinline__ void fold_logits(const f32x16 &d, float &m, float &l, float c, int lo, int hi, int hf)
 {
-    if (lo <= 0) {
+    if (lo <= 0 && hi >= 32) {
         float mn = max3(m, d[0], d[1]);      // running maximum including these 16 logits
 #pragma unroll
         for (int r = 2; r < 16; r += 2) mn = max3(mn, d[r], d[r + 1]);
@@ -446,12 +447,12 @@ __device__ __forceinline__ void fold_logits(const f32x16 &d, float &m, float &l,
 #pragma unroll
         for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(d[r], c, -mc));
         l += sum;
-    } else if (lo < 32) {
+    } else if (lo < 32 && hi > 0) {
         float tm = neg_inf();
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
-            if (key >= lo) tm = fmaxf(tm, d[r]);
+            if (key >= lo && key < hi) tm = fmaxf(tm, d[r]);
         }
         if (tm > neg_inf()) {
             const float mn = fmaxf(m, tm);
@@ -461,7 +462,7 @@ __device__ __forceinline__ void fold_logits(const f32x16 &d, float &m, float &l,
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
-                if (key >= lo) l += fast_exp2(fmaf(d[r], c, -mc));
+                if (key >= lo && key < hi) l += fast_exp2(fmaf(d[r], c, -mc));
             }
         }
     }
@@ -484,19 +485,20 @@ constexpr int kLoadsBehindLse = kSubInstr - kSubInstr / (NBLK * kNS);
 
 template <int NBLK, int PAR>
 __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t koff0,
-                                           uint32_t koff1, uint32_t wstats_ad, int r_lo, int wave, int lane,
+                                           uint32_t koff1, uint32_t wstats_ad, int r_range, int wave, int lane,
                                            const KIssue &ki, const uint32_t (&voff)[2], const uint64_t *lse_row,
                                            const float *look_row, int rows_pad, uint32_t xlse_ad)
 {
     constexpr int kPerStep = kSubInstr / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
     const int hf = lane >> 5;
-    const int lo0 = r_lo - wave * kNS * 32, lo1 = lo0 - 32;
+    const int lo0 = (r_range & 0xffff) - wave * kNS * 32, lo1 = lo0 - 32;      // r_range = r_lo | r_hi << 16
+    const int hi0 = (r_range >> 16) - wave * kNS * 32, hi1 = hi0 - 32;
     bf16x8 qf[kKS];
     lift_k_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, qf);
     f32x16 da = logits32(kf[0], qf);
     f32x16 db = logits32(kf[1], qf);
     float m = neg_inf(), l = 0.f;
-    fold_logits(da, m, l, c, lo0, hf);
+    fold_logits(da, m, l, c, lo0, hi0, hf);
     k_issue<kPerStep>(ki, voff, 0);
     if (lse_row != nullptr) stage_exchange_rows(xlse_ad, lse_row, look_row, rows_pad, lane);
     __builtin_amdgcn_sched_barrier(0);
@@ -504,17 +506,17 @@ __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], cons
         lift_at<kOffQ1 + PAR * kQTileBytes + 4096>(lc, qf);
         da = logits32(kf[0], qf);
     }
-    fold_logits(db, m, l, c, lo1, hf);
+    fold_logits(db, m, l, c, lo1, hi1, hf);
     store_row_stats(wstats_ad, m, l, c, hf);
     k_issue<kPerStep>(ki, voff, kPerStep);
     __builtin_amdgcn_sched_barrier(0);
     if (NBLK == 2) {
         db = logits32(kf[1], qf);
         m = neg_inf(); l = 0.f;
-        fold_logits(da, m, l, c, lo0, hf);
+        fold_logits(da, m, l, c, lo0, hi0, hf);
         k_issue<kPerStep>(ki, voff, 2 * kPerStep);
         __builtin_amdgcn_sched_barrier(0);
-        fold_logits(db, m, l, c, lo1, hf);
+        fold_logits(db, m, l, c, lo1, hi1, hf);
         store_row_stats(wstats_ad + 256, m, l, c, hf);
         k_issue<kPerStep>(ki, voff, 3 * kPerStep);
         __builtin_amdgcn_sched_barrier(0);
@@ -628,7 +630,7 @@ struct Walk {
 template <int NB, int GB, int SLOT, int PAR>
 __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, int s, int n_phases, Ring &ring,
                                      Acc<NB> &acc, const LaneConst &lc, Walk &wk, unsigned char *lds, uint32_t lds0,
-                                     uint64_t wave_off, int r_lo)
+                                     uint64_t wave_off, int r_range)
 {
     // Other lane-derived values are recomputed every step instead of being kept in registers across
     // the whole loop (the opaque copy stops the compiler from hoisting them).
@@ -732,7 +734,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
         if (do_stats) {
             const uint32_t wstats_ad = lds0 + kOffWstats + PAR * kWstatsBytes + wave * (kMaxRowsF * 8) + ((uint32_t)(lane & 31) << 3);
             stats_pass<NB * GB, PAR>(a.c, ring.kf[SLOT], lc, sub_slot_off(wave, wk.slot0, 0),
-                                     sub_slot_off(wave, wk.slot0, 1), wstats_ad, r_lo, wave, lane, ki, voff, lse_row,
+                                     sub_slot_off(wave, wk.slot0, 1), wstats_ad, r_range, wave, lane, ki, voff, lse_row,
                                      look_row, a.rows_pad, lds0 + kOffXlse);
         } else {
             if (lse_row != nullptr) stage_exchange_rows(lds0 + kOffXlse, lse_row, look_row, a.rows_pad, lane);
@@ -847,10 +849,15 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hf = lane >> 5, col = lane & 31;
     const int w = blockIdx.x;
     const int n_phases = a.n_layers * a.n_kv_heads;
-    // The last workgroup's tile is shifted back so that it ends with the prompt (the caller guarantees
-    // L >= 512): every workgroup loads 512 real keys; rows below r_lo belong to the previous workgroup.
-    const int64_t j0 = ((int64_t)(w + 1) * kFTile <= a.L) ? (int64_t)w * kFTile : a.L - kFTile;
+    // Contiguous keys: the last workgroup's tile is shifted back so that it ends with the prompt (the
+    // caller guarantees L >= 512): every workgroup loads 512 real keys; rows below r_lo belong to the
+    // previous workgroup. Paged keys: pages are allocated whole and hold a multiple of 512 keys, so the
+    // last tile stays where it is and rows from r_hi on (allocated, never written) are ignored.
+    const bool paged = a.block_table != nullptr;
+    const int64_t j0 = (paged || (int64_t)(w + 1) * kFTile <= a.L) ? (int64_t)w * kFTile : a.L - kFTile;
     const int r_lo = (int)((int64_t)w * kFTile - j0);
+    const int r_hi = (int)(a.L - j0 < kFTile ? a.L - j0 : kFTile);
+    const int r_range = r_lo | (r_hi << 16);
     const uint32_t lds0 = lds_addr(lds);
     const uint32_t stride_bytes = (uint32_t)a.k_stride_token * 2u;
 
@@ -894,6 +901,11 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     // byte offset of this wave's first key within a (layer, kv head): uniform, kept in scalar registers
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     uint64_t wave_off = (uint64_t)(j0 + wave_u * 64) * (uint64_t)a.k_stride_token * 2u;
+    if (paged) {
+        const int64_t page = j0 / a.page_tokens;
+        wave_off = ((uint64_t)a.block_table[page] * (uint64_t)a.page_stride +
+                    (uint64_t)(j0 - page * a.page_tokens + wave_u * 64) * (uint64_t)a.k_stride_token) * 2u;
+    }
     wave_off = (uint64_t)uniform32((uint32_t)wave_off) | ((uint64_t)uniform32((uint32_t)(wave_off >> 32)) << 32);
 
     // prologue: this wave's slice of Q(0) and both sub-tiles of K(0); everything lands before step 0
@@ -921,10 +933,10 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     // instruction stream uniform. The last probability pass (phase n_phases - 1) runs in step n_phases + 3.
     const int n_steps = (n_phases + kLag + 1 + 3) / 4 * 4;
     for (int s0 = 0; s0 < n_steps; s0 += 4) {
-        step<NB, GB, 0, 0>(a, kp, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_lo);
-        step<NB, GB, 1, 1>(a, kp, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_lo);
-        step<NB, GB, 2, 0>(a, kp, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_lo);
-        step<NB, GB, 3, 1>(a, kp, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_lo);
+        step<NB, GB, 0, 0>(a, kp, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 1, 1>(a, kp, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 2, 0>(a, kp, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 3, 1>(a, kp, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
     }
     vm_wait<0>();               // no direct-to-LDS load may outlive the workgroup
     lds_barrier();
@@ -934,7 +946,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     for (int s = 0; s < kNS; ++s) {
         const float both = acc.total[s] + __shfl_xor(acc.total[s], 32);
         const int key = (wave * kNS + s) * 32 + col;
-        if (hf == 0 && key >= r_lo) a.scores[j0 + key] = failed ? __uint_as_float(0x7fc00000u) : both * a.out_scale;   // quiet NaN marks a failed call
+        if (hf == 0 && key >= r_lo && key < r_hi) a.scores[j0 + key] = failed ? __uint_as_float(0x7fc00000u) : both * a.out_scale;   // quiet NaN marks a failed call
     }
 }
 

@@ -20,6 +20,9 @@ struct FusedArgs {
     uint32_t *err;
     const float *look;           // [n_phases][rows_pad] log-sum-exp of each row over its visible lookahead keys
                                  // (raw-logit units, -inf for none), or null: prompt keys only
+    const int32_t *block_table;  // paged keys: token j of a layer sits in page block_table[j / page_tokens] of that
+    int64_t page_tokens;         // layer's pool, page p at element offset p * page_stride; null: contiguous keys
+    int64_t page_stride;
     const uint64_t *zeros;       // 128 zero bytes (source of padding query rows)
     float *scores;
     int32_t n_wg;

@@ -70,6 +70,43 @@ def gpu_score_look(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], k_look: n
     return scores[:L].cpu().numpy()
 
 
+def make_paged(k_layers: Sequence[np.ndarray], page_tokens: int, layout: str, seed: int, spare_pages: int = 3):
+    """Scatters contiguous head-major keys ([Hkv][L][d] per layer) into per-layer page pools in a random
+    page order. Rows that hold no token (the tail of the last page, spare pages) are bf16 NaN: a kernel
+    that lets them into a result is caught. Returns (pools list of uint16 arrays, block_table int32)."""
+    Hkv, L, d = k_layers[0].shape
+    n_pages = (L + page_tokens - 1) // page_tokens
+    rng = np.random.default_rng(seed)
+    table = rng.permutation(n_pages + spare_pages)[:n_pages].astype(np.int32)
+    pools = []
+    for k in k_layers:
+        shape = (n_pages + spare_pages, Hkv, page_tokens, d) if layout == "HND" else (n_pages + spare_pages, page_tokens, Hkv, d)
+        pool = np.full(shape, 0x7FC0, dtype=np.uint16)
+        for p in range(n_pages):
+            rows = k[:, p * page_tokens:(p + 1) * page_tokens, :]
+            if layout == "HND":
+                pool[table[p], :, :rows.shape[1], :] = rows
+            else:
+                pool[table[p], :rows.shape[1], :, :] = rows.transpose(1, 0, 2)
+        pools.append(pool)
+    return pools, table
+
+
+def gpu_score_paged(q_bits: np.ndarray, pools: Sequence[np.ndarray], table: np.ndarray, page_tokens: int, L: int,
+                    scale: float, layer_agg: int = 0, layout: str = "HND") -> np.ndarray:
+    Lyr, H, n_q, d = q_bits.shape
+    Hkv = pools[0].shape[1] if layout == "HND" else pools[0].shape[2]
+    desc = make_desc(Lyr, H, Hkv, d, n_q, scale, layer_agg, layout, page_tokens)     # strides of one page
+    qd = dev_bits(q_bits)
+    pd = [dev_bits(p) for p in pools]
+    td = torch.from_numpy(np.ascontiguousarray(table, dtype=np.int32)).to(DEV)
+    ws = workspace(sp.sp_score_workspace(desc, L, 1))
+    scores = torch.full((max(L, 1),), float("nan"), dtype=torch.float32, device=DEV)
+    sp.sp_score_paged(desc, qd, pd, td, page_tokens, Hkv * page_tokens * d, L, scores, ws)
+    torch.cuda.synchronize()
+    return scores[:L].cpu().numpy()
+
+
 def gpu_score_batch(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], offsets: np.ndarray, scale: float,
                     layer_agg: int = 0, layout: str = "HND") -> np.ndarray:
     """q_bits: uint16 [B][Lyr][H][n_q][d]; k_layers packed along tokens."""

@@ -115,6 +115,18 @@ def test_score_workspace_and_argument_errors():
         sp.sp_score_look(d, fake, layers, 1024, fake, 2, fake, fake, n, stream=0)
     assert e.value.status == 1
     sp.sp_score_look(d, fake, layers, 0, fake, 1, fake, None, 0, stream=0)   # empty prompt: no-op
+    stride = 2 * 4096 * 64
+    with pytest.raises(sp.SpError) as e:        # paged variant: null block table
+        sp.sp_score_paged(d, fake, layers, None, 4096, stride, 1024, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    for bad_page in (0, 256, 4096 + 8):          # pages hold a positive multiple of 512 tokens
+        with pytest.raises(sp.SpError) as e:
+            sp.sp_score_paged(d, fake, layers, fake, bad_page, stride, 1024, fake, fake, n, stream=0)
+        assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:        # page stride not a multiple of 8 elements
+        sp.sp_score_paged(d, fake, layers, fake, 4096, stride + 4, 1024, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    sp.sp_score_paged(d, fake, layers, fake, 4096, stride, 0, fake, None, 0, stream=0)   # empty prompt: no-op
 
 
 def test_score_batch_argument_errors():

@@ -222,3 +222,40 @@ def test_score_with_lookahead_keys_matches_oracle(shape):
     assert np.max(np.abs(oracle.score_look(q, inp["k"], kl, 1, w.scale, 0) - plain) / plain) > 5e-3
     # and a call without lookahead keys afterwards is the plain result again (no state left behind)
     assert_scores_close(gpu_score(q, inp["k"], w.scale, 0), plain)
+
+
+PAGED_SHAPES = [
+    # name, Lyr, H, Hkv, d, n_q, L, page_tokens, layout
+    ("paged_general_d64", 3, 8, 2, 64, 16, 1500, 512, "HND"),
+    ("paged_general_d128_nhd", 2, 4, 2, 128, 8, 777, 512, "NHD"),
+    ("paged_general_one_page", 2, 4, 2, 64, 8, 300, 1024, "HND"),
+    ("paged_fused_4k_ragged_tail", 3, 8, 2, 64, 16, 33000 + 77, 4096, "HND"),
+    ("paged_fused_4k_whole_pages", 2, 8, 2, 64, 8, 8 * 4096, 4096, "HND"),
+    ("paged_fused_512_nhd", 2, 6, 2, 64, 5, 35000, 512, "NHD"),
+]
+
+
+@pytest.mark.parametrize("shape", PAGED_SHAPES, ids=[s[0] for s in PAGED_SHAPES])
+def test_score_over_paged_keys_matches_oracle(shape):
+    """sp_score_paged: the keys sit in shuffled pages of per-layer pools (Section 3.1: KV caches in
+    fixed-size blocks); rows that hold no token are NaN. Oracle: the plain score of the keys gathered
+    through the block table."""
+    import paper_2603_02631_amd as sp
+    from gpu_util import assert_scores_close, gpu_score_paged, make_desc, make_paged
+    name, Lyr, H, Hkv, d, n_q, L, P, layout = shape
+    say(f"[score-paged] {name} Lyr={Lyr} H={H} Hkv={Hkv} d={d} n_q={n_q} L={L} page={P} {layout}")
+    w = small_workload(name, Lyr, H, Hkv, d, n_q, L, cfg_id=400 + PAGED_SHAPES.index(shape), hh=(1, 1000))
+    fused = sp.sp_score_is_fused(make_desc(Lyr, H, Hkv, d, n_q, w.scale, 0, layout, P), L)
+    assert fused == (1 if "fused" in name else 0)
+    inp = synth.make_score_inputs(w)
+    q = inp["q"][0]
+    pools, table = make_paged(inp["k"], P, layout, seed=w.cfg_id)
+    gathered = [oracle.gather_pages(pool, table, L, layout) for pool in pools]
+    for l in range(Lyr):                      # the scatter of the test and the oracle's gather are inverse
+        ref = inp["k"][l] if layout == "HND" else inp["k"][l].transpose(1, 0, 2)
+        np.testing.assert_array_equal(gathered[l], ref)
+    for mode in (0, 1):
+        want = oracle.score(q, gathered, w.scale, mode, layout=layout)
+        got = gpu_score_paged(q, pools, table, P, L, w.scale, mode, layout)
+        assert_scores_close(got, want)
+        say(f"  mode {mode}: max rel err {np.max(np.abs(got - want) / want):.2e}")

@@ -268,6 +268,24 @@ def test_scale_is_applied_inside_the_exponent():
 
 
 
+def test_gather_pages_against_explicit_loops():
+    """Paged keys (Section 3.1, KV blocks): token j is row j % P of page table[j // P]. The gather is
+    checked element by element with plain loops, in both page layouts, with a ragged last page."""
+    rng = np.random.default_rng(35)
+    Hkv, P, d, L = 2, 4, 3, 10
+    pool_hnd = rng.integers(0, 60000, size=(5, Hkv, P, d)).astype(np.uint16)
+    table = np.array([3, 0, 4])
+    got = oracle.gather_pages(pool_hnd, table, L, "HND")
+    assert got.shape == (Hkv, L, d)
+    for kv in range(Hkv):
+        for j in range(L):
+            for e in range(d):
+                assert got[kv, j, e] == pool_hnd[table[j // P], kv, j % P, e]
+    pool_nhd = np.ascontiguousarray(pool_hnd.transpose(0, 2, 1, 3))
+    got2 = oracle.gather_pages(pool_nhd, table, L, "NHD")
+    np.testing.assert_array_equal(got2, got.transpose(1, 0, 2))
+
+
 # --------------------------------------------------------------------------
 # lookahead keys in the normaliser  (Algorithm 1, ForwardWithAttn with lookahead = i)
 # --------------------------------------------------------------------------
