@@ -485,14 +485,13 @@ constexpr int kLoadsBehindLse = kSubInstr - kSubInstr / (NBLK * kNS);
 
 template <int NBLK, int PAR>
 __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t koff0,
-                                           uint32_t koff1, uint32_t wstats_ad, int r_range, int wave, int lane,
+                                           uint32_t koff1, uint32_t wstats_ad, int lo0, int hi0, int lane,
                                            const KIssue &ki, const uint32_t (&voff)[2], const uint64_t *lse_row,
                                            const float *look_row, int rows_pad, uint32_t xlse_ad)
 {
     constexpr int kPerStep = kSubInstr / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
     const int hf = lane >> 5;
-    const int lo0 = (r_range & 0xffff) - wave * kNS * 32, lo1 = lo0 - 32;      // r_range = r_lo | r_hi << 16
-    const int hi0 = (r_range >> 16) - wave * kNS * 32, hi1 = hi0 - 32;
+    const int lo1 = lo0 - 32, hi1 = hi0 - 32;      // this wave's keys lo0 <= key < hi0 (of 64) are the workgroup's
     bf16x8 qf[kKS];
     lift_k_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, qf);
     f32x16 da = logits32(kf[0], qf);
@@ -627,7 +626,9 @@ struct Walk {
 // 4 K loads (prob), [normaliser load], 4 K loads (stats); the bracketed ones exist on some waves or
 // in some steps only, so every wait counts only operations that are certainly issued behind the
 // ones it needs.
-template <int NB, int GB, int SLOT, int PAR>
+// EXTRA selects the variant that also serves paged keys (an upper bound on the tile's rows) and
+// lookahead keys in the normaliser; the plain variant carries none of their code or registers.
+template <int NB, int GB, int SLOT, int PAR, bool EXTRA>
 __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, int s, int n_phases, Ring &ring,
                                      Acc<NB> &acc, const LaneConst &lc, Walk &wk, unsigned char *lds, uint32_t lds0,
                                      uint64_t wave_off, int r_range)
@@ -730,11 +731,15 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
         ki.base = kbase + (int64_t)32 * stride_bytes;
         ki.step_bytes = 8u * stride_bytes;
         const uint64_t *lse_row = wave == kLseWave ? a.lse + (size_t)(clampi(pl, 0, n_phases - 1) % kSlots) * a.rows_pad : nullptr;
-        const float *look_row = a.look != nullptr ? a.look + (size_t)clampi(pl, 0, n_phases - 1) * a.rows_pad : nullptr;
+        const float *look_row = nullptr;
+        if (EXTRA && a.look != nullptr) look_row = a.look + (size_t)clampi(pl, 0, n_phases - 1) * a.rows_pad;
+        // r_range = r_lo | r_hi << 16 (r_hi = 512 without EXTRA): this wave's share of it
+        const int lo0 = (r_range & 0xffff) - wave * kNS * 32;
+        const int hi0 = EXTRA ? (r_range >> 16) - wave * kNS * 32 : kNS * 32;
         if (do_stats) {
             const uint32_t wstats_ad = lds0 + kOffWstats + PAR * kWstatsBytes + wave * (kMaxRowsF * 8) + ((uint32_t)(lane & 31) << 3);
             stats_pass<NB * GB, PAR>(a.c, ring.kf[SLOT], lc, sub_slot_off(wave, wk.slot0, 0),
-                                     sub_slot_off(wave, wk.slot0, 1), wstats_ad, r_range, wave, lane, ki, voff, lse_row,
+                                     sub_slot_off(wave, wk.slot0, 1), wstats_ad, lo0, hi0, lane, ki, voff, lse_row,
                                      look_row, a.rows_pad, lds0 + kOffXlse);
         } else {
             if (lse_row != nullptr) stage_exchange_rows(lds0 + kOffXlse, lse_row, look_row, a.rows_pad, lane);
@@ -809,7 +814,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
                     } while ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1));
                 }
                 v = __uint_as_float((uint32_t)entry);
-                if (a.look != nullptr) {
+                if (EXTRA && a.look != nullptr) {
                     // the row's softmax also runs over its visible lookahead keys: log-sum-exp of the
                     // prompt's normaliser and theirs (-inf when the row sees none), in raw-logit units
                     const float lp = -v, lk = read_look_staging(lds0, lane), top = fmaxf(lp, lk);
@@ -841,7 +846,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
     lds_barrier();
 }
 
-template <int NB, int GB>
+template <int NB, int GB, bool EXTRA>
 __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, LayerPtrs kp)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[kLdsBytes];
@@ -853,7 +858,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     // caller guarantees L >= 512): every workgroup loads 512 real keys; rows below r_lo belong to the
     // previous workgroup. Paged keys: pages are allocated whole and hold a multiple of 512 keys, so the
     // last tile stays where it is and rows from r_hi on (allocated, never written) are ignored.
-    const bool paged = a.block_table != nullptr;
+    const bool paged = EXTRA && a.block_table != nullptr;
     const int64_t j0 = (paged || (int64_t)(w + 1) * kFTile <= a.L) ? (int64_t)w * kFTile : a.L - kFTile;
     const int r_lo = (int)((int64_t)w * kFTile - j0);
     const int r_hi = (int)(a.L - j0 < kFTile ? a.L - j0 : kFTile);
@@ -933,10 +938,10 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     // instruction stream uniform. The last probability pass (phase n_phases - 1) runs in step n_phases + 3.
     const int n_steps = (n_phases + kLag + 1 + 3) / 4 * 4;
     for (int s0 = 0; s0 < n_steps; s0 += 4) {
-        step<NB, GB, 0, 0>(a, kp, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 1, 1>(a, kp, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 2, 0>(a, kp, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 3, 1>(a, kp, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 0, 0, EXTRA>(a, kp, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 1, 1, EXTRA>(a, kp, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 2, 0, EXTRA>(a, kp, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 3, 1, EXTRA>(a, kp, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
     }
     vm_wait<0>();               // no direct-to-LDS load may outlive the workgroup
     lds_barrier();
@@ -969,8 +974,8 @@ size_t workspace_bytes(int rows_pad, int n_wg)
 bool fits_one_per_cu()
 {
     int n1 = 0, n2 = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, sp_fused_kernel<1, 1>, kFThreads, 0) != hipSuccess) return false;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, sp_fused_kernel<2, 1>, kFThreads, 0) != hipSuccess) return false;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, sp_fused_kernel<1, 1, true>, kFThreads, 0) != hipSuccess) return false;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, sp_fused_kernel<2, 1, true>, kFThreads, 0) != hipSuccess) return false;
     return n1 >= 1 && n2 >= 1;
 }
 
@@ -990,14 +995,20 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, hipStream_t st)
     // compute unit (LDS), so the grid may not exceed the number of compute units. All waits in the
     // kernel are bounded; should residency fail (the device shared with other work), the call ends
     // with NaN scores and the error word set instead of hanging.
-    if (a.n_nblk == 2 && a.n_gblk == 1)
-        hipLaunchKernelGGL((sp_fused_kernel<2, 1>), dim3(a.n_wg), dim3(kFThreads), 0, st, a, kp);
-    else if (a.n_nblk == 1 && a.n_gblk == 2)
-        hipLaunchKernelGGL((sp_fused_kernel<1, 2>), dim3(a.n_wg), dim3(kFThreads), 0, st, a, kp);
-    else if (a.n_nblk == 1 && a.n_gblk == 1)
-        hipLaunchKernelGGL((sp_fused_kernel<1, 1>), dim3(a.n_wg), dim3(kFThreads), 0, st, a, kp);
-    else
+    const bool extra = a.look != nullptr || a.block_table != nullptr;
+    const dim3 grid(a.n_wg), block(kFThreads);
+    if (a.n_nblk == 2 && a.n_gblk == 1) {
+        if (extra) hipLaunchKernelGGL((sp_fused_kernel<2, 1, true>), grid, block, 0, st, a, kp);
+        else hipLaunchKernelGGL((sp_fused_kernel<2, 1, false>), grid, block, 0, st, a, kp);
+    } else if (a.n_nblk == 1 && a.n_gblk == 2) {
+        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 2, true>), grid, block, 0, st, a, kp);
+        else hipLaunchKernelGGL((sp_fused_kernel<1, 2, false>), grid, block, 0, st, a, kp);
+    } else if (a.n_nblk == 1 && a.n_gblk == 1) {
+        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 1, true>), grid, block, 0, st, a, kp);
+        else hipLaunchKernelGGL((sp_fused_kernel<1, 1, false>), grid, block, 0, st, a, kp);
+    } else {
         return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel: %d x %d row blocks", a.n_nblk, a.n_gblk);
+    }
     SP_HIP_CHECK(hipGetLastError());
     return SP_OK;
 }
