@@ -20,8 +20,9 @@
 //    MFMA steps: while one wave waits for a slot the other waves compute;
 //  * phase p: the statistics pass computes the partial (max, sum exp) of every
 //    query row over the workgroup's keys and publishes it to global memory;
-//  * one wave of some workgroup (rotating "duty") combines the partials of one
-//    row over all workgroups in a fixed order and publishes the normaliser;
+//  * one wave of some workgroup (rotating "duty") combines the partials of four
+//    consecutive rows over all workgroups in a fixed order and publishes their
+//    normalisers;
 //  * three phases later the workgroup picks the normalisers up and runs the
 //    probability pass of phase p from the fragments still in its registers:
 //    logits again with -lse folded into the MFMA accumulator, maximum over
