@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0
 # It is reported only while the kernel sources are the ones the counters were taken on.
 TRAFFIC = {
     "workload": "long-128k",
-    "sources_sha256": "9517afdcd2c814f163270a8f7cefaef45ffa9facfc9c84ade3a15815c751ddd3",
-    "fetch_bytes": 1090918.9 * 2048,      # FETCH_SIZE 1090918.9 per dispatch; the 1 GiB copy reads 524288 -> 2 KiB per count
+    "sources_sha256": "88aad1866da600e03bb363f46d09f7d674ce58187f425fdd710cf19c68342ca9",
+    "fetch_bytes": 1090884.4 * 2048,      # FETCH_SIZE 1090884.4 per dispatch; the 1 GiB copy reads 524307 -> 2 KiB per count
     "write_bytes": 16960.0 * 1024,        # WRITE_SIZE 16960.0 per dispatch; the 1 GiB copy writes 1048576 -> 1 KiB per count
 }
 KERNEL_SOURCES = ["sp_score_fused.hip", "sp_score_fused.hpp", "sp_score_dev.hpp"]     # the dominant kernel and its headers
