@@ -120,6 +120,9 @@ __device__ __forceinline__ int block_scan_incl(int v, int *wave_tot /*[16]*/, in
     return x + base;
 }
 
+// R > 0: the keys of up to R * 1024 chunks are read once and kept in registers (every pass over the
+// chunk scores would otherwise pay a trip to memory); R = 0: any number of chunks, re-read per pass.
+template <int R>
 __global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__restrict__ cs, int64_t n_chunks,
                                                                int64_t k, const int64_t *__restrict__ k_dev,
                                                                int chunk, int64_t L, int32_t *sel,
@@ -136,15 +139,35 @@ __global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__re
     __shared__ int64_t s_need;
     const int tid = threadIdx.x;
 
+    uint32_t cached[R > 0 ? R : 1];
+    if (R > 0) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int64_t i = (int64_t)r * kTopkThreads + tid;
+            cached[r] = i < n_chunks ? order_key(cs[i]) : 0u;
+        }
+    }
+    // key of chunk i = seg * kTopkThreads + tid (seg is a compile-time index wherever R > 0)
+    auto key_of = [&](int seg, int64_t i) -> uint32_t { return R > 0 ? cached[seg] : order_key(cs[i]); };
+
     // ---- radix select: key of the k-th largest chunk score ----
     uint32_t prefix = 0, mask = 0;
     int64_t need = k;                        // how many still to take from the current bucket
     for (int shift = 24; shift >= 0; shift -= 8) {
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
-        for (int64_t i = tid; i < n_chunks; i += kTopkThreads) {
-            const uint32_t key = order_key(cs[i]);
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        if (R > 0) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int64_t i = (int64_t)r * kTopkThreads + tid;
+                const uint32_t key = cached[r];
+                if (i < n_chunks && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+            }
+        } else {
+            for (int64_t i = tid; i < n_chunks; i += kTopkThreads) {
+                const uint32_t key = order_key(cs[i]);
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+            }
         }
         __syncthreads();
         {
@@ -169,10 +192,14 @@ __global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__re
 
     // ---- emit kept chunk indices in ascending order ----
     int64_t eq_seen = 0, out_base = 0;
-    for (int64_t base = 0; base < n_chunks; base += kTopkThreads) {
+    const int n_seg = (int)((n_chunks + kTopkThreads - 1) / kTopkThreads);
+#pragma unroll
+    for (int seg = 0; seg < (R > 0 ? R : n_seg); ++seg) {
+        if (R > 0 && seg >= n_seg) break;            // uniform
+        const int64_t base = (int64_t)seg * kTopkThreads;
         const int64_t i = base + tid;
         uint32_t key = 0;
-        if (i < n_chunks) key = order_key(cs[i]);
+        if (i < n_chunks) key = key_of(seg, i);
         const int is_eq = (i < n_chunks && key == thr) ? 1 : 0;
         int eq_total;
         const int eq_rank = block_scan_incl(is_eq, wave_tot, eq_total);   // 1-based among equals of this segment
@@ -342,6 +369,18 @@ __global__ __launch_bounds__(kTopkThreads) void sp_budget_kernel(const int32_t *
     }
 }
 
+void launch_topk(hipStream_t st, const float *cs, int64_t C, int64_t k, const int64_t *k_dev, int chunk, int64_t L,
+                 int32_t *sel, int64_t *spans, int32_t *n_spans)
+{
+    const dim3 grid(1), block(kTopkThreads);
+    if (C <= 2 * kTopkThreads)
+        hipLaunchKernelGGL((sp_topk_kernel<2>), grid, block, 0, st, cs, C, k, k_dev, chunk, L, sel, spans, n_spans);
+    else if (C <= 8 * kTopkThreads)
+        hipLaunchKernelGGL((sp_topk_kernel<8>), grid, block, 0, st, cs, C, k, k_dev, chunk, L, sel, spans, n_spans);
+    else
+        hipLaunchKernelGGL((sp_topk_kernel<0>), grid, block, 0, st, cs, C, k, k_dev, chunk, L, sel, spans, n_spans);
+}
+
 size_t budget_ws_layout(int64_t C, size_t &off_rank, size_t &off_hist, size_t &off_k)
 {
     size_t off = sp::align_up(sizeof(float) * (size_t)C, 256);
@@ -387,8 +426,7 @@ extern "C" sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_
     hipLaunchKernelGGL(sp_chunk_kernel, dim3(grid), dim3(kChunkThreads), 0, st, scores_dev, L, (int)pool_w,
                        (int)chunk, C, cs, chunk_scores_dev);
     SP_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(sp_topk_kernel, dim3(1), dim3(kTopkThreads), 0, st, (const float *)cs, C, k,
-                       (const int64_t *)nullptr, (int)chunk, L, sel_chunks_dev, spans_dev, n_spans_dev);
+    launch_topk(st, cs, C, k, nullptr, (int)chunk, L, sel_chunks_dev, spans_dev, n_spans_dev);
     SP_HIP_CHECK(hipGetLastError());
     return SP_OK;
 }
@@ -446,8 +484,7 @@ extern "C" sp_status sp_select_budget(const float *scores_dev, int64_t L, int32_
     hipLaunchKernelGGL(sp_budget_kernel, dim3(1), dim3(kTopkThreads), 0, st, (const int32_t *)hist, (int)C, budget, k_dev,
                        n_kept_dev);
     SP_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(sp_topk_kernel, dim3(1), dim3(kTopkThreads), 0, st, (const float *)cs, C, (int64_t)1,
-                       (const int64_t *)k_dev, (int)chunk, L, sel_chunks_dev, spans_dev, n_spans_dev);
+    launch_topk(st, cs, C, 1, k_dev, (int)chunk, L, sel_chunks_dev, spans_dev, n_spans_dev);
     SP_HIP_CHECK(hipGetLastError());
     return SP_OK;
 }

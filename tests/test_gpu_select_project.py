@@ -50,6 +50,7 @@ def check_select(scores32: np.ndarray, pool_w: int, chunk: int, k: int, eps: flo
 @pytest.mark.parametrize("L,pool_w,chunk,keep", [
     (1024, 13, 32, (25, 100)), (1000, 13, 32, (20, 100)), (8192, 13, 32, (20, 100)),
     (131072, 13, 64, (10, 100)), (70000, 13, 16, (15, 100)),     # > 1024 chunks: multi-segment scans
+    (40000, 13, 4, (10, 100)),                                   # 10000 chunks: keys re-read per pass, not cached
     (5, 13, 32, (100, 100)), (12, 13, 4, (50, 100)), (300, 1, 7, (30, 100)), (300, 129, 32, (30, 100)),
     (4097, 13, 128, (25, 100)), (999, 5, 1, (10, 100)), (2000, 13, 5000, (10, 100)),
 ])
