@@ -847,10 +847,47 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
     lds_barrier();
 }
 
-template <int NB, int GB, bool EXTRA>
+// Model shapes. The kernel takes every dimension at run time (AnyModel); an instantiation for a
+// fixed model overwrites its copy of the arguments with the model's constants, which the compiler
+// then folds: fewer live scalars (the generic kernel spills some sixty of them) and no address
+// arithmetic on run-time dimensions. Prompt length, workgroup count, kv-head stride and pointers
+// stay run-time values.
+struct AnyModel {
+    static constexpr bool kFixed = false;
+    static constexpr int kLayers = 0, kQHeads = 0, kKvHeads = 0, kNq = 0;
+};
+// The 16-layer, 32-query / 8-kv-head, head_dim 64 draft shape (a Llama-3.2-1B-class draft; Table 1 of
+// the paper) with NQ lookahead rows, token-contiguous keys and scale 1/8.
+template <int NQ>
+struct Draft16x32x8 {
+    static constexpr bool kFixed = true;
+    static constexpr int kLayers = 16, kQHeads = 32, kKvHeads = 8, kNq = NQ;
+};
+constexpr float kScaleEighthLog2e = 0.125f * 1.44269504088896340736f;    // scale 1/sqrt(64) times log2(e), as the host computes it
+
+template <class M>
+__device__ __forceinline__ void fold_model_constants(FusedArgs &a)
+{
+    if (M::kFixed) {
+        a.n_layers = M::kLayers;
+        a.n_q_heads = M::kQHeads;
+        a.n_kv_heads = M::kKvHeads;
+        a.group = M::kQHeads / M::kKvHeads;
+        a.n_q = M::kNq;
+        a.n_nblk = (M::kNq + 7) / 8;
+        a.n_gblk = (M::kQHeads / M::kKvHeads + 3) / 4;
+        a.rows_pad = a.n_nblk * a.n_gblk * 32;
+        a.k_stride_token = kD;
+        a.c = kScaleEighthLog2e;
+        a.inv_c = 1.0f / kScaleEighthLog2e;
+    }
+}
+
+template <int NB, int GB, bool EXTRA, class M>
 __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, LayerPtrs kp)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[kLdsBytes];
+    fold_model_constants<M>(a);
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hf = lane >> 5, col = lane & 31;
     const int w = blockIdx.x;
@@ -975,8 +1012,8 @@ size_t workspace_bytes(int rows_pad, int n_wg)
 bool fits_one_per_cu()
 {
     int n1 = 0, n2 = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, sp_fused_kernel<1, 1, true>, kFThreads, 0) != hipSuccess) return false;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, sp_fused_kernel<2, 1, true>, kFThreads, 0) != hipSuccess) return false;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, sp_fused_kernel<1, 1, true, AnyModel>, kFThreads, 0) != hipSuccess) return false;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, sp_fused_kernel<2, 1, true, AnyModel>, kFThreads, 0) != hipSuccess) return false;
     return n1 >= 1 && n2 >= 1;
 }
 
@@ -998,15 +1035,22 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, hipStream_t st)
     // with NaN scores and the error word set instead of hanging.
     const bool extra = a.look != nullptr || a.block_table != nullptr;
     const dim3 grid(a.n_wg), block(kFThreads);
-    if (a.n_nblk == 2 && a.n_gblk == 1) {
-        if (extra) hipLaunchKernelGGL((sp_fused_kernel<2, 1, true>), grid, block, 0, st, a, kp);
-        else hipLaunchKernelGGL((sp_fused_kernel<2, 1, false>), grid, block, 0, st, a, kp);
+    // the fixed-model instantiations apply when every folded constant equals the call's value
+    const bool draft = !extra && a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
+                       a.c == kScaleEighthLog2e && a.inv_c == 1.0f / kScaleEighthLog2e;
+    if (draft && a.n_q == 16) {
+        hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16>>), grid, block, 0, st, a, kp);
+    } else if (draft && a.n_q == 8) {
+        hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, Draft16x32x8<8>>), grid, block, 0, st, a, kp);
+    } else if (a.n_nblk == 2 && a.n_gblk == 1) {
+        if (extra) hipLaunchKernelGGL((sp_fused_kernel<2, 1, true, AnyModel>), grid, block, 0, st, a, kp);
+        else hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, AnyModel>), grid, block, 0, st, a, kp);
     } else if (a.n_nblk == 1 && a.n_gblk == 2) {
-        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 2, true>), grid, block, 0, st, a, kp);
-        else hipLaunchKernelGGL((sp_fused_kernel<1, 2, false>), grid, block, 0, st, a, kp);
+        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 2, true, AnyModel>), grid, block, 0, st, a, kp);
+        else hipLaunchKernelGGL((sp_fused_kernel<1, 2, false, AnyModel>), grid, block, 0, st, a, kp);
     } else if (a.n_nblk == 1 && a.n_gblk == 1) {
-        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 1, true>), grid, block, 0, st, a, kp);
-        else hipLaunchKernelGGL((sp_fused_kernel<1, 1, false>), grid, block, 0, st, a, kp);
+        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 1, true, AnyModel>), grid, block, 0, st, a, kp);
+        else hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, AnyModel>), grid, block, 0, st, a, kp);
     } else {
         return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel: %d x %d row blocks", a.n_nblk, a.n_gblk);
     }

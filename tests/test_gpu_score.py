@@ -161,6 +161,9 @@ FUSED_SHAPES = [
     ("fused_g3_nq5_padding", 2, 6, 2, 64, 5, 35000),
     ("fused_single_phase_full_grid", 1, 4, 1, 64, 16, 131072),
     ("fused_20_phases", 5, 8, 4, 64, 16, 40000),
+    # the two kernel instantiations with a fixed model shape (16 layers, 32 / 8 heads): 8 and 16 lookahead rows
+    ("fused_draft_model_nq8", 16, 32, 8, 64, 8, 33000),
+    ("fused_draft_model_nq16", 16, 32, 8, 64, 16, 32768 + 513),
 ]
 
 
