@@ -851,17 +851,19 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
 // fixed model overwrites its copy of the arguments with the model's constants, which the compiler
 // then folds: fewer live scalars (the generic kernel spills some sixty of them) and no address
 // arithmetic on run-time dimensions. Prompt length, workgroup count, kv-head stride and pointers
-// stay run-time values.
+// stay run-time values; the workgroup count is folded too in the instantiations for a prompt that
+// fills the device (256 workgroups: 128K tokens), where every exchange slot is in use and the bounds
+// checks on workgroup indices fall away.
 struct AnyModel {
     static constexpr bool kFixed = false;
-    static constexpr int kLayers = 0, kQHeads = 0, kKvHeads = 0, kNq = 0;
+    static constexpr int kLayers = 0, kQHeads = 0, kKvHeads = 0, kNq = 0, kWorkgroups = 0;
 };
 // The 16-layer, 32-query / 8-kv-head, head_dim 64 draft shape (a Llama-3.2-1B-class draft; Table 1 of
 // the paper) with NQ lookahead rows, token-contiguous keys and scale 1/8.
-template <int NQ>
+template <int NQ, int WORKGROUPS>
 struct Draft16x32x8 {
     static constexpr bool kFixed = true;
-    static constexpr int kLayers = 16, kQHeads = 32, kKvHeads = 8, kNq = NQ;
+    static constexpr int kLayers = 16, kQHeads = 32, kKvHeads = 8, kNq = NQ, kWorkgroups = WORKGROUPS;   // 0: run-time count
 };
 constexpr float kScaleEighthLog2e = 0.125f * 1.44269504088896340736f;    // scale 1/sqrt(64) times log2(e), as the host computes it
 
@@ -880,6 +882,7 @@ __device__ __forceinline__ void fold_model_constants(FusedArgs &a)
         a.k_stride_token = kD;
         a.c = kScaleEighthLog2e;
         a.inv_c = 1.0f / kScaleEighthLog2e;
+        if (M::kWorkgroups > 0) a.n_wg = M::kWorkgroups;
     }
 }
 
@@ -1039,9 +1042,11 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, hipStream_t st)
     const bool draft = !extra && a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
                        a.c == kScaleEighthLog2e && a.inv_c == 1.0f / kScaleEighthLog2e;
     if (draft && a.n_q == 16) {
-        hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16>>), grid, block, 0, st, a, kp);
+        if (a.n_wg == 256) hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 256>>), grid, block, 0, st, a, kp);
+        else hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 0>>), grid, block, 0, st, a, kp);
     } else if (draft && a.n_q == 8) {
-        hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, Draft16x32x8<8>>), grid, block, 0, st, a, kp);
+        if (a.n_wg == 256) hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, Draft16x32x8<8, 256>>), grid, block, 0, st, a, kp);
+        else hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, Draft16x32x8<8, 0>>), grid, block, 0, st, a, kp);
     } else if (a.n_nblk == 2 && a.n_gblk == 1) {
         if (extra) hipLaunchKernelGGL((sp_fused_kernel<2, 1, true, AnyModel>), grid, block, 0, st, a, kp);
         else hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, AnyModel>), grid, block, 0, st, a, kp);

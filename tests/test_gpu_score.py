@@ -164,6 +164,7 @@ FUSED_SHAPES = [
     # the two kernel instantiations with a fixed model shape (16 layers, 32 / 8 heads): 8 and 16 lookahead rows
     ("fused_draft_model_nq8", 16, 32, 8, 64, 8, 33000),
     ("fused_draft_model_nq16", 16, 32, 8, 64, 16, 32768 + 513),
+    ("fused_draft_model_nq8_full_grid", 16, 32, 8, 64, 8, 131072 - 100),     # 256 workgroups, ragged last tile
 ]
 
 
