@@ -63,8 +63,12 @@ def log(msg: str) -> None:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="untimed: the step is repeated for this long before the warm-up steps, so that the device's "
+                         "power management has settled at its sustained clock (after an idle period the first few "
+                         "dispatches run ~2 %% faster than sustained, the next ~40 up to 25 %% slower)")
     ap.add_argument("--workload", default="long-128k")
     ap.add_argument("--layer-agg", default="mean", choices=["mean", "max"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -153,6 +157,11 @@ def main() -> int:
         a_dst.copy_(a_src)
         torch.cuda.synchronize()
         del a_src, a_dst
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -177,6 +186,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "settle_ms": args.settle_ms,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
