@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0
 # It is reported only while the kernel sources are the ones the counters were taken on.
 TRAFFIC = {
     "workload": "long-128k",
-    "sources_sha256": "88aad1866da600e03bb363f46d09f7d674ce58187f425fdd710cf19c68342ca9",
-    "fetch_bytes": 1090884.4 * 2048,      # FETCH_SIZE 1090884.4 per dispatch; the 1 GiB copy reads 524307 -> 2 KiB per count
+    "sources_sha256": "3f583bcc070e7a9b61a94a09f9e918ee01e130fc5da73d9b45b7b1fd390008bd",
+    "fetch_bytes": 1090789.5 * 2048,      # FETCH_SIZE 1090789.5 per dispatch; the 1 GiB copy reads 524307 -> 2 KiB per count
     "write_bytes": 16960.0 * 1024,        # WRITE_SIZE 16960.0 per dispatch; the 1 GiB copy writes 1048576 -> 1 KiB per count
 }
 KERNEL_SOURCES = ["sp_score_fused.hip", "sp_score_fused.hpp", "sp_score_dev.hpp"]     # the dominant kernel and its headers
