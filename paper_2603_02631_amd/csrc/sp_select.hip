@@ -151,11 +151,14 @@ __global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__re
     auto key_of = [&](int seg, int64_t i) -> uint32_t { return R > 0 ? cached[seg] : order_key(cs[i]); };
 
     // ---- radix select: key of the k-th largest chunk score ----
+    // Per pass: all threads count their candidates into a 256-bin histogram; wave 0 alone scans the
+    // bins from the top (four per lane, one shuffle scan), picks the bin that holds the k-th, and clears
+    // the histogram for the next pass: two barriers per pass.
     uint32_t prefix = 0, mask = 0;
     int64_t need = k;                        // how many still to take from the current bucket
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
     for (int shift = 24; shift >= 0; shift -= 8) {
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
         if (R > 0) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
@@ -170,28 +173,44 @@ __global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__re
             }
         }
         __syncthreads();
-        {
-            // thread t looks at bucket 255 - t: an inclusive scan gives the number of candidates in
-            // this bucket and above; the bucket where that count first reaches `need` holds the k-th
-            const int h = tid < 256 ? hist[255 - tid] : 0;
-            int total;
-            const int incl = block_scan_incl(h, wave_tot, total);
-            if (tid < 256 && (int64_t)(incl - h) < need && (int64_t)incl >= need) {
-                s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
-                s_need = need - (incl - h);
+        if (tid < 64) {
+            // lane l owns bins 255-4l .. 252-4l, in that (descending) order
+            int h[4], lane_sum = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                h[j] = hist[255 - 4 * tid - j];
+                hist[255 - 4 * tid - j] = 0;
+                lane_sum += h[j];
+            }
+            int incl = lane_sum;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int y = __shfl_up(incl, off);
+                if (tid >= off) incl += y;
+            }
+            int64_t before = incl - lane_sum;        // candidates in the bins above this lane's
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (before < need && before + h[j] >= need) {
+                    s_prefix = prefix | ((uint32_t)(255 - 4 * tid - j) << shift);
+                    s_need = need - before;
+                }
+                before += h[j];
             }
         }
         __syncthreads();
         prefix = s_prefix;
         need = s_need;
         mask |= 255u << shift;
-        __syncthreads();
     }
     const uint32_t thr = prefix;             // exact key of the k-th largest score
     // `need` = number of chunks equal to thr to keep, taken in index order.
 
     // ---- emit kept chunk indices in ascending order ----
-    int64_t eq_seen = 0, out_base = 0;
+    // Kept: every chunk above thr and the first `need` chunks equal to thr. One scan per segment of a
+    // packed pair (above in the low half, equal in the high half) gives each chunk's output position:
+    // chunks above before it plus min(equal chunks before it, need).
+    int64_t eq_seen = 0, gt_seen = 0;
     const int n_seg = (int)((n_chunks + kTopkThreads - 1) / kTopkThreads);
 #pragma unroll
     for (int seg = 0; seg < (R > 0 ? R : n_seg); ++seg) {
@@ -201,14 +220,15 @@ __global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__re
         uint32_t key = 0;
         if (i < n_chunks) key = key_of(seg, i);
         const int is_eq = (i < n_chunks && key == thr) ? 1 : 0;
-        int eq_total;
-        const int eq_rank = block_scan_incl(is_eq, wave_tot, eq_total);   // 1-based among equals of this segment
-        const int keep = (i < n_chunks) && (key > thr || (is_eq && eq_seen + eq_rank <= need));
-        int keep_total;
-        const int pos = block_scan_incl(keep, wave_tot, keep_total);
-        if (keep) sel[out_base + pos - 1] = (int32_t)i;
-        eq_seen += eq_total;
-        out_base += keep_total;
+        const int is_gt = (i < n_chunks && key > thr) ? 1 : 0;
+        int total;
+        const int incl = block_scan_incl(is_gt | (is_eq << 16), wave_tot, total);
+        const int64_t gt_before = gt_seen + (incl & 0xffff) - is_gt;
+        const int64_t eq_before = eq_seen + (incl >> 16) - is_eq;
+        if (is_gt) sel[gt_before + (eq_before < need ? eq_before : need)] = (int32_t)i;
+        else if (is_eq && eq_before < need) sel[gt_before + eq_before] = (int32_t)i;
+        gt_seen += total & 0xffff;
+        eq_seen += total >> 16;
     }
     __syncthreads();                         // sel[] written by this block is read below
 
