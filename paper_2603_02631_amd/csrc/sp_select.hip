@@ -28,10 +28,12 @@
 // inside one chunk or on a boundary whose chunks on both sides are all selected,
 // r(t) = the largest rank among them. Kept tokens at k = #{t : r(t) < k}: a
 // histogram of r and a prefix sum give the count for every k at once.
-//   sp_rank_kernel        rank of every chunk by counting (C^2 / 2 comparisons
-//                         spread over the device), clears the histogram;
+//   sp_chunk_kernel       also leaves the chunk boundaries' character offsets in a
+//                         compact array and clears the counters of the next two;
+//   sp_rank_kernel        rank of every chunk by counting: tiles of 256 chunks
+//                         against tiles of 256 chunks, one workgroup per pair;
 //   sp_token_rank_kernel  one thread per target token: binary searches of the
-//                         chunk boundaries' character offsets, r(t), histogram;
+//                         compact boundary array, r(t), histogram;
 //   sp_budget_kernel      one workgroup: prefix sum, largest k within the budget;
 //   sp_topk_kernel        as above, reading k from device memory.
 #include "sp_common.hpp"
@@ -47,7 +49,11 @@ constexpr int kTopkThreads = 1024;
 __global__ __launch_bounds__(kChunkThreads) void sp_chunk_kernel(const float *__restrict__ scores, int64_t L,
                                                                  int pool_w, int chunk, int64_t n_chunks,
                                                                  float *__restrict__ cs_ws,
-                                                                 float *__restrict__ cs_out)
+                                                                 float *__restrict__ cs_out,
+                                                                 const int64_t *__restrict__ draft_off,
+                                                                 int64_t *__restrict__ bnd,
+                                                                 int32_t *__restrict__ rank,
+                                                                 int32_t *__restrict__ hist)
 {
     __shared__ float stage[kChunkThreads / 64][kSegLds + 3];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -86,6 +92,17 @@ __global__ __launch_bounds__(kChunkThreads) void sp_chunk_kernel(const float *__
         const float v = part / ((float)pool_w * (float)(end - begin)) + 0.0f;
         cs_ws[ci] = v;
         if (cs_out) cs_out[ci] = v;
+        if (bnd) {
+            // set-up for the budget search: character offset of the chunk's first token (one more entry:
+            // the end of the text), cleared rank counters and histogram bins (one more: "never kept")
+            bnd[ci] = draft_off[begin];
+            rank[ci] = 0;
+            hist[ci] = 0;
+            if (ci == n_chunks - 1) {
+                bnd[n_chunks] = draft_off[L];
+                hist[n_chunks] = 0;
+            }
+        }
     }
 }
 
@@ -265,39 +282,37 @@ constexpr int kRankThreads = 256;
 constexpr int kMaxBudgetChunks = 1 << 16;
 
 // rank[j] = number of chunks that come before chunk j in the order (score descending, index
-// ascending). Also clears the C + 1 histogram bins.
+// ascending). Workgroup (x, y) counts, for the 256 chunks of tile x, the chunks of tile y that come
+// before them and adds the counts to rank (cleared beforehand): C^2 comparisons over (C / 256)^2
+// workgroups.
 __global__ __launch_bounds__(kRankThreads) void sp_rank_kernel(const float *__restrict__ cs, int n_chunks,
-                                                               int32_t *__restrict__ rank,
-                                                               int32_t *__restrict__ hist)
+                                                               int32_t *__restrict__ rank)
 {
-    __shared__ uint32_t tile[kRankThreads];
+    __shared__ uint4 tile[kRankThreads / 4];
     const int j = blockIdx.x * kRankThreads + threadIdx.x;
-    const uint32_t mine = j < n_chunks ? order_key(cs[j]) : 0u;
+    const int base = blockIdx.y * kRankThreads;
+    const int i = base + threadIdx.x;
+    // entries past the last chunk get key 0, the image of no finite score: they never count
+    reinterpret_cast<uint32_t *>(tile)[threadIdx.x] = i < n_chunks ? order_key(cs[i]) : 0u;
+    __syncthreads();
+    if (j >= n_chunks) return;
+    const uint32_t mine = order_key(cs[j]);
     int before = 0;
-    for (int base = 0; base < n_chunks; base += kRankThreads) {
-        const int i = base + threadIdx.x;
-        __syncthreads();
-        tile[threadIdx.x] = i < n_chunks ? order_key(cs[i]) : 0u;
-        __syncthreads();
-        const int n = min(kRankThreads, n_chunks - base);
-        for (int t = 0; t < n; ++t) {
-            const uint32_t other = tile[t];
-            before += (other > mine) || (other == mine && base + t < j);
-        }
+#pragma unroll 4
+    for (int t = 0; t < kRankThreads / 4; ++t) {
+        const uint4 o = tile[t];
+        const int i0 = base + 4 * t;
+        before += (o.x > mine) || (o.x == mine && i0 < j);
+        before += (o.y > mine) || (o.y == mine && i0 + 1 < j);
+        before += (o.z > mine) || (o.z == mine && i0 + 2 < j);
+        before += (o.w > mine) || (o.w == mine && i0 + 3 < j);
     }
-    if (j < n_chunks) {
-        rank[j] = before;
-        hist[j] = 0;
-    }
-    if (j == 0) hist[n_chunks] = 0;
+    if (before) atomicAdd(&rank[j], before);
 }
 
-// Character offset of chunk boundary m (0 .. C): boundary C is the end of the text.
-__device__ __forceinline__ int64_t boundary(const int64_t *__restrict__ doff, int64_t L, int chunk, int m)
-{
-    const int64_t tok = (int64_t)m * chunk;
-    return doff[tok < L ? tok : L];
-}
+// Character offset of chunk boundary m (0 .. C; boundary C is the end of the text), from the compact
+// array the chunk kernel has filled (a few KB: the searches below stay in the caches).
+__device__ __forceinline__ int64_t boundary(const int64_t *__restrict__ bnd, int64_t, int, int m) { return bnd[m]; }
 
 // First boundary index in [lo, hi] whose offset is > x (STRICT) or >= x; hi + 1 if none.
 template <bool STRICT>
@@ -320,11 +335,13 @@ __global__ __launch_bounds__(kRankThreads) void sp_token_rank_kernel(const int64
                                                                      int32_t *__restrict__ hist)
 {
     const int64_t t = (int64_t)blockIdx.x * kRankThreads + threadIdx.x;
-    if (t >= M) return;
-    const int64_t a = toff[t], b = toff[t + 1];
+    const bool live = t < M;
+    const int64_t a = live ? toff[t] : 0, b = live ? toff[t + 1] : 0;
     const int C = n_chunks;
     int r = C;                                   // bin C: kept by no selection
-    if (b > a) {
+    if (!live) {
+        r = -1;
+    } else if (b > a) {
         // chunks j with a < e[j+1] and b > e[j]: a contiguous range
         const int j_lo = first_boundary<true>(doff, L, chunk, 1, C, a) - 1;        // first j with e[j+1] > a
         const int j_hi = first_boundary<false>(doff, L, chunk, 0, C - 1, b) - 1;   // last j with e[j] < b
@@ -345,7 +362,17 @@ __global__ __launch_bounds__(kRankThreads) void sp_token_rank_kernel(const int64
             }
         }
     }
-    atomicAdd(&hist[r], 1);
+    // Neighbouring tokens mostly share their bin: the first lane of every run of equal r within the
+    // wave adds the run's length (integer counts: the histogram is the same in any order).
+    const int lane = threadIdx.x & 63;
+    const int prev = __shfl_up(r, 1);
+    const bool leader = lane == 0 || prev != r;
+    const uint64_t leaders = __ballot(leader);
+    if (leader && r >= 0) {
+        const uint64_t later = lane == 63 ? 0 : leaders >> (lane + 1);
+        const int run = later ? __ffsll((unsigned long long)later) : 64 - lane;
+        atomicAdd(&hist[r], run);
+    }
 }
 
 // kept(k) = hist[0] + .. + hist[k-1]; writes the largest k in 1..C with kept(k) <= budget (1 if none)
@@ -401,12 +428,12 @@ void launch_topk(hipStream_t st, const float *cs, int64_t C, int64_t k, const in
         hipLaunchKernelGGL((sp_topk_kernel<0>), grid, block, 0, st, cs, C, k, k_dev, chunk, L, sel, spans, n_spans);
 }
 
-size_t budget_ws_layout(int64_t C, size_t &off_rank, size_t &off_hist, size_t &off_k)
+size_t budget_ws_layout(int64_t C, size_t &off_rank, size_t &off_hist, size_t &off_bnd)
 {
     size_t off = sp::align_up(sizeof(float) * (size_t)C, 256);
     off_rank = off; off = sp::align_up(off + sizeof(int32_t) * (size_t)C, 256);
     off_hist = off; off = sp::align_up(off + sizeof(int32_t) * ((size_t)C + 1), 256);
-    off_k = off;    off = sp::align_up(off + sizeof(int64_t), 256);
+    off_bnd = off;  off = sp::align_up(off + sizeof(int64_t) * ((size_t)C + 1), 256);
     return off;
 }
 
@@ -444,7 +471,8 @@ extern "C" sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_
     const int waves_per_block = kChunkThreads / 64;
     const unsigned grid = (unsigned)((C + waves_per_block - 1) / waves_per_block);
     hipLaunchKernelGGL(sp_chunk_kernel, dim3(grid), dim3(kChunkThreads), 0, st, scores_dev, L, (int)pool_w,
-                       (int)chunk, C, cs, chunk_scores_dev);
+                       (int)chunk, C, cs, chunk_scores_dev, (const int64_t *)nullptr, (int64_t *)nullptr,
+                       (int32_t *)nullptr, (int32_t *)nullptr);
     SP_HIP_CHECK(hipGetLastError());
     launch_topk(st, cs, C, k, nullptr, (int)chunk, L, sel_chunks_dev, spans_dev, n_spans_dev);
     SP_HIP_CHECK(hipGetLastError());
@@ -480,8 +508,8 @@ extern "C" sp_status sp_select_budget(const float *scores_dev, int64_t L, int32_
     const int64_t C = (L + chunk - 1) / chunk;
     if (C > kMaxBudgetChunks)
         return sp::fail(SP_ERR_UNSUPPORTED, "%lld chunks (the budget search supports <= %d)", (long long)C, kMaxBudgetChunks);
-    size_t off_rank, off_hist, off_k;
-    const size_t need = budget_ws_layout(C, off_rank, off_hist, off_k);
+    size_t off_rank, off_hist, off_bnd;
+    const size_t need = budget_ws_layout(C, off_rank, off_hist, off_bnd);
     if (!ws_dev) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is null (%zu bytes needed)", need);
     if ((uintptr_t)ws_dev % 256 != 0) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is not 256-byte aligned");
     if (ws_bytes < need) return sp::fail(SP_ERR_WORKSPACE, "workspace too small: %zu < %zu", ws_bytes, need);
@@ -491,15 +519,17 @@ extern "C" sp_status sp_select_budget(const float *scores_dev, int64_t L, int32_
     float *cs = reinterpret_cast<float *>(ws);
     int32_t *rank = reinterpret_cast<int32_t *>(ws + off_rank);
     int32_t *hist = reinterpret_cast<int32_t *>(ws + off_hist);
+    int64_t *bnd = reinterpret_cast<int64_t *>(ws + off_bnd);
     const int waves_per_block = kChunkThreads / 64;
     hipLaunchKernelGGL(sp_chunk_kernel, dim3((unsigned)((C + waves_per_block - 1) / waves_per_block)),
-                       dim3(kChunkThreads), 0, st, scores_dev, L, (int)pool_w, (int)chunk, C, cs, chunk_scores_dev);
+                       dim3(kChunkThreads), 0, st, scores_dev, L, (int)pool_w, (int)chunk, C, cs, chunk_scores_dev,
+                       draft_off_dev, bnd, rank, hist);
     SP_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(sp_rank_kernel, dim3((unsigned)((C + kRankThreads - 1) / kRankThreads)), dim3(kRankThreads), 0, st,
-                       (const float *)cs, (int)C, rank, hist);
+    const unsigned n_tiles = (unsigned)((C + kRankThreads - 1) / kRankThreads);
+    hipLaunchKernelGGL(sp_rank_kernel, dim3(n_tiles, n_tiles), dim3(kRankThreads), 0, st, (const float *)cs, (int)C, rank);
     SP_HIP_CHECK(hipGetLastError());
     hipLaunchKernelGGL(sp_token_rank_kernel, dim3((unsigned)((M + kRankThreads - 1) / kRankThreads)), dim3(kRankThreads),
-                       0, st, draft_off_dev, L, (int)chunk, (int)C, target_off_dev, M, (const int32_t *)rank, hist);
+                       0, st, (const int64_t *)bnd, L, (int)chunk, (int)C, target_off_dev, M, (const int32_t *)rank, hist);
     SP_HIP_CHECK(hipGetLastError());
     hipLaunchKernelGGL(sp_budget_kernel, dim3(1), dim3(kTopkThreads), 0, st, (const int32_t *)hist, (int)C, budget, k_dev,
                        n_kept_dev);
