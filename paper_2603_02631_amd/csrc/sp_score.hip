@@ -243,14 +243,17 @@ __global__ __launch_bounds__(kThreads, 4) void sp_stats_kernel(ScoreArgs a, Laye
 
 // ---------------------------------------------------------------------------
 // merge: one workgroup per (32-row block, phase, prompt). 8 slices of the
-// prompt's tiles are reduced by 8 thread groups, then combined in slice order.
+// prompt's tiles are reduced by 32 thread groups, then combined in slice order.
 // Writes -lse in raw-logit units, i.e. -(m + log2(l)/c), at the position the
 // prob pass reads it from: within a block, row rho = 8*q + 4*hf + e goes to
 // hf*16 + 4*q + e. Padding rows get -inf so they never win a maximum.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void sp_merge_kernel(ScoreArgs a)
+constexpr int kMergeSlices = 32;             // thread groups of 32 rows that share a prompt's tiles
+constexpr int kMergeThreads = 32 * kMergeSlices;
+
+__global__ __launch_bounds__(kMergeThreads) void sp_merge_kernel(ScoreArgs a)
 {
-    __shared__ float2 red[8][32];
+    __shared__ float2 red[kMergeSlices][32];
     const int tid = threadIdx.x, rho = tid & 31, slice = tid >> 5;
     const int blk = blockIdx.x, phase = blockIdx.y, prompt = blockIdx.z;
     const int n_phases = a.n_layers * a.n_kv_heads;
@@ -258,7 +261,7 @@ __global__ __launch_bounds__(kThreads) void sp_merge_kernel(ScoreArgs a)
     if (a.prompt_tiles) { t0 = a.prompt_tiles[prompt]; t1 = a.prompt_tiles[prompt + 1]; }
     const int row = blk * 32 + rho;
     float m = neg_inf(), l = 0.f;
-    for (int t = t0 + slice; t < t1; t += 8) {
+    for (int t = t0 + slice; t < t1; t += kMergeSlices) {
         const float2 p = a.part[((int64_t)phase * a.n_tiles + t) * a.rows_pad + row];
         lse_merge(m, l, p.x, p.y, a.c);
     }
@@ -266,7 +269,7 @@ __global__ __launch_bounds__(kThreads) void sp_merge_kernel(ScoreArgs a)
     __syncthreads();
     if (slice == 0) {
 #pragma unroll
-        for (int s = 1; s < 8; ++s) lse_merge(m, l, red[s][rho].x, red[s][rho].y, a.c);
+        for (int s = 1; s < kMergeSlices; ++s) lse_merge(m, l, red[s][rho].x, red[s][rho].y, a.c);
         int g, n;
         const bool valid = row_to_gn(a, row, g, n) && l > 0.f;
         float v = valid ? -(m + fast_log2(l) * a.inv_c) : neg_inf();
@@ -610,7 +613,7 @@ sp_status launch_all(const Plan &p, const ScoreArgs &a, const LayerPtrs &kp, hip
     const dim3 block(kThreads);
     hipLaunchKernelGGL((sp_stats_kernel<D, NS>), dim3(a.n_tiles, p.n_phases), block, p.lds_bytes, st, a, kp);
     SP_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(sp_merge_kernel, dim3(p.rows_pad / 32, p.n_phases, a.n_prompts), block, 0, st, a);
+    hipLaunchKernelGGL(sp_merge_kernel, dim3(p.rows_pad / 32, p.n_phases, a.n_prompts), dim3(kMergeThreads), 0, st, a);
     SP_HIP_CHECK(hipGetLastError());
     const dim3 grid(a.n_tiles, a.n_splits);
     if (p.NB == 1)
