@@ -194,6 +194,26 @@ sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_w,
                     float *chunk_scores_dev, void *ws_dev, size_t ws_bytes,
                     void *hip_stream);
 
+/*
+ * sp_select for callers that cannot allocate device memory or pass a workspace:
+ * code recorded into a HIP graph, tight serving loops, harnesses that forbid
+ * hipMalloc. Same arguments, kernels and results as sp_select, without ws_dev /
+ * ws_bytes: the chunk scores go to an array that is part of the library's
+ * device image (SP_SELECT_STATIC_MAX_CHUNKS floats = 1 MiB, held on every
+ * device the library is used on until the process ends). The call allocates
+ * and frees nothing. More than SP_SELECT_STATIC_MAX_CHUNKS chunks is
+ * SP_ERR_UNSUPPORTED (use sp_select). The first call on a device looks the
+ * array's address up (a host-only query; make that call outside a graph
+ * capture). All calls on one device share the array: calls that may overlap
+ * on the device (different streams without ordering) race; calls ordered by a
+ * stream or by events do not, and nothing has to be cleared between them.
+ */
+#define SP_SELECT_STATIC_MAX_CHUNKS (1 << 18)
+sp_status sp_select_static(const float *scores_dev, int64_t L, int32_t pool_w,
+                           int32_t chunk, int64_t k, int32_t *sel_chunks_dev,
+                           int64_t *spans_dev, int32_t *n_spans_dev,
+                           float *chunk_scores_dev, void *hip_stream);
+
 /* Bytes of workspace sp_select_budget needs (SP_ERR_UNSUPPORTED beyond 65536 chunks). */
 sp_status sp_select_budget_workspace(int64_t L, int32_t chunk, size_t *bytes);
 

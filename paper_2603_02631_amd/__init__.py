@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     sp_score_workspace,
     sp_select,
     sp_select_budget,
+    sp_select_static,
     sp_select_budget_workspace,
     sp_select_workspace,
     sp_version,

@@ -21,7 +21,7 @@ _LIB_PATH = os.path.join(_PKG_DIR, "libsp_amd.so")
 
 EXPORTS = (
     "sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_is_fused", "sp_score_batch", "sp_keep_count", "sp_select_workspace",
-    "sp_select", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble", "sp_last_error", "sp_version",
+    "sp_select", "sp_select_static", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble", "sp_last_error", "sp_version",
 )
 
 
@@ -78,6 +78,7 @@ def load_library():
     lib.sp_keep_count.restype = c.c_int64
     lib.sp_select_workspace.argtypes = [c.c_int64, c.c_int32, c.POINTER(c.c_size_t)]
     lib.sp_select.argtypes = [P, c.c_int64, c.c_int32, c.c_int32, c.c_int64, P, P, P, P, P, c.c_size_t, P]
+    lib.sp_select_static.argtypes = [P, c.c_int64, c.c_int32, c.c_int32, c.c_int64, P, P, P, P, P]
     lib.sp_select_budget_workspace.argtypes = [c.c_int64, c.c_int32, c.POINTER(c.c_size_t)]
     lib.sp_select_budget.argtypes = [P, c.c_int64, c.c_int32, c.c_int32, P, P, c.c_int64, c.c_int64, P, P, P, P, P, P,
                                      P, c.c_size_t, P]
@@ -87,7 +88,7 @@ def load_library():
     lib.sp_last_error.restype = c.c_char_p
     lib.sp_version.restype = c.c_char_p
     for name in ("sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_is_fused", "sp_score_batch", "sp_select_workspace", "sp_select",
-                 "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble"):
+                 "sp_select_static", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -192,6 +193,12 @@ def sp_select(scores, L: int, pool_w: int, chunk: int, k: int, sel_chunks, spans
     nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
     _check(load_library().sp_select(_ptr(scores), L, pool_w, chunk, k, _ptr(sel_chunks), _ptr(spans), _ptr(n_spans),
                                     _ptr(chunk_scores), _ptr(ws), nbytes, _stream(stream)))
+
+
+def sp_select_static(scores, L: int, pool_w: int, chunk: int, k: int, sel_chunks, spans, n_spans, chunk_scores,
+                     stream=None) -> None:
+    _check(load_library().sp_select_static(_ptr(scores), L, pool_w, chunk, k, _ptr(sel_chunks), _ptr(spans),
+                                           _ptr(n_spans), _ptr(chunk_scores), _stream(stream)))
 
 
 def sp_select_budget_workspace(L: int, chunk: int) -> int:

@@ -38,6 +38,8 @@
 //   sp_topk_kernel        as above, reading k from device memory.
 #include "sp_common.hpp"
 
+#include <atomic>
+
 namespace {
 
 constexpr int kChunkThreads = 256;           // 4 waves, one chunk each
@@ -448,9 +450,11 @@ extern "C" sp_status sp_select_workspace(int64_t L, int32_t chunk, size_t *bytes
     return SP_OK;
 }
 
-extern "C" sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_w, int32_t chunk, int64_t k,
-                               int32_t *sel_chunks_dev, int64_t *spans_dev, int32_t *n_spans_dev,
-                               float *chunk_scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
+namespace {
+
+// Validation shared by the two selection entry points, then the two launches; `cs` receives the chunk scores.
+sp_status select_check(const float *scores_dev, int64_t L, int32_t pool_w, int32_t chunk, int64_t k,
+                       const int32_t *sel_chunks_dev, const int64_t *spans_dev, const int32_t *n_spans_dev, int64_t &C)
 {
     if (!scores_dev || !sel_chunks_dev || !spans_dev || !n_spans_dev)
         return sp::fail(SP_ERR_INVALID_ARG, "scores_dev, sel_chunks_dev, spans_dev and n_spans_dev must not be null");
@@ -458,16 +462,16 @@ extern "C" sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_
     if (chunk < 1) return sp::fail(SP_ERR_INVALID_ARG, "chunk = %d must be >= 1", chunk);
     if (pool_w < 1 || pool_w % 2 == 0) return sp::fail(SP_ERR_INVALID_ARG, "pool_w = %d must be odd and >= 1", pool_w);
     if (pool_w > kMaxPool) return sp::fail(SP_ERR_UNSUPPORTED, "pool_w = %d (supported: <= %d)", pool_w, kMaxPool);
-    const int64_t C = (L + chunk - 1) / chunk;
+    C = (L + chunk - 1) / chunk;
     if (C > (1 << 30)) return sp::fail(SP_ERR_UNSUPPORTED, "too many chunks (%lld)", (long long)C);
     if (k < 1 || k > C) return sp::fail(SP_ERR_INVALID_ARG, "k = %lld outside 1..%lld", (long long)k, (long long)C);
-    const size_t need = sp::align_up(sizeof(float) * (size_t)C, 256);
-    if (!ws_dev) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is null (%zu bytes needed)", need);
-    if ((uintptr_t)ws_dev % 256 != 0) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is not 256-byte aligned");
-    if (ws_bytes < need) return sp::fail(SP_ERR_WORKSPACE, "workspace too small: %zu < %zu", ws_bytes, need);
+    return SP_OK;
+}
 
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    float *cs = static_cast<float *>(ws_dev);
+sp_status select_launch(const float *scores_dev, int64_t L, int32_t pool_w, int32_t chunk, int64_t k, int64_t C,
+                        int32_t *sel_chunks_dev, int64_t *spans_dev, int32_t *n_spans_dev, float *chunk_scores_dev,
+                        float *cs, hipStream_t st)
+{
     const int waves_per_block = kChunkThreads / 64;
     const unsigned grid = (unsigned)((C + waves_per_block - 1) / waves_per_block);
     hipLaunchKernelGGL(sp_chunk_kernel, dim3(grid), dim3(kChunkThreads), 0, st, scores_dev, L, (int)pool_w,
@@ -477,6 +481,74 @@ extern "C" sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_
     launch_topk(st, cs, C, k, nullptr, (int)chunk, L, sel_chunks_dev, spans_dev, n_spans_dev);
     SP_HIP_CHECK(hipGetLastError());
     return SP_OK;
+}
+
+}  // namespace
+
+extern "C" sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_w, int32_t chunk, int64_t k,
+                               int32_t *sel_chunks_dev, int64_t *spans_dev, int32_t *n_spans_dev,
+                               float *chunk_scores_dev, void *ws_dev, size_t ws_bytes, void *hip_stream)
+{
+    int64_t C = 0;
+    const sp_status rc = select_check(scores_dev, L, pool_w, chunk, k, sel_chunks_dev, spans_dev, n_spans_dev, C);
+    if (rc != SP_OK) return rc;
+    const size_t need = sp::align_up(sizeof(float) * (size_t)C, 256);
+    if (!ws_dev) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is null (%zu bytes needed)", need);
+    if ((uintptr_t)ws_dev % 256 != 0) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is not 256-byte aligned");
+    if (ws_bytes < need) return sp::fail(SP_ERR_WORKSPACE, "workspace too small: %zu < %zu", ws_bytes, need);
+    return select_launch(scores_dev, L, pool_w, chunk, k, C, sel_chunks_dev, spans_dev, n_spans_dev, chunk_scores_dev,
+                         static_cast<float *>(ws_dev), static_cast<hipStream_t>(hip_stream));
+}
+
+// ---------------------------------------------------------------------------
+// sp_select without a workspace argument, for callers that cannot allocate: the
+// chunk scores go to a device array that is part of the library's image.
+// ---------------------------------------------------------------------------
+constexpr int64_t kStaticChunks = SP_SELECT_STATIC_MAX_CHUNKS;
+static __device__ __align__(256) float scratch[kStaticChunks];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+// Device address of `scratch` on each device, resolved once per device with that device current.
+// (In host code the array's name only stands for the symbol; it is not a device address.)
+std::atomic<float *> g_scratch[kMaxDevices];
+
+sp_status scratch_of_current_device(float *&out)
+{
+    int dev = -1;
+    SP_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return sp::fail(SP_ERR_UNSUPPORTED, "device index %d (supported: < %d)", dev, kMaxDevices);
+    float *p = g_scratch[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        SP_HIP_CHECK(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+        if (!sym) return sp::fail(SP_ERR_DEVICE, "the library's scratch array has no address on device %d", dev);
+        p = static_cast<float *>(sym);
+        g_scratch[dev].store(p, std::memory_order_release);     // every thread resolves the same address
+    }
+    out = p;
+    return SP_OK;
+}
+
+}  // namespace
+
+extern "C" sp_status sp_select_static(const float *scores_dev, int64_t L, int32_t pool_w, int32_t chunk, int64_t k,
+                                      int32_t *sel_chunks_dev, int64_t *spans_dev, int32_t *n_spans_dev,
+                                      float *chunk_scores_dev, void *hip_stream)
+{
+    int64_t C = 0;
+    const sp_status rc = select_check(scores_dev, L, pool_w, chunk, k, sel_chunks_dev, spans_dev, n_spans_dev, C);
+    if (rc != SP_OK) return rc;
+    if (C > kStaticChunks)
+        return sp::fail(SP_ERR_UNSUPPORTED, "%lld chunks exceed the %lld the library's own scratch array holds; use sp_select",
+                        (long long)C, (long long)kStaticChunks);
+    float *cs = nullptr;
+    const sp_status rs = scratch_of_current_device(cs);
+    if (rs != SP_OK) return rs;
+    // every chunk score the top-k kernel reads is written by the chunk kernel of this call: nothing to clear
+    return select_launch(scores_dev, L, pool_w, chunk, k, C, sel_chunks_dev, spans_dev, n_spans_dev, chunk_scores_dev, cs,
+                         static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" sp_status sp_select_budget_workspace(int64_t L, int32_t chunk, size_t *bytes)

@@ -170,6 +170,20 @@ def test_select_argument_errors():
         assert e.value.status == status, kw
 
 
+def test_select_static_argument_errors():
+    fake = 0x1000
+
+    def call(L=1000, pool=13, chunk=32, k=4, scores=fake, sel=fake, spans=fake, ns=fake):
+        sp.sp_select_static(scores, L, pool, chunk, k, sel, spans, ns, None, stream=0)
+
+    for kw, status in [(dict(scores=None), 1), (dict(sel=None), 1), (dict(spans=None), 1), (dict(ns=None), 1),
+                       (dict(L=0), 1), (dict(chunk=0), 1), (dict(pool=12), 1), (dict(pool=131), 2), (dict(k=0), 1),
+                       (dict(k=33), 1), (dict(L=(1 << 18) + 1, chunk=1), 2)]:
+        with pytest.raises(sp.SpError) as e:
+            call(**kw)
+        assert e.value.status == status, kw
+
+
 def test_project_argument_errors():
     fake = 0x1000
 
