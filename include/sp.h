@@ -60,7 +60,12 @@ typedef enum { SP_LAYER_MEAN = 0, SP_LAYER_MAX = 1 } sp_layer_agg;
  * elements, multiples of 8; layer base pointers 16-byte aligned). Query head h
  * reads kv head h / (n_q_heads / n_kv_heads).
  * Supported: head_dim 64 or 128; 1 <= n_q <= 16; n_q_heads a multiple of
- * n_kv_heads with ratio <= 16; n_layers <= 128; scale finite and > 0. */
+ * n_kv_heads with ratio G <= 16; n_layers <= 128; n_layers * n_kv_heads <=
+ * 65535; scale finite and > 0; and the kv head's query group must fit the
+ * on-chip staging: with R = 32 * ceil(G/4) * ceil(n_q/8) padded query rows,
+ * R <= 224 at head_dim 64 and R <= 96 at head_dim 128 (so G = 16 with
+ * n_q > 8 at head_dim 64, and G > 12 or G > 4 with n_q > 8 at head_dim 128,
+ * are SP_ERR_UNSUPPORTED). */
 typedef struct {
     int32_t n_layers;
     int32_t n_q_heads;
@@ -74,7 +79,11 @@ typedef struct {
 } sp_score_desc;
 
 /* Bytes of workspace sp_score / sp_score_batch need for `total_tokens` prompt
- * tokens in `n_prompts` prompts (upper bound; 1 prompt for sp_score). */
+ * tokens in `n_prompts` prompts (upper bound; 1 prompt for sp_score).
+ * The first 32-bit word of the workspace is the status word of the last score
+ * call that used it: once the stream has been synchronised it reads 0 when the
+ * scores are valid and 1 when the single-launch kernel gave up (see sp_score);
+ * a caller that cannot scan the scores for NaN can copy this word back. */
 sp_status sp_score_workspace(const sp_score_desc *desc, int64_t total_tokens,
                              int32_t n_prompts, size_t *bytes);
 
@@ -94,8 +103,9 @@ sp_status sp_score_workspace(const sp_score_desc *desc, int64_t total_tokens,
  * The single-launch kernel (see sp_score_is_fused) needs all its workgroups
  * resident at once, which an otherwise idle device guarantees; if other work
  * occupies the device, its waits on other workgroups are bounded (about a
- * second), after which every score of the call is NaN: it never hangs, and a
- * NaN score means "run again", never a wrong value.
+ * second), after which the call has failed as a whole: every score of the call
+ * is NaN and the workspace's status word (see sp_score_workspace) is 1. It
+ * never hangs, and a failed call means "run again", never a wrong value.
  */
 sp_status sp_score(const sp_score_desc *desc, const void *q_dev,
                    const void *const *k_layers_host, int64_t L,
@@ -299,6 +309,13 @@ sp_status sp_assemble(const int32_t *target_ids_dev, int64_t M,
                       int32_t *out_ids_dev, int32_t *out_pos_dev,
                       int64_t *out_src_dev, int64_t *out_len_dev,
                       void *ws_dev, size_t ws_bytes, void *hip_stream);
+
+/* Test hook for the failure path of the single-launch score kernel; not for
+ * production use. Launches that follow give a wait up after `spin_limit` polls
+ * (default 1 << 20), and with force_miss != 0 the waves that combine partial
+ * results treat them as never arriving, so that the bounded waits give up on an
+ * idle device and every kernel still runs to its end. Process-wide. */
+void sp_debug_fused_giveup(uint32_t spin_limit, int32_t force_miss);
 
 /* Description of the last error raised on the calling thread ("" if none).
  * The string lives in thread-local storage owned by the library. */

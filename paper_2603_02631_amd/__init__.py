@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     load_library,
     sp_assemble,
     sp_assemble_workspace,
+    sp_debug_fused_giveup,
     sp_keep_count,
     sp_last_error,
     sp_project,

@@ -22,6 +22,7 @@ _LIB_PATH = os.path.join(_PKG_DIR, "libsp_amd.so")
 EXPORTS = (
     "sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_is_fused", "sp_score_batch", "sp_keep_count", "sp_select_workspace",
     "sp_select", "sp_select_static", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble", "sp_last_error", "sp_version",
+    "sp_debug_fused_giveup",
 )
 
 
@@ -85,6 +86,8 @@ def load_library():
     lib.sp_project.argtypes = [P, c.c_int64, P, c.c_int64, P, P, c.c_int32, P, P, P, P, P]
     lib.sp_assemble_workspace.argtypes = [c.c_int32, c.POINTER(c.c_size_t)]
     lib.sp_assemble.argtypes = [P, c.c_int64, P, P, c.c_int32, P, c.c_int32, c.c_int64, P, P, P, P, P, c.c_size_t, P]
+    lib.sp_debug_fused_giveup.argtypes = [c.c_uint32, c.c_int32]
+    lib.sp_debug_fused_giveup.restype = None
     lib.sp_last_error.restype = c.c_char_p
     lib.sp_version.restype = c.c_char_p
     for name in ("sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_is_fused", "sp_score_batch", "sp_select_workspace", "sp_select",
@@ -123,6 +126,11 @@ def sp_last_error() -> str:
 
 def sp_version() -> str:
     return load_library().sp_version().decode()
+
+
+def sp_debug_fused_giveup(spin_limit: int = 1 << 20, force_miss: int = 0) -> None:
+    """Test hook: see ``sp_debug_fused_giveup`` in ``include/sp.h``."""
+    load_library().sp_debug_fused_giveup(int(spin_limit), int(force_miss))
 
 
 def sp_keep_count(n_chunks: int, keep_num: int, keep_den: int) -> int:

@@ -58,6 +58,7 @@ struct ScoreArgs {
     float2 *part;             // [n_phases][n_tiles][rows_pad]
     float *lse_neg;           // [B][n_phases][rows_pad]  (-lse in raw-logit units, permuted)
     float *scores;
+    uint32_t *status;         // the call's status word (cleared here: this path cannot give up)
     const int32_t *block_table;   // paged keys (single prompt): token j lives in page block_table[j / page_tokens]
     int64_t page_tokens;          // of its layer's pool, page p at element offset p * page_stride; null: contiguous
     int64_t page_stride;
@@ -168,6 +169,7 @@ __global__ __launch_bounds__(kThreads, 4) void sp_stats_kernel(ScoreArgs a, Laye
     const int tile = blockIdx.x, phase = blockIdx.y;
     const int layer = phase / a.n_kv_heads, kv = phase - layer * a.n_kv_heads;
     const TileInfo ti = get_tile(a, tile, TILE);
+    if (tile == 0 && phase == 0 && tid == 0) *a.status = 0u;
 
     stage_q<D>(qs, a, ti.prompt, layer, kv, tid);
     stage_k<D, NS>(ks, key_base(a, kp, layer, kv, ti), a.k_stride_token, ti.j0, ti.end, tid);
@@ -542,6 +544,8 @@ sp_status make_plan(const sp_score_desc *d, Plan &p)
     p.rows_pad = p.NB * p.n_gblk * 32;
     p.tile_keys = kWaves * p.NS * 32;
     p.n_phases = d->n_layers * d->n_kv_heads;
+    if (p.n_phases > 65535)
+        return sp::fail(SP_ERR_UNSUPPORTED, "desc: %d (layer, kv head) pairs (supported: <= 65535)", p.n_phases);
     p.n_layers = d->n_layers;
     p.layer_agg = d->layer_agg;
     p.lds_bytes = (size_t)p.tile_keys * p.D * 2 + (size_t)p.rows_pad * p.D * 2 + (size_t)p.rows_pad * 4;
@@ -552,7 +556,7 @@ sp_status make_plan(const sp_score_desc *d, Plan &p)
 }
 
 struct WsLayout {
-    size_t part, lse, tiles, prompt_tiles, split, look, fused, total;
+    size_t status, part, lse, tiles, prompt_tiles, split, look, fused, total;
 };
 
 // Shapes the fused single-launch kernel can hold on chip (any L; the length test is separate).
@@ -591,6 +595,7 @@ WsLayout ws_layout(const Plan &p, int64_t n_tiles, int n_prompts)
 {
     WsLayout w;
     size_t off = 0;
+    w.status = off; off += 256;           // the call's status word leads the workspace (see sp.h)
     w.part = off;  off = sp::align_up(off + sizeof(float2) * (size_t)p.n_phases * (size_t)n_tiles * p.rows_pad, 256);
     w.lse = off;   off = sp::align_up(off + sizeof(float) * (size_t)n_prompts * p.n_phases * p.rows_pad, 256);
     w.tiles = off; off = sp::align_up(off + sizeof(TileInfo) * (size_t)n_tiles, 256);
@@ -704,6 +709,7 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
     a.part = reinterpret_cast<float2 *>(ws + w.part);
     a.lse_neg = reinterpret_cast<float *>(ws + w.lse);
     a.scores = scores_dev;
+    a.status = reinterpret_cast<uint32_t *>(ws + w.status);
     a.split_buf = reinterpret_cast<float *>(ws + w.split);
     a.layers_per_split = prob_layers_per_split(p, n_tiles);
     a.n_splits = prob_splits(p, n_tiles);
@@ -752,7 +758,7 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
             f.n_nblk = a.n_nblk; f.n_gblk = a.n_gblk; f.rows_pad = a.rows_pad;
             f.layer_agg = a.layer_agg;
             f.c = a.c; f.inv_c = a.inv_c; f.out_scale = a.out_scale;
-            return sp_fused::launch(f, kp, ws + w.fused, st);
+            return sp_fused::launch(f, kp, ws + w.fused, a.status, st);
         }
     }
     if (batch) {
@@ -782,6 +788,11 @@ extern "C" sp_status sp_score_workspace(const sp_score_desc *desc, int64_t total
     const int64_t n_tiles = (total_tokens + p.tile_keys - 1) / p.tile_keys + n_prompts;
     *bytes = ws_layout(p, n_tiles, n_prompts).total;
     return SP_OK;
+}
+
+extern "C" void sp_debug_fused_giveup(uint32_t spin_limit, int32_t force_miss)
+{
+    sp_fused::set_giveup(spin_limit, force_miss);
 }
 
 extern "C" int32_t sp_score_is_fused(const sp_score_desc *desc, int64_t L)

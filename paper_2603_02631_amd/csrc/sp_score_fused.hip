@@ -37,8 +37,14 @@
 // carries the parity of the slot's use; normalisers carry the phase number),
 // and all waits are bounded. The grid never exceeds the number of compute units
 // (one workgroup fits per unit), so every workgroup is resident on an idle device.
+// A wait that gives up makes the whole call fail: the workgroup raises the
+// call's status word at once, a duty that could not be completed publishes a
+// poison entry that fails every workgroup reading it, and every workgroup
+// reads the status word before it stores its scores (once any workgroup has
+// passed that point all exchanged data is out, so none can fail after it).
 #include "sp_score_fused.hpp"
 
+#include <atomic>
 #include <cstring>
 
 namespace {
@@ -58,11 +64,11 @@ constexpr int kLag = 3;                   // phases between statistics and proba
 constexpr int kRing = kLag + 1;           // fragment ring: four phases
 constexpr int kSlots = sp_fused::kSlots;  // exchange ring depth
 constexpr int kMaxRowsF = sp_fused::kMaxRows;   // 64 padded query rows per kv head
-constexpr unsigned kSpinMax = 1u << 20;    // polls before a wait gives up (about a second)
 constexpr int kPubWave = 0;                // the wave that publishes this workgroup's partials
 constexpr int kDutyWave = 1;               // the wave that combines this workgroup's duty rows
 constexpr int kDutyRows = 4;               // consecutive query rows one duty covers (32 bytes per source workgroup)
 constexpr int kLseWave = 2;                // the wave that fetches the normalisers
+constexpr uint32_t kPoisonTag = 0xffffffffu;   // normaliser entry of a duty that gave up
 
 // LDS map in bytes. Everything but the K transit ring sits below 64 KB, so that reads of it can
 // carry the buffer's place in the instruction's offset field.
@@ -602,6 +608,14 @@ __device__ __forceinline__ bool duty_ready(const DutyBlock &d, uint32_t par, int
     return ok != 0;
 }
 
+// A wait gave up (or met a poison entry): the workgroup stops waiting for anything and the call's
+// status word is raised at once, so that every workgroup finds it before storing its scores.
+__device__ __forceinline__ void raise_failure(const FusedArgs &a, int *fail)
+{
+    *fail = 1;
+    __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Uniform state that walks along with the steps.
 struct Walk {
     PhaseCtr k;       // phase s + 1: next statistics pass (its K tile is being fetched)
@@ -764,16 +778,18 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
                 const uint64_t *src = a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad + duty_blk * kDutyRows;
                 // fast path: the partials requested at the start of this step are all there; otherwise poll (bounded)
                 DutyBlock de = read_duty_staging(lds0, lane);
-                if (__any(!duty_ready(de, par, lane, a.n_wg, row_mask)) && *fail == 0) {
+                bool ready = !__any(!duty_ready(de, par, lane, a.n_wg, row_mask)) && a.force_miss == 0;
+                if (!ready && *fail == 0) {
                     unsigned spins = 0;
                     do {
-                        if (++spins > kSpinMax) { *fail = 1; break; }
+                        if (++spins > a.spin_max) { raise_failure(a, fail); break; }
 #pragma unroll
                         for (int r = 0; r < kDutyRows; ++r)
 #pragma unroll
                             for (int q = 0; q < 4; ++q)
                                 de.e[r][q] = ld64(src + (size_t)min(lane + 64 * q, a.n_wg - 1) * a.rows_pad + r);
-                    } while (__any(!duty_ready(de, par, lane, a.n_wg, row_mask)));
+                        ready = !__any(!duty_ready(de, par, lane, a.n_wg, row_mask)) && a.force_miss == 0;
+                    } while (!ready);
                 }
                 // per row: maximum first, then one exponential per partial (short dependency chains, fixed order)
                 float mine = 0.f;       // lane r keeps the normaliser of row r of the block
@@ -795,9 +811,12 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
                     const float v = -(m + fast_log2(l) * a.inv_c);
                     if (lane == r) mine = v;
                 }
+                // a duty that could not be completed (now or because the workgroup has failed before)
+                // publishes poison: whoever reads it fails too instead of using a wrong normaliser
+                const uint32_t tag = (ready && *fail == 0) ? (uint32_t)(pd + 1) : kPoisonTag;
                 if (lane < kDutyRows && ((row_mask >> lane) & 1u))
                     st64(a.lse + (size_t)(pd % kSlots) * a.rows_pad + duty_blk * kDutyRows + lane,
-                         (uint64_t)__float_as_uint(mine) | ((uint64_t)(uint32_t)(pd + 1) << 32));
+                         (uint64_t)__float_as_uint(mine) | ((uint64_t)tag << 32));
             }
         }
     } else if (wave == kLseWave) {
@@ -809,10 +828,10 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
                 uint64_t entry = read_lse_staging(lds0, lane);
                 if ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1) && *fail == 0) {
                     unsigned spins = 0;
-                    do {
-                        if (++spins > kSpinMax) { *fail = 1; break; }
+                    while ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1)) {
+                        if ((uint32_t)(entry >> 32) == kPoisonTag || ++spins > a.spin_max) { raise_failure(a, fail); break; }
                         entry = ld64(src);
-                    } while ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1));
+                    }
                 }
                 v = __uint_as_float((uint32_t)entry);
                 if (EXTRA && a.look != nullptr) {
@@ -986,8 +1005,8 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     }
     vm_wait<0>();               // no direct-to-LDS load may outlive the workgroup
     lds_barrier();
-    const bool failed = *reinterpret_cast<int *>(lds + kOffFail) != 0;
-    if (failed && tid == 0) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // the call has failed if any workgroup raised the status word; this workgroup's own failures are in it
+    const bool failed = __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
 #pragma unroll
     for (int s = 0; s < kNS; ++s) {
         const float both = acc.total[s] + __shfl_xor(acc.total[s], 32);
@@ -996,20 +1015,32 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     }
 }
 
-// Clears the exchange area: a zero sum marks a partial as not yet written and
+// Clears the exchange area and the status word: a zero sum marks a partial as not yet written and
 // phase numbers start at 1, so zero normaliser entries are never taken as ready.
-__global__ void sp_fused_clear_kernel(uint64_t *p, size_t n)
+__global__ void sp_fused_clear_kernel(uint64_t *p, size_t n, uint32_t *err)
 {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *err = 0u;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
 }
+
+// Test hook (see sp_debug_fused_giveup): polls before a wait gives up, and whether duty waves treat
+// their partials as never arriving.
+std::atomic<uint32_t> g_spin_max{1u << 20};     // about a second
+std::atomic<int32_t> g_force_miss{0};
 
 }  // namespace
 
 namespace sp_fused {
 
+void set_giveup(uint32_t spin_max, int32_t force_miss)
+{
+    g_spin_max.store(spin_max, std::memory_order_relaxed);
+    g_force_miss.store(force_miss, std::memory_order_relaxed);
+}
+
 size_t workspace_bytes(int rows_pad, int n_wg)
 {
-    return sp::align_up(sizeof(uint64_t) * ((size_t)kSlots * rows_pad * n_wg + (size_t)kSlots * rows_pad + 32), 256);
+    return sp::align_up(sizeof(uint64_t) * ((size_t)kSlots * rows_pad * n_wg + (size_t)kSlots * rows_pad), 256);
 }
 
 bool fits_one_per_cu()
@@ -1020,22 +1051,23 @@ bool fits_one_per_cu()
     return n1 >= 1 && n2 >= 1;
 }
 
-sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, hipStream_t st)
+sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, uint32_t *status_word, hipStream_t st)
 {
     uint64_t *base = static_cast<uint64_t *>(ws);
     const size_t n_part = (size_t)kSlots * a.rows_pad * a.n_wg, n_lse = (size_t)kSlots * a.rows_pad;
     a.part = base;
     a.lse = base + n_part;
-    a.err = reinterpret_cast<uint32_t *>(base + n_part + n_lse);
-    a.zeros = base + n_part + n_lse + 16;          // 128 bytes of zeros for padding query rows
-    const size_t n_clear = n_part + n_lse + 32;
+    a.err = status_word;
+    a.spin_max = g_spin_max.load(std::memory_order_relaxed);
+    a.force_miss = g_force_miss.load(std::memory_order_relaxed);
+    const size_t n_clear = n_part + n_lse;
     hipLaunchKernelGGL(sp_fused_clear_kernel, dim3((unsigned)((n_clear + 255) / 256 > 1024 ? 1024 : (n_clear + 255) / 256)),
-                       dim3(256), 0, st, base, n_clear);
+                       dim3(256), 0, st, base, n_clear, status_word);
     SP_HIP_CHECK(hipGetLastError());
     // Every workgroup must be resident for the exchange to make progress: one workgroup fits per
     // compute unit (LDS), so the grid may not exceed the number of compute units. All waits in the
     // kernel are bounded; should residency fail (the device shared with other work), the call ends
-    // with NaN scores and the error word set instead of hanging.
+    // with NaN scores and the status word set instead of hanging.
     const bool extra = a.look != nullptr || a.block_table != nullptr;
     const dim3 grid(a.n_wg), block(kFThreads);
     // the fixed-model instantiations apply when every folded constant equals the call's value

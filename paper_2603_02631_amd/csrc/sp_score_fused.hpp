@@ -17,13 +17,14 @@ struct FusedArgs {
     int64_t L;
     uint64_t *part;              // [kSlots][n_wg][rows_pad]  (max, sum exp) partials, parity in bit 63
     uint64_t *lse;               // [kSlots][rows_pad]        (-lse, phase + 1)
-    uint32_t *err;
+    uint32_t *err;               // the call's status word: raised by any workgroup whose bounded wait gave up
+    uint32_t spin_max;           // polls before a wait gives up
+    int32_t force_miss;          // test hook: duty waves treat their partials as never arriving
     const float *look;           // [n_phases][rows_pad] log-sum-exp of each row over its visible lookahead keys
                                  // (raw-logit units, -inf for none), or null: prompt keys only
     const int32_t *block_table;  // paged keys: token j of a layer sits in page block_table[j / page_tokens] of that
     int64_t page_tokens;         // layer's pool, page p at element offset p * page_stride; null: contiguous keys
     int64_t page_stride;
-    const uint64_t *zeros;       // 128 zero bytes (source of padding query rows)
     float *scores;
     int32_t n_wg;
     int32_t n_layers, n_q_heads, n_kv_heads, group, n_q;
@@ -37,7 +38,12 @@ size_t workspace_bytes(int rows_pad, int n_wg);
 // True when the device can hold one workgroup of the fused kernel per compute unit.
 bool fits_one_per_cu();
 
-// Enqueues the clear kernel and the fused kernel. `ws` must hold workspace_bytes().
-sp_status launch(FusedArgs a, const sp_dev::LayerPtrs &kp, void *ws, hipStream_t st);
+// Enqueues the clear kernel and the fused kernel. `ws` must hold workspace_bytes(); `status_word`
+// (device) is cleared first and raised if the call gives up.
+sp_status launch(FusedArgs a, const sp_dev::LayerPtrs &kp, void *ws, uint32_t *status_word, hipStream_t st);
+
+// Test hook: polls before a bounded wait gives up (default 2^20) and whether duty waves treat their
+// partials as never arriving; applies to launches that follow.
+void set_giveup(uint32_t spin_max, int32_t force_miss);
 
 }  // namespace sp_fused

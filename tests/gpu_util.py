@@ -29,7 +29,13 @@ def make_desc(n_layers, H, Hkv, d, n_q, scale, layer_agg, layout, T) -> sp.Score
 
 
 def workspace(nbytes: int) -> torch.Tensor:
-    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=DEV)
+    # filled with ones so that a status word nobody cleared reads as non-zero
+    return torch.full((max(nbytes, 256),), 0xFF, dtype=torch.uint8, device=DEV)
+
+
+def status_word(ws: torch.Tensor) -> int:
+    """The 32-bit status word that leads a score workspace (0 = the scores are valid)."""
+    return int(ws[:4].cpu().numpy().view(np.uint32)[0])
 
 
 def gpu_score(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], scale: float, layer_agg: int = 0,
@@ -47,6 +53,7 @@ def gpu_score(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], scale: float, 
     scores = torch.full((max(L, 1),), float("nan"), dtype=torch.float32, device=DEV)
     sp.sp_score(desc, qd, kd, L, scores, ws)
     torch.cuda.synchronize()
+    assert status_word(ws) == 0 or L == 0
     return scores[:L].cpu().numpy()
 
 
@@ -67,6 +74,7 @@ def gpu_score_look(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], k_look: n
     scores = torch.full((max(L, 1),), float("nan"), dtype=torch.float32, device=DEV)
     sp.sp_score_look(desc, qd, kd, L, kl, look_self, scores, ws)
     torch.cuda.synchronize()
+    assert status_word(ws) == 0
     return scores[:L].cpu().numpy()
 
 
@@ -104,6 +112,7 @@ def gpu_score_paged(q_bits: np.ndarray, pools: Sequence[np.ndarray], table: np.n
     scores = torch.full((max(L, 1),), float("nan"), dtype=torch.float32, device=DEV)
     sp.sp_score_paged(desc, qd, pd, td, page_tokens, Hkv * page_tokens * d, L, scores, ws)
     torch.cuda.synchronize()
+    assert status_word(ws) == 0
     return scores[:L].cpu().numpy()
 
 
@@ -121,6 +130,7 @@ def gpu_score_batch(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], offsets:
     scores = torch.full((max(T, 1),), float("nan"), dtype=torch.float32, device=DEV)
     sp.sp_score_batch(desc, qd, kd, [int(v) for v in offsets], off_d, scores, ws)
     torch.cuda.synchronize()
+    assert status_word(ws) == 0 or T == 0
     return scores[:T].cpu().numpy()
 
 

@@ -58,6 +58,12 @@ def good_desc(**kw):
     (dict(head_dim=96), 2), (dict(n_q=17), 2), (dict(n_layers=129), 2),
     (dict(n_q_heads=34, n_kv_heads=2), 2),
     (dict(n_q_heads=32, n_kv_heads=2, n_q=16, head_dim=128, k_stride_token=128), 2),
+    # query groups beyond the on-chip staging: 16 heads x 16 rows at head_dim 64, 8 heads x 16 rows at head_dim 128
+    (dict(n_q_heads=32, n_kv_heads=2, n_q=16), 2),
+    (dict(n_q_heads=16, n_kv_heads=2, n_q=16, head_dim=128, k_stride_token=128), 2),
+    (dict(n_q_heads=16, n_kv_heads=1, n_q=8, head_dim=128, k_stride_token=128), 2),
+    # more (layer, kv head) pairs than a launch dimension holds
+    (dict(n_layers=128, n_q_heads=512, n_kv_heads=512), 2),
 ])
 def test_score_desc_validation(kw, status):
     with pytest.raises(sp.SpError) as e:

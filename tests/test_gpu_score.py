@@ -189,6 +189,40 @@ def test_fused_score_matches_oracle(shape):
     assert got_nhd.tobytes() == got.tobytes()        # same keys through token-major strides
 
 
+def test_fused_score_gives_up_as_a_whole():
+    """The bounded waits of the single-launch kernel, driven to give up from the host (the test hook
+    makes the combining waves treat their partial results as never arriving, with a spin limit of a few
+    polls, so every kernel still runs to its end): all scores NaN, status word 1; the next ordinary
+    call on the same workspace is valid again."""
+    import torch
+    import paper_2603_02631_amd as sp
+    from gpu_util import DEV, dev_bits, make_desc, status_word, workspace
+    Lyr, H, Hkv, d, n_q, L = 2, 8, 2, 64, 16, 40000
+    w = small_workload("fused_give_up", Lyr, H, Hkv, d, n_q, L, cfg_id=290, hh=(1, 1000))
+    inp = synth.make_score_inputs(w)
+    desc = make_desc(Lyr, H, Hkv, d, n_q, w.scale, 0, "HND", L)
+    assert sp.sp_score_is_fused(desc, L) == 1
+    qd = dev_bits(inp["q"][0])
+    kd = [dev_bits(k) for k in inp["k"]]
+    ws = workspace(sp.sp_score_workspace(desc, L, 1))
+    scores = torch.zeros(L, dtype=torch.float32, device=DEV)
+    say("[score-fused] give-up path: spin limit 4, partials treated as missing")
+    try:
+        sp.sp_debug_fused_giveup(4, 1)
+        sp.sp_score(desc, qd, kd, L, scores, ws)
+        torch.cuda.synchronize()
+    finally:
+        sp.sp_debug_fused_giveup(1 << 20, 0)
+    assert status_word(ws) == 1
+    assert bool(torch.isnan(scores).all())
+    say("[score-fused] ordinary call on the same workspace")
+    sp.sp_score(desc, qd, kd, L, scores, ws)
+    torch.cuda.synchronize()
+    assert status_word(ws) == 0
+    from gpu_util import assert_scores_close
+    assert_scores_close(scores.cpu().numpy(), oracle.score(inp["q"][0], inp["k"], w.scale, 0))
+
+
 LOOK_SHAPES = [
     # name, Lyr, H, Hkv, d, n_q, L   (general path: short prompts, head_dim 128; fused path: long prompts)
     ("look_g4_nq16_d64", 3, 8, 2, 64, 16, 1500),
