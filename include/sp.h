@@ -310,6 +310,20 @@ sp_status sp_assemble(const int32_t *target_ids_dev, int64_t M,
                       int64_t *out_src_dev, int64_t *out_len_dev,
                       void *ws_dev, size_t ws_bytes, void *hip_stream);
 
+/*
+ * Measurement aid: streams `bytes` bytes of buf_dev (device, 16-byte aligned,
+ * bytes a positive multiple of 16) with plain wide loads and XORs what it read
+ * into *sink_dev (device, 64 bits: lanes fold their 16-byte chunks to 64 bits
+ * as (x ^ z) << 32 | (y ^ w) of the four 32-bit words; not cleared first).
+ * The rate at which this call reads is the device's achievable streaming-read
+ * bandwidth: the practical ceiling, next to the datasheet figure, for
+ * sp_score, which streams the K cache once (Appendix A.1.1's attention of the
+ * lookahead rows over the whole prompt). Enqueued on hip_stream like every
+ * other call.
+ */
+sp_status sp_hbm_read_probe(const void *buf_dev, size_t bytes, uint64_t *sink_dev,
+                            void *hip_stream);
+
 /* Test hook for the failure path of the single-launch score kernel; not for
  * production use. Launches that follow give a wait up after `spin_limit` polls
  * (default 1 << 20), and with force_miss != 0 the waves that combine partial

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     sp_assemble,
     sp_assemble_workspace,
     sp_debug_fused_giveup,
+    sp_hbm_read_probe,
     sp_keep_count,
     sp_last_error,
     sp_project,

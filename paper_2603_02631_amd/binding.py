@@ -22,7 +22,7 @@ _LIB_PATH = os.path.join(_PKG_DIR, "libsp_amd.so")
 EXPORTS = (
     "sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_is_fused", "sp_score_batch", "sp_keep_count", "sp_select_workspace",
     "sp_select", "sp_select_static", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble", "sp_last_error", "sp_version",
-    "sp_debug_fused_giveup",
+    "sp_debug_fused_giveup", "sp_hbm_read_probe",
 )
 
 
@@ -86,6 +86,8 @@ def load_library():
     lib.sp_project.argtypes = [P, c.c_int64, P, c.c_int64, P, P, c.c_int32, P, P, P, P, P]
     lib.sp_assemble_workspace.argtypes = [c.c_int32, c.POINTER(c.c_size_t)]
     lib.sp_assemble.argtypes = [P, c.c_int64, P, P, c.c_int32, P, c.c_int32, c.c_int64, P, P, P, P, P, c.c_size_t, P]
+    lib.sp_hbm_read_probe.argtypes = [P, c.c_size_t, P, P]
+    lib.sp_hbm_read_probe.restype = c.c_int
     lib.sp_debug_fused_giveup.argtypes = [c.c_uint32, c.c_int32]
     lib.sp_debug_fused_giveup.restype = None
     lib.sp_last_error.restype = c.c_char_p
@@ -102,13 +104,35 @@ def _check(status: int) -> None:
         raise SpError(status, sp_last_error())
 
 
-def _ptr(t) -> Optional[int]:
-    """Device (or host) address of a tensor; None passes NULL."""
+def _ptr(t, what: str = "buffer", nbytes: int = 0) -> Optional[int]:
+    """Device address of a tensor; None passes NULL, an int is taken as a raw address.
+
+    A tensor is checked before its address leaves Python: it has to live on the GPU, be contiguous
+    and hold at least ``nbytes`` bytes (what the call will read or write), so that a short or
+    host-side buffer becomes an :class:`SpError` instead of an out-of-bounds device access."""
     if t is None:
         return None
     if isinstance(t, int):
         return t
+    if not getattr(t, "is_cuda", False):
+        raise SpError(1, f"{what} is not a device tensor")
+    if not t.is_contiguous():
+        raise SpError(1, f"{what} is not contiguous")
+    have = t.numel() * t.element_size()
+    if have < nbytes:
+        raise SpError(1, f"{what} holds {have} bytes, the call needs {nbytes}")
     return t.data_ptr()
+
+
+def _q_bytes(desc: "ScoreDesc", n_prompts: int = 1) -> int:
+    return n_prompts * desc.n_layers * desc.n_q_heads * desc.n_q * desc.head_dim * 2
+
+
+def _k_bytes(desc: "ScoreDesc", tokens: int) -> int:
+    """Bytes a layer's K buffer must hold for `tokens` tokens under the desc's strides."""
+    if tokens <= 0:
+        return 0
+    return ((desc.n_kv_heads - 1) * desc.k_stride_head + (tokens - 1) * desc.k_stride_token + desc.head_dim) * 2
 
 
 def _stream(stream) -> Optional[int]:
@@ -133,6 +157,10 @@ def sp_debug_fused_giveup(spin_limit: int = 1 << 20, force_miss: int = 0) -> Non
     load_library().sp_debug_fused_giveup(int(spin_limit), int(force_miss))
 
 
+def sp_hbm_read_probe(buf, nbytes: int, sink, stream=None) -> None:
+    _check(load_library().sp_hbm_read_probe(_ptr(buf, "buf", nbytes), nbytes, _ptr(sink, "sink", 8), _stream(stream)))
+
+
 def sp_keep_count(n_chunks: int, keep_num: int, keep_den: int) -> int:
     return int(load_library().sp_keep_count(n_chunks, keep_num, keep_den))
 
@@ -147,36 +175,51 @@ def sp_score_is_fused(desc: ScoreDesc, L: int) -> int:
     return int(load_library().sp_score_is_fused(ctypes.byref(desc), L))
 
 
-def _layer_array(k_layers: Sequence):
-    return (ctypes.c_void_p * len(k_layers))(*[_ptr(k) for k in k_layers])
+def _layer_array(k_layers: Sequence, nbytes: int = 0):
+    return (ctypes.c_void_p * len(k_layers))(*[_ptr(k, f"k_layers[{i}]", nbytes) for i, k in enumerate(k_layers)])
+
+
+def _ws_bytes(ws, ws_bytes: Optional[int]) -> int:
+    have = 0 if ws is None or isinstance(ws, int) else ws.numel() * ws.element_size()
+    if ws_bytes is None:
+        return have
+    if not isinstance(ws, int) and ws is not None and ws_bytes > have:
+        raise SpError(3, f"ws_bytes = {ws_bytes} exceeds the workspace tensor ({have} bytes)")
+    return ws_bytes
 
 
 def sp_score(desc: ScoreDesc, q, k_layers: Sequence, L: int, scores, ws, ws_bytes: Optional[int] = None,
              stream=None) -> None:
     if len(k_layers) != desc.n_layers:
         raise SpError(1, f"k_layers has {len(k_layers)} entries, desc.n_layers is {desc.n_layers}")
-    nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
-    _check(load_library().sp_score(ctypes.byref(desc), _ptr(q), _layer_array(k_layers), L, _ptr(scores), _ptr(ws),
-                                   nbytes, _stream(stream)))
+    nbytes = _ws_bytes(ws, ws_bytes)
+    _check(load_library().sp_score(ctypes.byref(desc), _ptr(q, "q", _q_bytes(desc)),
+                                   _layer_array(k_layers, _k_bytes(desc, L)), L, _ptr(scores, "scores", 4 * max(L, 0)),
+                                   _ptr(ws, "ws"), nbytes, _stream(stream)))
 
 
 def sp_score_look(desc: ScoreDesc, q, k_layers: Sequence, L: int, k_look, look_self: int, scores, ws,
                   ws_bytes: Optional[int] = None, stream=None) -> None:
     if len(k_layers) != desc.n_layers:
         raise SpError(1, f"k_layers has {len(k_layers)} entries, desc.n_layers is {desc.n_layers}")
-    nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
-    _check(load_library().sp_score_look(ctypes.byref(desc), _ptr(q), _layer_array(k_layers), L, _ptr(k_look),
-                                        int(look_self), _ptr(scores), _ptr(ws), nbytes, _stream(stream)))
+    nbytes = _ws_bytes(ws, ws_bytes)
+    look_bytes = desc.n_layers * desc.n_kv_heads * desc.n_q * desc.head_dim * 2
+    _check(load_library().sp_score_look(ctypes.byref(desc), _ptr(q, "q", _q_bytes(desc)),
+                                        _layer_array(k_layers, _k_bytes(desc, L)), L, _ptr(k_look, "k_look", look_bytes),
+                                        int(look_self), _ptr(scores, "scores", 4 * max(L, 0)), _ptr(ws, "ws"), nbytes,
+                                        _stream(stream)))
 
 
 def sp_score_paged(desc: ScoreDesc, q, k_pools: Sequence, block_table, page_tokens: int, page_stride: int, L: int,
                    scores, ws, ws_bytes: Optional[int] = None, stream=None) -> None:
     if len(k_pools) != desc.n_layers:
         raise SpError(1, f"k_pools has {len(k_pools)} entries, desc.n_layers is {desc.n_layers}")
-    nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
-    _check(load_library().sp_score_paged(ctypes.byref(desc), _ptr(q), _layer_array(k_pools), _ptr(block_table),
-                                         int(page_tokens), int(page_stride), L, _ptr(scores), _ptr(ws), nbytes,
-                                         _stream(stream)))
+    nbytes = _ws_bytes(ws, ws_bytes)
+    n_pages = (max(L, 0) + page_tokens - 1) // page_tokens if page_tokens > 0 else 0
+    _check(load_library().sp_score_paged(ctypes.byref(desc), _ptr(q, "q", _q_bytes(desc)), _layer_array(k_pools),
+                                         _ptr(block_table, "block_table", 4 * n_pages), int(page_tokens),
+                                         int(page_stride), L, _ptr(scores, "scores", 4 * max(L, 0)), _ptr(ws, "ws"),
+                                         nbytes, _stream(stream)))
 
 
 def sp_score_batch(desc: ScoreDesc, q, k_layers: Sequence, offsets_host: Sequence[int], offsets_dev, scores, ws,
@@ -185,9 +228,13 @@ def sp_score_batch(desc: ScoreDesc, q, k_layers: Sequence, offsets_host: Sequenc
         raise SpError(1, f"k_layers has {len(k_layers)} entries, desc.n_layers is {desc.n_layers}")
     B = len(offsets_host) - 1
     off = (ctypes.c_int64 * (B + 1))(*[int(v) for v in offsets_host])
-    nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
-    _check(load_library().sp_score_batch(ctypes.byref(desc), _ptr(q), _layer_array(k_layers), off, _ptr(offsets_dev),
-                                         B, _ptr(scores), _ptr(ws), nbytes, _stream(stream)))
+    nbytes = _ws_bytes(ws, ws_bytes)
+    total = int(offsets_host[-1]) if B >= 0 else 0
+    _check(load_library().sp_score_batch(ctypes.byref(desc), _ptr(q, "q", _q_bytes(desc, max(B, 0))),
+                                         _layer_array(k_layers, _k_bytes(desc, total)), off,
+                                         _ptr(offsets_dev, "offsets_dev", 8 * (B + 1)), B,
+                                         _ptr(scores, "scores", 4 * max(total, 0)), _ptr(ws, "ws"), nbytes,
+                                         _stream(stream)))
 
 
 def sp_select_workspace(L: int, chunk: int) -> int:
@@ -198,15 +245,23 @@ def sp_select_workspace(L: int, chunk: int) -> int:
 
 def sp_select(scores, L: int, pool_w: int, chunk: int, k: int, sel_chunks, spans, n_spans, chunk_scores, ws,
               ws_bytes: Optional[int] = None, stream=None) -> None:
-    nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
-    _check(load_library().sp_select(_ptr(scores), L, pool_w, chunk, k, _ptr(sel_chunks), _ptr(spans), _ptr(n_spans),
-                                    _ptr(chunk_scores), _ptr(ws), nbytes, _stream(stream)))
+    nbytes = _ws_bytes(ws, ws_bytes)
+    C = (L + chunk - 1) // chunk if chunk > 0 and L > 0 else 0
+    kk = max(int(k), 0)
+    _check(load_library().sp_select(_ptr(scores, "scores", 4 * max(L, 0)), L, pool_w, chunk, k,
+                                    _ptr(sel_chunks, "sel_chunks", 4 * kk), _ptr(spans, "spans", 16 * kk),
+                                    _ptr(n_spans, "n_spans", 4), _ptr(chunk_scores, "chunk_scores", 4 * C),
+                                    _ptr(ws, "ws"), nbytes, _stream(stream)))
 
 
 def sp_select_static(scores, L: int, pool_w: int, chunk: int, k: int, sel_chunks, spans, n_spans, chunk_scores,
                      stream=None) -> None:
-    _check(load_library().sp_select_static(_ptr(scores), L, pool_w, chunk, k, _ptr(sel_chunks), _ptr(spans),
-                                           _ptr(n_spans), _ptr(chunk_scores), _stream(stream)))
+    C = (L + chunk - 1) // chunk if chunk > 0 and L > 0 else 0
+    kk = max(int(k), 0)
+    _check(load_library().sp_select_static(_ptr(scores, "scores", 4 * max(L, 0)), L, pool_w, chunk, k,
+                                           _ptr(sel_chunks, "sel_chunks", 4 * kk), _ptr(spans, "spans", 16 * kk),
+                                           _ptr(n_spans, "n_spans", 4), _ptr(chunk_scores, "chunk_scores", 4 * C),
+                                           _stream(stream)))
 
 
 def sp_select_budget_workspace(L: int, chunk: int) -> int:
@@ -218,16 +273,25 @@ def sp_select_budget_workspace(L: int, chunk: int) -> int:
 def sp_select_budget(scores, L: int, pool_w: int, chunk: int, draft_off, target_off, M: int, budget: int, sel_chunks,
                      spans, n_spans, k_out, n_kept, chunk_scores, ws, ws_bytes: Optional[int] = None,
                      stream=None) -> None:
-    nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
-    _check(load_library().sp_select_budget(_ptr(scores), L, pool_w, chunk, _ptr(draft_off), _ptr(target_off), M,
-                                           budget, _ptr(sel_chunks), _ptr(spans), _ptr(n_spans), _ptr(k_out),
-                                           _ptr(n_kept), _ptr(chunk_scores), _ptr(ws), nbytes, _stream(stream)))
+    nbytes = _ws_bytes(ws, ws_bytes)
+    C = (L + chunk - 1) // chunk if chunk > 0 and L > 0 else 0
+    _check(load_library().sp_select_budget(_ptr(scores, "scores", 4 * max(L, 0)), L, pool_w, chunk,
+                                           _ptr(draft_off, "draft_off", 8 * (max(L, 0) + 1)),
+                                           _ptr(target_off, "target_off", 8 * (max(M, 0) + 1)), M, budget,
+                                           _ptr(sel_chunks, "sel_chunks", 4 * C), _ptr(spans, "spans", 16 * C),
+                                           _ptr(n_spans, "n_spans", 4), _ptr(k_out, "k_out", 8), _ptr(n_kept, "n_kept", 8),
+                                           _ptr(chunk_scores, "chunk_scores", 4 * C), _ptr(ws, "ws"), nbytes,
+                                           _stream(stream)))
 
 
 def sp_project(draft_off, L: int, target_off, M: int, spans, n_spans, max_spans: int, tspans, n_tspans, keep_mask,
                n_kept, stream=None) -> None:
-    _check(load_library().sp_project(_ptr(draft_off), L, _ptr(target_off), M, _ptr(spans), _ptr(n_spans), max_spans,
-                                     _ptr(tspans), _ptr(n_tspans), _ptr(keep_mask), _ptr(n_kept), _stream(stream)))
+    cap = max(int(max_spans), 0)
+    _check(load_library().sp_project(_ptr(draft_off, "draft_off", 8 * (max(L, 0) + 1)), L,
+                                     _ptr(target_off, "target_off", 8 * (max(M, 0) + 1)), M,
+                                     _ptr(spans, "spans", 16 * cap), _ptr(n_spans, "n_spans", 4), max_spans,
+                                     _ptr(tspans, "tspans", 16 * cap), _ptr(n_tspans, "n_tspans", 4),
+                                     _ptr(keep_mask, "keep_mask", max(M, 0)), _ptr(n_kept, "n_kept", 8), _stream(stream)))
 
 
 def sp_assemble_workspace(max_spans: int) -> int:
@@ -238,7 +302,12 @@ def sp_assemble_workspace(max_spans: int) -> int:
 
 def sp_assemble(target_ids, M: int, tspans, n_tspans, max_spans: int, delim_ids, n_delim: int, out_capacity: int,
                 out_ids, out_pos, out_src, out_len, ws, ws_bytes: Optional[int] = None, stream=None) -> None:
-    nbytes = ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
-    _check(load_library().sp_assemble(_ptr(target_ids), M, _ptr(tspans), _ptr(n_tspans), max_spans, _ptr(delim_ids),
-                                      n_delim, out_capacity, _ptr(out_ids), _ptr(out_pos), _ptr(out_src),
-                                      _ptr(out_len), _ptr(ws), nbytes, _stream(stream)))
+    nbytes = _ws_bytes(ws, ws_bytes)
+    cap = max(int(max_spans), 0)
+    oc = max(int(out_capacity), 0)
+    _check(load_library().sp_assemble(_ptr(target_ids, "target_ids", 4 * max(M, 0)), M, _ptr(tspans, "tspans", 16 * cap),
+                                      _ptr(n_tspans, "n_tspans", 4), max_spans,
+                                      _ptr(delim_ids, "delim_ids", 4 * max(int(n_delim), 0)), n_delim, out_capacity,
+                                      _ptr(out_ids, "out_ids", 4 * oc), _ptr(out_pos, "out_pos", 4 * oc),
+                                      _ptr(out_src, "out_src", 8 * oc), _ptr(out_len, "out_len", 8), _ptr(ws, "ws"),
+                                      nbytes, _stream(stream)))

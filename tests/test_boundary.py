@@ -242,3 +242,30 @@ def test_select_budget_argument_errors():
         with pytest.raises(sp.SpError) as e:
             call(**kw)
         assert e.value.status == status, kw
+
+
+def test_binding_rejects_host_tensors_before_the_call():
+    """Tensors are checked in the binding: a host tensor never reaches the library as a device address."""
+    import torch
+    host = torch.zeros(1000, dtype=torch.float32)
+    sel = torch.zeros(4, dtype=torch.int32)
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_select(host, 1000, 13, 32, 4, sel, sel, sel, None, 0x1000, 256, stream=0)
+    assert e.value.status == 1 and "scores is not a device tensor" in e.value.message
+    d = good_desc()
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_score(d, host, [0x1000, 0x1000], 1024, 0x1000, 0x1000, 1 << 20, stream=0)
+    assert e.value.status == 1 and "q is not a device tensor" in e.value.message
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_score(d, 0x1000, [0x1000, host], 1024, 0x1000, 0x1000, 1 << 20, stream=0)
+    assert "k_layers[1]" in e.value.message
+
+
+def test_read_probe_argument_errors():
+    fake = 0x1000
+    for kw in [dict(buf=None), dict(sink=None), dict(n=0), dict(n=24), dict(buf=fake + 8)]:
+        args = dict(buf=fake, n=1024, sink=fake)
+        args.update(kw)
+        with pytest.raises(sp.SpError) as e:
+            sp.sp_hbm_read_probe(args["buf"], args["n"], args["sink"], stream=0)
+        assert e.value.status == 1, kw
