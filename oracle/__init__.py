@@ -53,6 +53,12 @@ def _load():
                                     c.c_int, c.c_int64, c.c_double, c.c_int, P]
     lib.sp_oracle_score_look.argtypes = [P, P, c.c_int64, c.c_int64, c.c_int, c.c_int, c.c_int, c.c_int,
                                          c.c_int, c.c_int64, c.c_double, c.c_int, P, c.c_int, P]
+    lib.sp_oracle_e4m3_to_f64.argtypes = [c.c_uint8]
+    lib.sp_oracle_e4m3_to_f64.restype = c.c_double
+    lib.sp_oracle_logits_layer_fp8.argtypes = [P, P, c.c_int64, c.c_int64, c.c_int, c.c_int, c.c_int,
+                                               c.c_int, c.c_int64, P, c.c_double, P]
+    lib.sp_oracle_score_fp8.argtypes = [P, P, c.c_int64, c.c_int64, c.c_int, c.c_int, c.c_int, c.c_int,
+                                        c.c_int, c.c_int64, P, c.c_double, c.c_int, P]
     lib.sp_oracle_pool.argtypes = [P, c.c_int64, c.c_int, P]
     lib.sp_oracle_chunk_mean.argtypes = [P, c.c_int64, c.c_int, P]
     lib.sp_oracle_keep_count.argtypes = [c.c_int64, c.c_int64, c.c_int64]
@@ -139,6 +145,50 @@ def score(q: np.ndarray, k_layers: Sequence[np.ndarray], scale: float, layer_agg
     out = np.empty(L, dtype=np.float64)
     _check(_load().sp_oracle_score(_ptr(q), ctypes.cast(ptrs, ctypes.c_void_p), st, sh, Lyr, H, hkv, n_q,
                                    d, L, float(scale), int(layer_agg), _ptr(out)), "score")
+    return out
+
+
+def e4m3_to_f64(codes: np.ndarray) -> np.ndarray:
+    """Values of E4M3 codes (uint8, any shape) as float64; the all-ones codes are NaN."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    lib = _load()
+    table = np.array([lib.sp_oracle_e4m3_to_f64(b) for b in range(256)], dtype=np.float64)
+    return table[codes]
+
+
+def logits_layer_fp8(q_layer: np.ndarray, k8_layer: np.ndarray, kscale: np.ndarray, scale: float,
+                     layout: str = "HND") -> np.ndarray:
+    """Scaled logits of one layer over quantised keys, float64 [H][n_q][L]. k8_layer: uint8 E4M3 codes,
+    kscale: [Hkv] scales."""
+    q_layer = np.ascontiguousarray(q_layer, dtype=np.uint16)
+    k8_layer = np.ascontiguousarray(k8_layer, dtype=np.uint8)
+    H, n_q, d = q_layer.shape
+    st, sh, hkv, L, dk = _k_strides(k8_layer, layout)
+    ksc = np.ascontiguousarray(kscale, dtype=np.float64)
+    if dk != d or ksc.shape != (hkv,):
+        raise ValueError("shape mismatch")
+    s = np.empty((H, n_q, L), dtype=np.float64)
+    _check(_load().sp_oracle_logits_layer_fp8(_ptr(q_layer), _ptr(k8_layer), st, sh, H, hkv, n_q, d, L, _ptr(ksc),
+                                              float(scale), _ptr(s)), "logits_layer_fp8")
+    return s
+
+
+def score_fp8(q: np.ndarray, k8_layers: Sequence[np.ndarray], kscale: np.ndarray, scale: float,
+              layer_agg: int = LAYER_MEAN, layout: str = "HND") -> np.ndarray:
+    """Token importance over quantised keys. k8_layers: uint8 E4M3 codes per layer; kscale: [Lyr][Hkv]."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    Lyr, H, n_q, d = q.shape
+    if len(k8_layers) != Lyr:
+        raise ValueError("need one K array per layer")
+    ks = [np.ascontiguousarray(k, dtype=np.uint8) for k in k8_layers]
+    st, sh, hkv, L, dk = _k_strides(ks[0], layout)
+    ksc = np.ascontiguousarray(kscale, dtype=np.float64)
+    if dk != d or ksc.shape != (Lyr, hkv) or any(k.shape != ks[0].shape for k in ks):
+        raise ValueError("shape mismatch")
+    ptrs = (ctypes.c_void_p * Lyr)(*[k.ctypes.data for k in ks])
+    out = np.empty(L, dtype=np.float64)
+    _check(_load().sp_oracle_score_fp8(_ptr(q), ctypes.cast(ptrs, ctypes.c_void_p), st, sh, Lyr, H, hkv, n_q, d, L,
+                                       _ptr(ksc), float(scale), int(layer_agg), _ptr(out)), "score_fp8")
     return out
 
 

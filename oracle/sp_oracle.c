@@ -233,6 +233,105 @@ int sp_oracle_score(const uint16_t *q, const uint16_t *const *k_layers,
 }
 
 /*
+ * Keys kept as 8-bit floating point (Section 3.1 has the deployment's KV cache in
+ * fixed blocks; a quantised cache halves what the importance pass must stream).
+ * Format: OCP "E4M3" (the finite-only variant): 1 sign bit, 4 exponent bits with
+ * bias 7, 3 mantissa bits; exponent field 0 holds the subnormals m/8 * 2^-6; there
+ * are no infinities, and only the all-ones pattern (0x7f / 0xff) is NaN, so the
+ * largest finite value is 1.75 * 2^8 = 448. Every E4M3 value is exact in double.
+ */
+double sp_oracle_e4m3_to_f64(uint8_t b)
+{
+    const int sign = b >> 7, e = (b >> 3) & 15, m = b & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m / 8.0, -6);
+    else        v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+/*
+ * Logits of one layer over quantised keys: the key vector of (kv, j) is
+ *   kscale[kv] * E4M3(k8[kv * k_stride_head + j * k_stride_token + e]),  e in [0, d),
+ * taken as exact inputs (the dequantised keys ARE the keys; nothing is rounded
+ * here), and otherwise as sp_oracle_logits_layer:
+ *   s[h][n][j] = scale * sum_e Q[h][n][e] * kscale[kv(h)] * E4M3(k8[...]).
+ */
+int sp_oracle_logits_layer_fp8(const uint16_t *q_layer, const uint8_t *k8_layer,
+                               int64_t k_stride_token, int64_t k_stride_head,
+                               int H, int Hkv, int n_q, int d, int64_t L,
+                               const double *kscale, double scale, double *s)
+{
+    if (!q_layer || !k8_layer || !kscale || !s || H <= 0 || Hkv <= 0 || H % Hkv != 0 ||
+        n_q <= 0 || d <= 0 || L <= 0)
+        return 1;
+    const int G = H / Hkv;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int h = 0; h < H; ++h) {
+        for (int n = 0; n < n_q; ++n) {
+            const int kv = h / G;
+            const uint16_t *qrow = q_layer + ((int64_t)h * n_q + n) * d;
+            double *srow = s + ((int64_t)h * n_q + n) * L;
+            for (int64_t j = 0; j < L; ++j) {
+                const uint8_t *krow = k8_layer + kv * k_stride_head + j * k_stride_token;
+                double acc = 0.0;
+                for (int e = 0; e < d; ++e)
+                    acc += bf16_to_f64(qrow[e]) * (kscale[kv] * sp_oracle_e4m3_to_f64(krow[e]));
+                srow[j] = scale * acc;
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Token importance over quantised keys: sp_oracle_score with the logits of
+ * sp_oracle_logits_layer_fp8; kscale is [Lyr][Hkv], one scale per layer and kv
+ * head. Softmax over the prompt keys, head maximum, aggregation over lookahead
+ * rows and layers exactly as in sp_oracle_score_look (Appendix A.1.1).
+ */
+int sp_oracle_score_fp8(const uint16_t *q, const uint8_t *const *k8_layers,
+                        int64_t k_stride_token, int64_t k_stride_head,
+                        int Lyr, int H, int Hkv, int n_q, int d, int64_t L,
+                        const double *kscale, double scale, int layer_agg, double *I)
+{
+    if (!q || !k8_layers || !kscale || !I || Lyr <= 0 || (layer_agg != 0 && layer_agg != 1)) return 1;
+    const int64_t rows = (int64_t)H * n_q;
+    double *p = (double *)malloc(sizeof(double) * rows * L);
+    double *acc = (double *)malloc(sizeof(double) * (int64_t)n_q * L); /* per (n, j) */
+    if (!p || !acc) { free(p); free(acc); return 2; }
+    for (int64_t i = 0; i < (int64_t)n_q * L; ++i) acc[i] = 0.0;
+    for (int l = 0; l < Lyr; ++l) {
+        int rc = sp_oracle_logits_layer_fp8(q + (int64_t)l * rows * d, k8_layers[l], k_stride_token, k_stride_head,
+                                            H, Hkv, n_q, d, L, kscale + (int64_t)l * Hkv, scale, p);
+        if (!rc) rc = sp_oracle_softmax_rows(p, rows, L, NULL, NULL);
+        if (rc) { free(p); free(acc); return rc; }
+#pragma omp parallel for schedule(static)
+        for (int n = 0; n < n_q; ++n) {
+            for (int64_t j = 0; j < L; ++j) {
+                double mh = 0.0; /* probabilities are positive */
+                for (int h = 0; h < H; ++h) {
+                    double v = p[((int64_t)h * n_q + n) * L + j];
+                    if (v > mh) mh = v;
+                }
+                double *a = &acc[(int64_t)n * L + j];
+                if (layer_agg == 1) { if (mh > *a) *a = mh; }   /* max over layers */
+                else                { *a += mh; }               /* sum over layers */
+            }
+        }
+    }
+    const double denom = (layer_agg == 1) ? (double)n_q : (double)n_q * (double)Lyr;
+    for (int64_t j = 0; j < L; ++j) {
+        double sum = 0.0;
+        for (int n = 0; n < n_q; ++n) sum += acc[(int64_t)n * L + j];
+        I[j] = sum / denom;
+    }
+    free(p);
+    free(acc);
+    return 0;
+}
+
+/*
  * 1-D average pooling (Algorithm 1 "AvgPool1D"; Appendix A.3: kernel 13).
  * The paper gives only the kernel size. Reading: stride 1, window centred on
  * j, output length L, zeros outside [0, L), and the divisor is always w:

@@ -18,6 +18,7 @@ from .gen import (
     gen_q,
     heavy_hitter_positions,
     make_score_inputs,
+    quantise_k_e4m3,
 )
 
 __all__ = [
@@ -34,4 +35,5 @@ __all__ = [
     "gen_q",
     "heavy_hitter_positions",
     "make_score_inputs",
+    "quantise_k_e4m3",
 ]

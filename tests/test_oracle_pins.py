@@ -754,3 +754,90 @@ def test_generator_shapes_and_heavy_hitters_show_up():
     assert (np.diff(doff) >= 1).all() and np.diff(doff).max() <= 8 and np.diff(toff).max() <= 7
     x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 0.0], np.float32)   # RNE ties and exact values
     assert bf16_bits_to_f32(f32_to_bf16_bits(x)).tolist() == [1.0, 1.0, 1.015625, -2.5, 0.0]
+
+
+# ---------------------------------------------------------------------------
+# keys kept as 8-bit floating point (E4M3) with one scale per (layer, kv head)
+# ---------------------------------------------------------------------------
+def test_e4m3_decode_matches_the_format_and_a_library():
+    """The oracle's E4M3 decode against values that follow from the format's definition (bias 7, three
+    mantissa bits, subnormals at exponent field 0, largest finite value 448, NaN only at all ones) and
+    against an independent library's decode of all 256 codes."""
+    import torch
+    val = oracle.e4m3_to_f64
+    one = lambda b: float(val(np.array([b], dtype=np.uint8))[0])
+    assert one(0x38) == 1.0 and one(0xB8) == -1.0           # exponent field 7, mantissa 0
+    assert one(0x3C) == 1.5 and one(0x40) == 2.0
+    assert one(0x7E) == 448.0 and one(0xFE) == -448.0       # largest finite: 1.75 * 2^8
+    assert one(0x08) == 2.0 ** -6                           # smallest normal
+    assert one(0x01) == 2.0 ** -9 and one(0x07) == 7 * 2.0 ** -9   # subnormals m/8 * 2^-6
+    assert one(0x00) == 0.0 and one(0x80) == 0.0 and np.signbit(one(0x80))
+    assert np.isnan(one(0x7F)) and np.isnan(one(0xFF))
+    codes = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    got = val(codes)
+    assert np.array_equal(np.isnan(got), np.isnan(lib))
+    ok = ~np.isnan(lib)
+    assert np.array_equal(got[ok], lib[ok]) and np.array_equal(np.signbit(got[ok]), np.signbit(lib[ok]))
+
+
+def _fp8_case(seed, Lyr=2, H=4, Hkv=2, d=16, n_q=3, L=37):
+    rng = np.random.default_rng([260302631, 61, seed])
+    q = synth.f32_to_bf16_bits(rng.standard_normal((Lyr, H, n_q, d)).astype(np.float32))
+    finite = np.array([b for b in range(256) if (b & 0x7F) != 0x7F], dtype=np.uint8)
+    k8 = [finite[rng.integers(0, finite.size, size=(Hkv, L, d))] for _ in range(Lyr)]
+    return q, k8, rng
+
+
+def test_fp8_scores_equal_the_bf16_path_on_exactly_representable_keys():
+    """With power-of-two scales, scale * E4M3 value is exact in bf16: the quantised-key path must then
+    agree with the (separately pinned) bf16 path fed those very keys, in both layouts and both modes:
+    this ties its strides, kv-head mapping, softmax and aggregation to the pinned ones."""
+    q, k8, rng = _fp8_case(1)
+    kscale = 2.0 ** rng.integers(-6, 3, size=(2, 2)).astype(np.float64)
+    kb = [synth.f32_to_bf16_bits((oracle.e4m3_to_f64(k) * kscale[l][:, None, None]).astype(np.float32))
+          for l, k in enumerate(k8)]
+    for l, k in enumerate(k8):      # the bf16 keys hold exactly the dequantised values
+        assert np.array_equal(synth.bf16_bits_to_f32(kb[l]).astype(np.float64), oracle.e4m3_to_f64(k) * kscale[l][:, None, None])
+    for mode in (oracle.LAYER_MEAN, oracle.LAYER_MAX):
+        want = oracle.score(q, kb, 0.25, mode)
+        got = oracle.score_fp8(q, k8, kscale, 0.25, mode)
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=0)
+        k8_nhd = [np.ascontiguousarray(k.transpose(1, 0, 2)) for k in k8]
+        np.testing.assert_allclose(oracle.score_fp8(q, k8_nhd, kscale, 0.25, mode, layout="NHD"), want, rtol=1e-12, atol=0)
+
+
+def test_fp8_logits_with_arbitrary_scales_against_numpy():
+    """Scales that are not powers of two (one per layer and kv head): logits against a numpy einsum over
+    the library-decoded keys, scores against scipy's softmax and numpy's max/mean written out."""
+    import torch
+    from scipy.special import softmax
+    q, k8, rng = _fp8_case(2)
+    kscale = rng.uniform(0.003, 0.07, size=(2, 2))
+    qf = synth.bf16_bits_to_f32(q).astype(np.float64)
+    P = []
+    for l in range(2):
+        kd = torch.from_numpy(k8[l]).view(torch.float8_e4m3fn).to(torch.float64).numpy() * kscale[l][:, None, None]
+        s = np.stack([0.25 * np.einsum("ne,je->nj", qf[l, h], kd[h // 2]) for h in range(4)])
+        np.testing.assert_allclose(oracle.logits_layer_fp8(q[l], k8[l], kscale[l], 0.25), s, rtol=1e-12, atol=1e-13)
+        P.append(softmax(s, axis=-1))
+    P = np.stack(P)                                   # [Lyr][H][n_q][L]
+    np.testing.assert_allclose(oracle.score_fp8(q, k8, kscale, 0.25, oracle.LAYER_MEAN), P.max(axis=1).mean(axis=(0, 1)), rtol=1e-11)
+    np.testing.assert_allclose(oracle.score_fp8(q, k8, kscale, 0.25, oracle.LAYER_MAX), P.max(axis=(0, 1)).mean(axis=0), rtol=1e-11)
+    # a wrong scale index (layer and head swapped) must show: the scales differ in every entry
+    swapped = oracle.score_fp8(q, k8, kscale.T.copy(), 0.25, oracle.LAYER_MEAN)
+    assert np.max(np.abs(swapped - P.max(axis=1).mean(axis=(0, 1)))) > 1e-6
+
+
+def test_quantised_keys_of_the_generator_decode_close_to_the_originals():
+    """The input generator's 8-bit keys (library cast, scale = head maximum / 448): decoded with the
+    oracle's table they sit within half an E4M3 step of the bf16 keys they came from."""
+    w = synth.get_config("tiny")
+    inp = synth.make_score_inputs(w)
+    k8, ksc = synth.quantise_k_e4m3(inp["k"][0])
+    x = synth.bf16_bits_to_f32(inp["k"][0]).astype(np.float64)
+    back = oracle.e4m3_to_f64(k8) * ksc.astype(np.float64)[:, None, None]
+    assert not np.isnan(back).any()
+    step = np.maximum(np.abs(x) * 2.0 ** -3, ksc.astype(np.float64)[:, None, None] * 2.0 ** -9)   # spacing at x
+    assert np.all(np.abs(back - x) <= 0.5 * step * (1 + 1e-6))
+    assert np.allclose(np.abs(back).max(axis=(1, 2)), np.abs(x).max(axis=(1, 2)))
