@@ -78,6 +78,9 @@ def main() -> int:
     ap.add_argument("--probe-passes", type=int, default=10)
     ap.add_argument("--workload", default="long-128k")
     ap.add_argument("--layer-agg", default="mean", choices=["mean", "max"])
+    ap.add_argument("--k-dtype", default="bf16", choices=["bf16", "fp8"],
+                    help="fp8: the keys quantised to E4M3 codes with one scale per layer and kv head, scored by "
+                         "sp_score_fp8 (a line of its own beside the bf16 one, never instead of it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-layers", type=int, default=0,
                     help="layers the CPU oracle is timed on with all cores (0 = all layers of the workload)")
@@ -105,6 +108,10 @@ def main() -> int:
     w = synth.get_config(args.workload)
     mode = sp.SP_LAYER_MEAN if args.layer_agg == "mean" else sp.SP_LAYER_MAX
     ragged = w.batch > 0
+    fp8 = args.k_dtype == "fp8"
+    if fp8 and ragged:
+        print("bench.py: 8-bit keys are scored one prompt at a time (sp_score_fp8)", file=sys.stderr)
+        return 2
 
     # ---- inputs: generated on the host by the seeded generator, uploaded once ----
     t0 = time.time()
@@ -114,7 +121,7 @@ def main() -> int:
     T = int(offsets[-1])                     # tokens per step (all prompts)
     hh = synth.heavy_hitter_positions(w, lengths)
     q_bits = synth.gen_q(w, B)
-    k_bytes = float(w.k_bytes_per_token) * T
+    k_bytes = float(w.k_bytes_per_token) * T / (2 if fp8 else 1)
     # short workloads: the same K replicated n_rot times and walked round-robin, so that every call streams
     # from HBM rather than from the 256 MB memory-side cache
     n_rot = 1 if k_bytes >= ROTATE_BYTES else int(-(-ROTATE_BYTES // int(k_bytes)))
@@ -122,13 +129,18 @@ def main() -> int:
         args.cpu_sample_layers = w.n_layers
     qd = torch.from_numpy((q_bits if ragged else q_bits[0]).view(np.int16)).to(dev)
     # all layers of a copy sit in one allocation (the probe then streams a copy with one launch)
-    k_big = torch.empty((n_rot, w.n_layers, w.n_kv_heads, T, w.head_dim), dtype=torch.int16, device=dev)
+    k_big = torch.empty((n_rot, w.n_layers, w.n_kv_heads, T, w.head_dim), dtype=torch.uint8 if fp8 else torch.int16,
+                        device=dev)
     k_sample = []                # host copies of the layers the CPU baseline uses
+    kscale = np.ones((w.n_layers, w.n_kv_heads), dtype=np.float32)
     for l in range(w.n_layers):
         k = synth.gen_k_layer(w, l, q_bits, lengths, hh)
+        if fp8:
+            k, kscale[l] = synth.quantise_k_e4m3(k)
         if l < args.cpu_sample_layers and not args.no_cpu_baseline:
             k_sample.append(k)
-        k_big[:, l] = torch.from_numpy(k.view(np.int16)).to(dev).unsqueeze(0)
+        k_big[:, l] = torch.from_numpy(k if fp8 else k.view(np.int16)).to(dev).unsqueeze(0)
+    kscale_dev = torch.from_numpy(kscale).to(dev)
     k_sets = [[k_big[r, l] for l in range(w.n_layers)] for r in range(n_rot)]
     chars = [synth.gen_char_offsets(w, int(lengths[b]), prompt=b) for b in range(B)]
     M_all = [int(t.size - 1) for _, t in chars]
@@ -155,7 +167,7 @@ def main() -> int:
             n_t=torch.zeros(1, dtype=torch.int32, device=dev), mask=torch.empty(M_all[b], dtype=torch.uint8, device=dev),
             n_kept=torch.zeros(1, dtype=torch.int64, device=dev)))
     stream = torch.cuda.current_stream()
-    fused = 0 if ragged else sp.sp_score_is_fused(desc, T)
+    fused = 0 if (ragged or fp8) else sp.sp_score_is_fused(desc, T)
     calls = [0]
 
     def step(ev=None):
@@ -166,6 +178,8 @@ def main() -> int:
             ev[0].record(stream)
         if ragged:
             sp.sp_score_batch(desc, qd, k_dev, off_host, off_dev, scores, ws1, stream=stream)
+        elif fp8:
+            sp.sp_score_fp8(desc, qd, k_dev, kscale_dev, T, scores, ws1, stream=stream)
         else:
             sp.sp_score(desc, qd, k_dev, T, scores, ws1, stream=stream)
         if ev is not None:
@@ -230,7 +244,7 @@ def main() -> int:
         f"kept {n_kept} of {sum(M_all)}"
         + (f"; first {args.first_calls} calls: score {float(np.median(first_score)):.3f} ms median" if first_score.size else ""))
 
-    score_name = "sp_score_batch" if ragged else "sp_score"
+    score_name = "sp_score_batch" if ragged else ("sp_score_fp8" if fp8 else "sp_score")
     stage_ms = {score_name: score_ms, score_name + "_mean": score_mean, "sp_select+sp_project": rest_ms}
     if first_score.size:
         stage_ms[score_name + "_first_calls_median"] = float(np.median(first_score))
@@ -238,7 +252,7 @@ def main() -> int:
         stage_ms["step_first_calls"] = first_wall
     cfg = {"workload": w.name, "n_layers": w.n_layers, "n_q_heads": w.n_q_heads,
            "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "n_q": w.n_q, "pool": w.pool, "chunk": w.chunk,
-           "keep": f"{w.keep_num}/{w.keep_den}", "layer_agg": args.layer_agg, "k_layout": "HND",
+           "keep": f"{w.keep_num}/{w.keep_den}", "layer_agg": args.layer_agg, "k_layout": "HND", "k_dtype": args.k_dtype,
            "k_rotating_copies": n_rot, "score_path": "single-launch" if fused == 1 else "three-kernel"}
     if ragged:
         cfg.update({"prompts": B, "total_tokens": T, "min_len": int(lengths.min()), "max_len": int(lengths.max())})
@@ -256,7 +270,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "fp8" if fp8 else "bf16",
         "data": "synthetic",
         "config": cfg,
         "stage_ms": stage_ms,
@@ -279,7 +293,10 @@ def main() -> int:
             for b in range(B):
                 sl = slice(off_host[b], off_host[b + 1])
                 kb = [np.ascontiguousarray(k[:, sl, :]) for k in k_sample[:n_layers]] if ragged else k_sample[:n_layers]
-                res.append(oracle.score(q_bits[b, :n_layers], kb, w.scale, mode))
+                if fp8:
+                    res.append(oracle.score_fp8(q_bits[b, :n_layers], kb, kscale[:n_layers].astype(np.float64), w.scale, mode))
+                else:
+                    res.append(oracle.score(q_bits[b, :n_layers], kb, w.scale, mode))
             return time.perf_counter() - t_a, res
 
         t_score, I_all = oracle_score_seconds(n_s)

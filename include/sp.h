@@ -152,6 +152,25 @@ sp_status sp_score_paged(const sp_score_desc *desc, const void *q_dev,
                          int64_t page_stride, int64_t L, float *scores_dev,
                          void *ws_dev, size_t ws_bytes, void *hip_stream);
 
+/*
+ * sp_score over keys stored as 8-bit floating point (Section 3.1: the deployment
+ * keeps its KV cache in blocks on the accelerator; a quantised cache halves the
+ * bytes this pass streams). k8_layers_host[l] points at layer l's keys as OCP
+ * E4M3 codes (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, finite
+ * only; one byte per element), addressed with desc's strides counted in
+ * elements, i.e. bytes (multiples of 8, layer bases 16-byte aligned).
+ * kscale_dev: device, float [n_layers][n_kv_heads], positive and finite, only
+ * read: the key vector of (l, kv, j) is kscale[l][kv] * E4M3(code), and the
+ * scores are those of sp_score on exactly these dequantised keys (the queries
+ * stay bf16; products are exact, sums are fp32). NaN codes are the caller's to
+ * avoid. Contiguous keys of one prompt only; three-kernel path (see
+ * sp_score_is_fused), same workspace size as sp_score.
+ */
+sp_status sp_score_fp8(const sp_score_desc *desc, const void *q_dev,
+                       const void *const *k8_layers_host, const float *kscale_dev,
+                       int64_t L, float *scores_dev, void *ws_dev, size_t ws_bytes,
+                       void *hip_stream);
+
 /* Which implementation sp_score picks for this shape and length on the current
  * device: 1 = the single-launch kernel that keeps K on chip and reads it from
  * HBM once (long prompts of head_dim 64 whose query group fits 64 padded rows),

@@ -20,7 +20,7 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG_DIR, "libsp_amd.so")
 
 EXPORTS = (
-    "sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_is_fused", "sp_score_batch", "sp_keep_count", "sp_select_workspace",
+    "sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_fp8", "sp_score_is_fused", "sp_score_batch", "sp_keep_count", "sp_select_workspace",
     "sp_select", "sp_select_static", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble", "sp_last_error", "sp_version",
     "sp_debug_fused_giveup", "sp_hbm_read_probe",
 )
@@ -72,6 +72,7 @@ def load_library():
     lib.sp_score.argtypes = [D, P, c.POINTER(P), c.c_int64, P, P, c.c_size_t, P]
     lib.sp_score_look.argtypes = [D, P, c.POINTER(P), c.c_int64, P, c.c_int32, P, P, c.c_size_t, P]
     lib.sp_score_paged.argtypes = [D, P, c.POINTER(P), P, c.c_int64, c.c_int64, c.c_int64, P, P, c.c_size_t, P]
+    lib.sp_score_fp8.argtypes = [D, P, c.POINTER(P), P, c.c_int64, P, P, c.c_size_t, P]
     lib.sp_score_batch.argtypes = [D, P, c.POINTER(P), c.POINTER(c.c_int64), P, c.c_int32, P, P, c.c_size_t, P]
     lib.sp_score_is_fused.argtypes = [D, c.c_int64]
     lib.sp_score_is_fused.restype = c.c_int32
@@ -92,7 +93,7 @@ def load_library():
     lib.sp_debug_fused_giveup.restype = None
     lib.sp_last_error.restype = c.c_char_p
     lib.sp_version.restype = c.c_char_p
-    for name in ("sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_is_fused", "sp_score_batch", "sp_select_workspace", "sp_select",
+    for name in ("sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_fp8", "sp_score_is_fused", "sp_score_batch", "sp_select_workspace", "sp_select",
                  "sp_select_static", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
@@ -220,6 +221,17 @@ def sp_score_paged(desc: ScoreDesc, q, k_pools: Sequence, block_table, page_toke
                                          _ptr(block_table, "block_table", 4 * n_pages), int(page_tokens),
                                          int(page_stride), L, _ptr(scores, "scores", 4 * max(L, 0)), _ptr(ws, "ws"),
                                          nbytes, _stream(stream)))
+
+
+def sp_score_fp8(desc: ScoreDesc, q, k8_layers: Sequence, kscale, L: int, scores, ws, ws_bytes: Optional[int] = None,
+                 stream=None) -> None:
+    if len(k8_layers) != desc.n_layers:
+        raise SpError(1, f"k8_layers has {len(k8_layers)} entries, desc.n_layers is {desc.n_layers}")
+    nbytes = _ws_bytes(ws, ws_bytes)
+    _check(load_library().sp_score_fp8(ctypes.byref(desc), _ptr(q, "q", _q_bytes(desc)),
+                                       _layer_array(k8_layers, _k_bytes(desc, L) // 2),
+                                       _ptr(kscale, "kscale", 4 * desc.n_layers * desc.n_kv_heads), L,
+                                       _ptr(scores, "scores", 4 * max(L, 0)), _ptr(ws, "ws"), nbytes, _stream(stream)))
 
 
 def sp_score_batch(desc: ScoreDesc, q, k_layers: Sequence, offsets_host: Sequence[int], offsets_dev, scores, ws,

@@ -63,6 +63,7 @@ struct ScoreArgs {
     int64_t page_tokens;          // of its layer's pool, page p at element offset p * page_stride; null: contiguous
     int64_t page_stride;
     const float *look;        // [n_phases][rows_pad] lookahead-key term of each row's normaliser, or null
+    const float *kscale;      // 8-bit keys: [n_phases] scale of each (layer, kv head); null: bf16 keys
     float *split_buf;         // layer-split results: MEAN [n_splits][n_tiles][TILE],
                               //                      MAX  [n_splits][8*n_nblk][n_tiles][TILE]
     int32_t n_splits, layers_per_split;
@@ -113,6 +114,12 @@ __device__ __forceinline__ bool row_to_gn(const ScoreArgs &a, int row, int &g, i
     return g < a.group && n < a.n_q;
 }
 
+// 8-bit keys (contiguous only): byte address of key 0 of (layer, kv head).
+__device__ __forceinline__ const uint8_t *key_base_fp8(const ScoreArgs &a, const LayerPtrs &kp, int layer, int kv)
+{
+    return reinterpret_cast<const uint8_t *>(kp.p[layer]) + (int64_t)kv * a.k_stride_head;
+}
+
 template <int D>
 __device__ __forceinline__ void stage_q(u32x4 *qs, const ScoreArgs &a, int prompt, int layer, int kv, int tid)
 {
@@ -126,6 +133,46 @@ __device__ __forceinline__ void stage_q(u32x4 *qs, const ScoreArgs &a, int promp
         if (row_to_gn(a, row, g, n))
             v = *reinterpret_cast<const u32x4 *>(qb + ((int64_t)g * a.n_q + n) * D + ch * 8);
         qs[lds_slot<D>(row, ch)] = v;
+    }
+}
+
+// Eight E4M3 codes (two dwords) -> eight bf16 (every E4M3 value is exact in bf16: the upper half of
+// its float image).
+__device__ __forceinline__ u32x4 e4m3x8_to_bf16x8(uint2 c)
+{
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    u32x4 r;
+    const uint32_t w[2] = {c.x, c.y};
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);     // codes 0, 1 of the dword
+        const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);      // codes 2, 3
+        r[2 * i] = __builtin_amdgcn_perm(__float_as_uint(lo.y), __float_as_uint(lo.x), 0x07060302u);
+        r[2 * i + 1] = __builtin_amdgcn_perm(__float_as_uint(hi.y), __float_as_uint(hi.x), 0x07060302u);
+    }
+    return r;
+}
+
+// The same staging for 8-bit keys: kb8 addresses bytes, strides are in elements (= bytes).
+template <int D, int NS>
+__device__ __forceinline__ void stage_k_fp8(u32x4 *ks, const uint8_t *kb8, int64_t stride_token, int64_t j0,
+                                            int64_t end, int tid)
+{
+    constexpr int CH = D / 8;
+    constexpr int TILE = kWaves * NS * 32;
+    constexpr int N = TILE * CH / kThreads;
+    uint2 v[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int idx = tid + i * kThreads;
+        const int row = idx / CH, ch = idx % CH;
+        const int64_t j = j0 + row;
+        v[i] = *reinterpret_cast<const uint2 *>(kb8 + (j < end ? j : end - 1) * stride_token + ch * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int idx = tid + i * kThreads;
+        ks[lds_slot<D>(idx / CH, idx % CH)] = e4m3x8_to_bf16x8(v[i]);
     }
 }
 
@@ -157,7 +204,7 @@ __device__ __forceinline__ void stage_k(u32x4 *ks, const uint16_t *kb, int64_t s
 // stats: partial (max, sum exp) of every query row of one (layer, kv head)
 // over one key tile.
 // ---------------------------------------------------------------------------
-template <int D, int NS>
+template <int D, int NS, bool FP8>
 __global__ __launch_bounds__(kThreads, 4) void sp_stats_kernel(ScoreArgs a, LayerPtrs kp)
 {
     constexpr int KS = D / 16;
@@ -172,7 +219,8 @@ __global__ __launch_bounds__(kThreads, 4) void sp_stats_kernel(ScoreArgs a, Laye
     if (tile == 0 && phase == 0 && tid == 0) *a.status = 0u;
 
     stage_q<D>(qs, a, ti.prompt, layer, kv, tid);
-    stage_k<D, NS>(ks, key_base(a, kp, layer, kv, ti), a.k_stride_token, ti.j0, ti.end, tid);
+    if (FP8) stage_k_fp8<D, NS>(ks, key_base_fp8(a, kp, layer, kv), a.k_stride_token, ti.j0, ti.end, tid);
+    else stage_k<D, NS>(ks, key_base(a, kp, layer, kv, ti), a.k_stride_token, ti.j0, ti.end, tid);
     __syncthreads();
 
     bf16x8 kf[NS][KS];
@@ -181,7 +229,9 @@ __global__ __launch_bounds__(kThreads, 4) void sp_stats_kernel(ScoreArgs a, Laye
     __syncthreads();                         // ks is reused for the per-wave statistics below
     float2 *wstats = reinterpret_cast<float2 *>(ks);   // [kWaves][rows_pad]
 
-    const float c = a.c;
+    // statistics are kept in units of the raw dot product with the stored keys; with 8-bit keys the
+    // (layer, kv head)'s scale joins the logit scale
+    const float c = FP8 ? a.c * a.kscale[phase] : a.c;
     const int n_blk = a.rows_pad >> 5;
     for (int blk = 0; blk < n_blk; ++blk) {
         bf16x8 qf[KS];
@@ -262,19 +312,21 @@ __global__ __launch_bounds__(kMergeThreads) void sp_merge_kernel(ScoreArgs a)
     int t0 = 0, t1 = a.n_tiles;
     if (a.prompt_tiles) { t0 = a.prompt_tiles[prompt]; t1 = a.prompt_tiles[prompt + 1]; }
     const int row = blk * 32 + rho;
+    const float c = a.kscale ? a.c * a.kscale[phase] : a.c;      // the phase's logit scale (8-bit keys carry their own)
+    const float inv_c = a.kscale ? 1.0f / c : a.inv_c;
     float m = neg_inf(), l = 0.f;
     for (int t = t0 + slice; t < t1; t += kMergeSlices) {
         const float2 p = a.part[((int64_t)phase * a.n_tiles + t) * a.rows_pad + row];
-        lse_merge(m, l, p.x, p.y, a.c);
+        lse_merge(m, l, p.x, p.y, c);
     }
     red[slice][rho] = make_float2(m, l);
     __syncthreads();
     if (slice == 0) {
 #pragma unroll
-        for (int s = 1; s < kMergeSlices; ++s) lse_merge(m, l, red[s][rho].x, red[s][rho].y, a.c);
+        for (int s = 1; s < kMergeSlices; ++s) lse_merge(m, l, red[s][rho].x, red[s][rho].y, c);
         int g, n;
         const bool valid = row_to_gn(a, row, g, n) && l > 0.f;
-        float v = valid ? -(m + fast_log2(l) * a.inv_c) : neg_inf();
+        float v = valid ? -(m + fast_log2(l) * inv_c) : neg_inf();
         if (valid && a.look != nullptr) {
             // the softmax also runs over the row's visible lookahead keys: log-sum-exp of both parts
             const float lp = -v, lk = a.look[(int64_t)phase * a.rows_pad + row], top = fmaxf(lp, lk);
@@ -321,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void sp_look_kernel(ScoreArgs a, const ui
 // prob: per key, sum over lookahead rows (and layers) of the head-maximum of
 // the attention probability.
 // ---------------------------------------------------------------------------
-template <int D, int NS, int NB>
+template <int D, int NS, int NB, bool FP8>
 __global__ __launch_bounds__(kThreads, 3) void sp_prob_kernel(ScoreArgs a, LayerPtrs kp)
 {
     constexpr int KS = D / 16;
@@ -355,7 +407,11 @@ __global__ __launch_bounds__(kThreads, 3) void sp_prob_kernel(ScoreArgs a, Layer
             const int phase = layer * a.n_kv_heads + kv;
             __syncthreads();
             stage_q<D>(qs, a, ti.prompt, layer, kv, tid);
-            stage_k<D, NS>(ks, key_base(a, kp, layer, kv, ti), a.k_stride_token, ti.j0, ti.end, tid);
+            if (FP8) stage_k_fp8<D, NS>(ks, key_base_fp8(a, kp, layer, kv), a.k_stride_token, ti.j0, ti.end, tid);
+            else stage_k<D, NS>(ks, key_base(a, kp, layer, kv, ti), a.k_stride_token, ti.j0, ti.end, tid);
+            // 8-bit keys: logit differences of this (layer, kv head) are in units of its stored keys; its scale
+            // brings them to the common unit before they meet those of other heads and layers
+            const float ksc = FP8 ? a.kscale[phase] : 1.0f;
             for (int i = tid; i < a.rows_pad; i += kThreads)
                 ci[i] = a.lse_neg[((int64_t)ti.prompt * n_phases + phase) * a.rows_pad + i];
             __syncthreads();
@@ -388,7 +444,7 @@ __global__ __launch_bounds__(kThreads, 3) void sp_prob_kernel(ScoreArgs a, Layer
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const float v = fmaxf(fmaxf(acc[e], acc[4 + e]), fmaxf(acc[8 + e], acc[12 + e]));
-                            mx[s][nb][e] = fmaxf(mx[s][nb][e], v);
+                            mx[s][nb][e] = fmaxf(mx[s][nb][e], FP8 ? v * ksc : v);
                         }
                     }
                 }
@@ -612,19 +668,19 @@ WsLayout ws_layout(const Plan &p, int64_t n_tiles, int n_prompts)
     return w;
 }
 
-template <int D, int NS>
+template <int D, int NS, bool FP8 = false>
 sp_status launch_all(const Plan &p, const ScoreArgs &a, const LayerPtrs &kp, hipStream_t st)
 {
     const dim3 block(kThreads);
-    hipLaunchKernelGGL((sp_stats_kernel<D, NS>), dim3(a.n_tiles, p.n_phases), block, p.lds_bytes, st, a, kp);
+    hipLaunchKernelGGL((sp_stats_kernel<D, NS, FP8>), dim3(a.n_tiles, p.n_phases), block, p.lds_bytes, st, a, kp);
     SP_HIP_CHECK(hipGetLastError());
     hipLaunchKernelGGL(sp_merge_kernel, dim3(p.rows_pad / 32, p.n_phases, a.n_prompts), dim3(kMergeThreads), 0, st, a);
     SP_HIP_CHECK(hipGetLastError());
     const dim3 grid(a.n_tiles, a.n_splits);
     if (p.NB == 1)
-        hipLaunchKernelGGL((sp_prob_kernel<D, NS, 1>), grid, block, p.lds_bytes, st, a, kp);
+        hipLaunchKernelGGL((sp_prob_kernel<D, NS, 1, FP8>), grid, block, p.lds_bytes, st, a, kp);
     else
-        hipLaunchKernelGGL((sp_prob_kernel<D, NS, 2>), grid, block, p.lds_bytes, st, a, kp);
+        hipLaunchKernelGGL((sp_prob_kernel<D, NS, 2, FP8>), grid, block, p.lds_bytes, st, a, kp);
     SP_HIP_CHECK(hipGetLastError());
     if (a.n_splits > 1) {
         constexpr int TILE = kWaves * NS * 32;
@@ -640,6 +696,7 @@ struct ScoreOptions {
     int32_t look_self = 0;
     const int32_t *block_table = nullptr;    // paged keys
     int64_t page_tokens = 0, page_stride = 0;
+    const float *kscale = nullptr;           // 8-bit keys with these scales
 };
 
 sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,
@@ -731,12 +788,17 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
     a.block_table = opt.block_table;
     a.page_tokens = opt.page_tokens;
     a.page_stride = opt.page_stride;
+    a.kscale = opt.kscale;
     if (opt.k_look) {
         float *look = reinterpret_cast<float *>(ws + w.look);
         hipLaunchKernelGGL(sp_look_kernel, dim3(p.n_phases), dim3(kThreads), 0, st, a,
                            static_cast<const uint16_t *>(opt.k_look), (int)opt.look_self, p.D, look);
         SP_HIP_CHECK(hipGetLastError());
         a.look = look;
+    }
+    if (opt.kscale) {            // 8-bit keys take the three-kernel path
+        if (p.D == 64) return launch_all<64, 2, true>(p, a, kp, st);
+        return launch_all<128, 1, true>(p, a, kp, st);
     }
     if (!batch && fused_applies(p, total, desc->k_stride_token)) {
         const int n_wg = fused_workgroups(total);
@@ -831,6 +893,16 @@ extern "C" sp_status sp_score_paged(const sp_score_desc *desc, const void *q_dev
     opt.page_tokens = page_tokens;
     opt.page_stride = page_stride;
     return score_impl(desc, q_dev, k_pools_host, nullptr, nullptr, 1, L, opt, scores_dev, ws_dev, ws_bytes, hip_stream);
+}
+
+extern "C" sp_status sp_score_fp8(const sp_score_desc *desc, const void *q_dev, const void *const *k8_layers_host,
+                                  const float *kscale_dev, int64_t L, float *scores_dev, void *ws_dev, size_t ws_bytes,
+                                  void *hip_stream)
+{
+    if (!kscale_dev) return sp::fail(SP_ERR_INVALID_ARG, "kscale_dev is null");
+    ScoreOptions opt;
+    opt.kscale = kscale_dev;
+    return score_impl(desc, q_dev, k8_layers_host, nullptr, nullptr, 1, L, opt, scores_dev, ws_dev, ws_bytes, hip_stream);
 }
 
 extern "C" sp_status sp_score_batch(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,

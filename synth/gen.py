@@ -122,15 +122,15 @@ def gen_k_layer(w: Workload, layer: int, q_bits: np.ndarray, lengths: Sequence[i
     return k
 
 
-def quantise_k_e4m3(k_bits: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+def quantise_k_e4m3(k_bits: np.ndarray, headroom: float = 1.0) -> Tuple[np.ndarray, np.ndarray]:
     """8-bit keys for one layer: bf16 keys ``[Hkv][T][d]`` -> (E4M3 codes uint8 of the same shape,
     float32 scale per kv head), scale = largest magnitude of the head / 448 (the format's largest
-    finite value), codes = the library's round-to-nearest cast of key / scale. This is input
+    finite value) times ``headroom`` (>= 1), codes = the library's round-to-nearest cast of key / scale. This is input
     preparation, like the rounding to bf16: what the codes and scales mean is for the consumers."""
     import torch
     x = torch.from_numpy(bf16_bits_to_f32(k_bits))
     amax = x.abs().amax(dim=(1, 2)).clamp_min(1e-30)
-    scale = (amax / 448.0).to(torch.float32)
+    scale = (amax / 448.0 * float(headroom)).to(torch.float32)
     codes = (x / scale[:, None, None]).to(torch.float8_e4m3fn).view(torch.uint8)
     return codes.numpy().copy(), scale.numpy().copy()
 

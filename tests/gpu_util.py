@@ -78,6 +78,27 @@ def gpu_score_look(q_bits: np.ndarray, k_layers: Sequence[np.ndarray], k_look: n
     return scores[:L].cpu().numpy()
 
 
+def gpu_score_fp8(q_bits: np.ndarray, k8_layers: Sequence[np.ndarray], kscale: np.ndarray, scale: float,
+                  layer_agg: int = 0, layout: str = "HND") -> np.ndarray:
+    """q_bits: uint16 [Lyr][H][n_q][d]; k8_layers: uint8 E4M3 codes [Hkv][L][d] (HND) or [L][Hkv][d] (NHD);
+    kscale: float32 [Lyr][Hkv]."""
+    Lyr, H, n_q, d = q_bits.shape
+    if layout == "HND":
+        Hkv, L, _ = k8_layers[0].shape
+    else:
+        L, Hkv, _ = k8_layers[0].shape
+    desc = make_desc(Lyr, H, Hkv, d, n_q, scale, layer_agg, layout, L)
+    qd = dev_bits(q_bits)
+    kd = [torch.from_numpy(np.ascontiguousarray(k, dtype=np.uint8)).to(DEV) for k in k8_layers]
+    sc = torch.from_numpy(np.ascontiguousarray(kscale, dtype=np.float32)).to(DEV)
+    ws = workspace(sp.sp_score_workspace(desc, L, 1))
+    scores = torch.full((max(L, 1),), float("nan"), dtype=torch.float32, device=DEV)
+    sp.sp_score_fp8(desc, qd, kd, sc, L, scores, ws)
+    torch.cuda.synchronize()
+    assert status_word(ws) == 0
+    return scores[:L].cpu().numpy()
+
+
 def make_paged(k_layers: Sequence[np.ndarray], page_tokens: int, layout: str, seed: int, spare_pages: int = 3):
     """Scatters contiguous head-major keys ([Hkv][L][d] per layer) into per-layer page pools in a random
     page order. Rows that hold no token (the tail of the last page, spare pages) are bf16 NaN: a kernel

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "sp.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sp_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(sp_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -269,3 +269,18 @@ def test_read_probe_argument_errors():
         with pytest.raises(sp.SpError) as e:
             sp.sp_hbm_read_probe(args["buf"], args["n"], args["sink"], stream=0)
         assert e.value.status == 1, kw
+
+
+def test_score_fp8_argument_errors():
+    d = good_desc()
+    fake = 0x1000
+    n = sp.sp_score_workspace(d, 1024, 1)
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_score_fp8(d, fake, [fake, fake], None, 1024, fake, fake, n, stream=0)
+    assert e.value.status == 1 and "kscale" in e.value.message
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_score_fp8(d, fake, [fake, None], fake, 1024, fake, fake, n, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_score_fp8(d, fake, [fake, fake], fake, 1024, fake, fake, 256, stream=0)
+    assert e.value.status == 3
