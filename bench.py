@@ -167,7 +167,10 @@ def main() -> int:
             n_t=torch.zeros(1, dtype=torch.int32, device=dev), mask=torch.empty(M_all[b], dtype=torch.uint8, device=dev),
             n_kept=torch.zeros(1, dtype=torch.int64, device=dev)))
     stream = torch.cuda.current_stream()
-    fused = 0 if (ragged or fp8) else sp.sp_score_is_fused(desc, T)
+    if ragged:
+        fused = 1 if sp.sp_score_batch_is_fused(desc, off_host) > 0 else 0
+    else:
+        fused = 0 if fp8 else sp.sp_score_is_fused(desc, T)
     calls = [0]
 
     def step(ev=None):

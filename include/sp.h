@@ -192,6 +192,14 @@ sp_status sp_score_batch(const sp_score_desc *desc, const void *q_dev,
                          int32_t B, float *scores_dev, void *ws_dev,
                          size_t ws_bytes, void *hip_stream);
 
+/* How sp_score_batch runs this batch on the current device: n > 0 = on the
+ * single-launch kernel in n launches (every prompt empty or at least 512 tokens
+ * long and no longer than 512 tokens per compute unit; prompts share launches,
+ * each with all its keys in one), 0 = the three-kernel path, -1 = invalid
+ * arguments. Same results either way (to rounding). Host-only. */
+int32_t sp_score_batch_is_fused(const sp_score_desc *desc,
+                                const int64_t *offsets_host, int32_t B);
+
 /* Number of chunks to keep for a keep rate keep_num/keep_den (Section 3.1: the
  * top-K chunks make up a fraction rho of the draft sequence):
  * clamp(ceil(n_chunks * keep_num / keep_den), 1, n_chunks) in integer

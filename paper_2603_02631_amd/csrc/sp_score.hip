@@ -29,8 +29,10 @@
 #include "sp_score_dev.hpp"
 #include "sp_score_fused.hpp"
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <vector>
 
 namespace {
 
@@ -647,6 +649,58 @@ bool fused_applies(const Plan &p, int64_t L, int64_t k_stride_token)
     return n_wg >= sp_fused::kMinWorkgroups && n_wg <= 256 && n_wg <= device_compute_units();
 }
 
+// A ragged batch on the single-launch kernel: the prompts are packed into launches of at most one
+// workgroup per compute unit (first fit, longest first), each prompt with all its 512-key tiles in one
+// launch. Applies when every prompt is empty or at least one tile long and fits a launch, the batch has
+// enough tiles to be worth it, and every launch has at least as many workgroups as duty blocks.
+struct BatchGroups {
+    std::vector<sp_fused::GroupTable> groups;
+    std::vector<int> wgs;
+};
+
+bool plan_fused_batch(const Plan &p, const int64_t *offsets, int B, int64_t k_stride_token, BatchGroups &out)
+{
+    if (!fused_shape_ok(p) || k_stride_token > (int64_t(1) << 20)) return false;
+    const int cap = std::min(256, device_compute_units());
+    if (cap < sp_fused::kMinWorkgroups) return false;
+    std::vector<std::pair<int, int>> order;        // (tiles, prompt)
+    int64_t total_tiles = 0;
+    for (int b = 0; b < B; ++b) {
+        const int64_t len = offsets[b + 1] - offsets[b];
+        if (len == 0) continue;
+        if (len < sp_fused::kTileKeys) return false;
+        const int64_t tiles = (len + sp_fused::kTileKeys - 1) / sp_fused::kTileKeys;
+        if (tiles > cap) return false;
+        order.emplace_back((int)tiles, b);
+        total_tiles += tiles;
+    }
+    if (total_tiles < sp_fused::kMinWorkgroups) return false;
+    std::stable_sort(order.begin(), order.end(), [](const std::pair<int, int> &x, const std::pair<int, int> &y) { return x.first > y.first; });
+    out.groups.clear();
+    out.wgs.clear();
+    for (const auto &tp : order) {
+        size_t g = 0;
+        for (; g < out.groups.size(); ++g)
+            if (out.wgs[g] + tp.first <= cap && out.groups[g].n < sp_fused::kMaxGroupPrompts) break;
+        if (g == out.groups.size()) {
+            sp_fused::GroupTable t;
+            std::memset(&t, 0, sizeof t);
+            out.groups.push_back(t);
+            out.wgs.push_back(0);
+        }
+        sp_fused::GroupTable &t = out.groups[g];
+        t.prompt[t.n] = tp.second;
+        t.start[t.n] = offsets[tp.second];
+        t.len[t.n] = offsets[tp.second + 1] - offsets[tp.second];
+        t.w0[t.n] = out.wgs[g];
+        out.wgs[g] += tp.first;
+        t.w0[++t.n] = out.wgs[g];
+    }
+    for (size_t g = 0; g < out.groups.size(); ++g)
+        if (out.groups[g].n * (p.rows_pad / 4) > out.wgs[g]) return false;      // more duty blocks than workgroups
+    return true;
+}
+
 WsLayout ws_layout(const Plan &p, int64_t n_tiles, int n_prompts)
 {
     WsLayout w;
@@ -659,10 +713,10 @@ WsLayout ws_layout(const Plan &p, int64_t n_tiles, int n_prompts)
     w.split = off; off = sp::align_up(off + sizeof(float) * split_buf_floats(p, n_tiles), 256);
     w.look = off; off = sp::align_up(off + sizeof(float) * (size_t)p.n_phases * p.rows_pad, 256);
     w.fused = off;
-    if (fused_shape_ok(p) && n_prompts == 1) {
-        int64_t n_wg = n_tiles * p.tile_keys / sp_fused::kTileKeys + 1;
+    if (fused_shape_ok(p)) {
+        int64_t n_wg = n_tiles * p.tile_keys / sp_fused::kTileKeys + n_prompts;
         if (n_wg > 1024) n_wg = 1024;
-        off += sp_fused::workspace_bytes(p.rows_pad, (int)n_wg);
+        off += sp_fused::workspace_bytes(p.rows_pad, (int)n_wg, std::min(n_prompts, sp_fused::kMaxGroupPrompts));
     }
     w.total = off;
     return w;
@@ -820,8 +874,29 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
             f.n_nblk = a.n_nblk; f.n_gblk = a.n_gblk; f.rows_pad = a.rows_pad;
             f.layer_agg = a.layer_agg;
             f.c = a.c; f.inv_c = a.inv_c; f.out_scale = a.out_scale;
-            return sp_fused::launch(f, kp, ws + w.fused, a.status, st);
+            return sp_fused::launch(f, kp, nullptr, true, ws + w.fused, a.status, st);
         }
+    }
+    BatchGroups bg;
+    if (batch && !opt.k_look && !opt.block_table && plan_fused_batch(p, offsets_host, B, desc->k_stride_token, bg)) {
+        for (size_t g = 0; g < bg.groups.size(); ++g) {
+            sp_fused::FusedArgs f;
+            std::memset(&f, 0, sizeof f);
+            f.q = a.q;
+            f.k_stride_token = a.k_stride_token;
+            f.k_stride_head = a.k_stride_head;
+            f.L = 0;
+            f.scores = scores_dev;
+            f.n_wg = bg.wgs[g];
+            f.n_layers = a.n_layers; f.n_q_heads = a.n_q_heads; f.n_kv_heads = a.n_kv_heads;
+            f.group = a.group; f.n_q = a.n_q;
+            f.n_nblk = a.n_nblk; f.n_gblk = a.n_gblk; f.rows_pad = a.rows_pad;
+            f.layer_agg = a.layer_agg;
+            f.c = a.c; f.inv_c = a.inv_c; f.out_scale = a.out_scale;
+            const sp_status rs = sp_fused::launch(f, kp, &bg.groups[g], g == 0, ws + w.fused, a.status, st);
+            if (rs != SP_OK) return rs;
+        }
+        return SP_OK;
     }
     if (batch) {
         TileInfo *tiles = reinterpret_cast<TileInfo *>(ws + w.tiles);
@@ -862,6 +937,16 @@ extern "C" int32_t sp_score_is_fused(const sp_score_desc *desc, int64_t L)
     Plan p;
     if (make_plan(desc, p) != SP_OK) return -1;
     return fused_applies(p, L, desc->k_stride_token) ? 1 : 0;
+}
+
+extern "C" int32_t sp_score_batch_is_fused(const sp_score_desc *desc, const int64_t *offsets_host, int32_t B)
+{
+    Plan p;
+    if (make_plan(desc, p) != SP_OK || !offsets_host || B < 1 || B > kMaxPrompts) return -1;
+    for (int b = 0; b < B; ++b)
+        if (offsets_host[b + 1] < offsets_host[b]) return -1;
+    BatchGroups bg;
+    return plan_fused_batch(p, offsets_host, B, desc->k_stride_token, bg) ? (int32_t)bg.groups.size() : 0;
 }
 
 extern "C" sp_status sp_score(const sp_score_desc *desc, const void *q_dev, const void *const *k_layers_host,

@@ -51,6 +51,7 @@ namespace {
 
 using namespace sp_dev;
 using sp_fused::FusedArgs;
+using sp_fused::GroupTable;
 
 constexpr int kD = 64;
 constexpr int kKS = kD / 16;              // MFMA k-steps per row
@@ -644,7 +645,7 @@ struct Walk {
 // EXTRA selects the variant that also serves paged keys (an upper bound on the tile's rows) and
 // lookahead keys in the normaliser; the plain variant carries none of their code or registers.
 template <int NB, int GB, int SLOT, int PAR, bool EXTRA>
-__device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, int s, int n_phases, Ring &ring,
+__device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, const GroupTable &gt, int s, int n_phases, Ring &ring,
                                      Acc<NB> &acc, const LaneConst &lc, Walk &wk, unsigned char *lds, uint32_t lds0,
                                      uint64_t wave_off, int r_range)
 {
@@ -660,8 +661,19 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
     const int pl = s - kLag;              // phase whose normalisers are fetched in this step
     const bool do_stats = s < n_phases, do_prob = pc >= 0 && pc < n_phases;
     const uint32_t stride_bytes = (uint32_t)a.k_stride_token * 2u;
+    // Duty blocks of a phase: kDutyRows consecutive rows of one prompt (launches over several prompts have
+    // blocks_per_prompt of them for each); block i goes to workgroup dfirst + i. src_w0 / src_n: the
+    // workgroups whose partials the block combines (its prompt's), lse_idx: the prompt's row of normalisers.
+    const int blocks_per_prompt = a.rows_pad / kDutyRows;
     int duty_blk = wk.dfirst <= w ? w - wk.dfirst : w - wk.dfirst + a.n_wg;
-    if (pd < 0 || pd >= n_phases || duty_blk >= a.rows_pad / kDutyRows) duty_blk = -1;
+    if (pd < 0 || pd >= n_phases || duty_blk >= blocks_per_prompt * a.n_gp) duty_blk = -1;
+    int src_w0 = 0, src_n = a.n_wg, lse_idx = 0;
+    if (EXTRA && a.n_gp > 1 && duty_blk >= 0) {
+        lse_idx = duty_blk / blocks_per_prompt;
+        duty_blk -= lse_idx * blocks_per_prompt;
+        src_w0 = gt.w0[lse_idx];
+        src_n = gt.w0[lse_idx + 1] - src_w0;
+    }
 
     // ---- mid ----
     if (wave == kPubWave) {
@@ -704,8 +716,8 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
         }
     } else if (wave == kDutyWave) {
         if (duty_blk >= 0)
-            stage_duty_block(lds0 + kOffXduty, a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad, a.rows_pad, a.n_wg,
-                             duty_blk * kDutyRows, lane);
+            stage_duty_block(lds0 + kOffXduty, a.part + ((size_t)(pd % kSlots) * a.n_wg + src_w0) * a.rows_pad, a.rows_pad,
+                             src_n, duty_blk * kDutyRows, lane);
     }
     const char *kbase = wk.kptr;
     int slot_next = wk.slot0 + 2;         // sub-tile 0 of phase s + 1
@@ -745,7 +757,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
         ki.lds_dst = lds0 + sub_slot_off(wave, slot_next, 1);
         ki.base = kbase + (int64_t)32 * stride_bytes;
         ki.step_bytes = 8u * stride_bytes;
-        const uint64_t *lse_row = wave == kLseWave ? a.lse + (size_t)(clampi(pl, 0, n_phases - 1) % kSlots) * a.rows_pad : nullptr;
+        const uint64_t *lse_row = wave == kLseWave ? a.lse + ((size_t)(clampi(pl, 0, n_phases - 1) % kSlots) * a.n_gp + a.p_idx) * a.rows_pad : nullptr;
         const float *look_row = nullptr;
         if (EXTRA && a.look != nullptr) look_row = a.look + (size_t)clampi(pl, 0, n_phases - 1) * a.rows_pad;
         // r_range = r_lo | r_hi << 16 (r_hi = 512 without EXTRA): this wave's share of it
@@ -775,10 +787,10 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
             }
             if (row_mask != 0) {
                 const uint32_t par = (uint32_t)(pd / kSlots) & 1u;
-                const uint64_t *src = a.part + (size_t)(pd % kSlots) * a.n_wg * a.rows_pad + duty_blk * kDutyRows;
+                const uint64_t *src = a.part + ((size_t)(pd % kSlots) * a.n_wg + src_w0) * a.rows_pad + duty_blk * kDutyRows;
                 // fast path: the partials requested at the start of this step are all there; otherwise poll (bounded)
                 DutyBlock de = read_duty_staging(lds0, lane);
-                bool ready = !__any(!duty_ready(de, par, lane, a.n_wg, row_mask)) && a.force_miss == 0;
+                bool ready = !__any(!duty_ready(de, par, lane, src_n, row_mask)) && a.force_miss == 0;
                 if (!ready && *fail == 0) {
                     unsigned spins = 0;
                     do {
@@ -787,8 +799,8 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
                         for (int r = 0; r < kDutyRows; ++r)
 #pragma unroll
                             for (int q = 0; q < 4; ++q)
-                                de.e[r][q] = ld64(src + (size_t)min(lane + 64 * q, a.n_wg - 1) * a.rows_pad + r);
-                        ready = !__any(!duty_ready(de, par, lane, a.n_wg, row_mask)) && a.force_miss == 0;
+                                de.e[r][q] = ld64(src + (size_t)min(lane + 64 * q, src_n - 1) * a.rows_pad + r);
+                        ready = !__any(!duty_ready(de, par, lane, src_n, row_mask)) && a.force_miss == 0;
                     } while (!ready);
                 }
                 // per row: maximum first, then one exponential per partial (short dependency chains, fixed order)
@@ -798,7 +810,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
                     float pm[4], pl4[4], m = neg_inf();
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const bool valid = lane + 64 * q < a.n_wg;
+                        const bool valid = lane + 64 * q < src_n;
                         pm[q] = valid ? __uint_as_float((uint32_t)de.e[r][q]) : neg_inf();
                         pl4[q] = valid ? __uint_as_float((uint32_t)(de.e[r][q] >> 32) & 0x7fffffffu) : 0.f;
                         m = fmaxf(m, pm[q]);
@@ -815,7 +827,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
                 // publishes poison: whoever reads it fails too instead of using a wrong normaliser
                 const uint32_t tag = (ready && *fail == 0) ? (uint32_t)(pd + 1) : kPoisonTag;
                 if (lane < kDutyRows && ((row_mask >> lane) & 1u))
-                    st64(a.lse + (size_t)(pd % kSlots) * a.rows_pad + duty_blk * kDutyRows + lane,
+                    st64(a.lse + ((size_t)(pd % kSlots) * a.n_gp + lse_idx) * a.rows_pad + duty_blk * kDutyRows + lane,
                          (uint64_t)__float_as_uint(mine) | ((uint64_t)tag << 32));
             }
         }
@@ -824,7 +836,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
             int g, n;
             float v = neg_inf();
             if (row_valid<NB>(a, lane, g, n)) {
-                const uint64_t *src = a.lse + (size_t)(pl % kSlots) * a.rows_pad + lane;
+                const uint64_t *src = a.lse + ((size_t)(pl % kSlots) * a.n_gp + a.p_idx) * a.rows_pad + lane;
                 uint64_t entry = read_lse_staging(lds0, lane);
                 if ((uint32_t)(entry >> 32) != (uint32_t)(pl + 1) && *fail == 0) {
                     unsigned spins = 0;
@@ -860,7 +872,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, in
     phase_advance(wk.c, s - 3, n_phases, a.n_kv_heads);
     wk.slot0 = slot_next;
     if (s - 1 > 0 && s - 1 < n_phases) {
-        wk.dfirst += a.rows_pad / kDutyRows;
+        wk.dfirst += (a.rows_pad / kDutyRows) * a.n_gp;
         if (wk.dfirst >= a.n_wg) wk.dfirst -= a.n_wg;
     }
     lds_barrier();
@@ -906,7 +918,7 @@ __device__ __forceinline__ void fold_model_constants(FusedArgs &a)
 }
 
 template <int NB, int GB, bool EXTRA, class M>
-__global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, LayerPtrs kp)
+__global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, LayerPtrs kp, GroupTable gt)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[kLdsBytes];
     fold_model_constants<M>(a);
@@ -918,10 +930,30 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     // caller guarantees L >= 512): every workgroup loads 512 real keys; rows below r_lo belong to the
     // previous workgroup. Paged keys: pages are allocated whole and hold a multiple of 512 keys, so the
     // last tile stays where it is and rows from r_hi on (allocated, never written) are ignored.
+    // Several prompts in one launch (their keys packed back to back, every prompt at least one tile long):
+    // prompt p owns workgroups gt.w0[p] .. gt.w0[p+1]-1 and is a prompt of its own in everything
+    // below: tile positions count from its first key, its queries are its own, partials are combined
+    // among its workgroups only and its normalisers have their own row.
     const bool paged = EXTRA && a.block_table != nullptr;
-    const int64_t j0 = (paged || (int64_t)(w + 1) * kFTile <= a.L) ? (int64_t)w * kFTile : a.L - kFTile;
-    const int r_lo = (int)((int64_t)w * kFTile - j0);
-    const int r_hi = (int)(a.L - j0 < kFTile ? a.L - j0 : kFTile);
+    int64_t p_start = 0, p_len = a.L;
+    int wl = w;                               // this workgroup's index within its prompt
+    if (EXTRA && gt.n > 0) {
+        int p = 0;
+        while (p + 1 < gt.n && w >= gt.w0[p + 1]) ++p;
+        p_start = gt.start[p];
+        p_len = gt.len[p];
+        wl = w - gt.w0[p];
+        a.q += (size_t)gt.prompt[p] * ((size_t)a.n_layers * a.n_q_heads * a.n_q * kD);
+        a.p_idx = p;
+        a.n_gp = gt.n;
+    } else {
+        a.p_idx = 0;
+        a.n_gp = 1;
+    }
+    const int64_t j0l = (paged || (int64_t)(wl + 1) * kFTile <= p_len) ? (int64_t)wl * kFTile : p_len - kFTile;
+    const int64_t j0 = p_start + j0l;         // first key of the tile in the layer's key array
+    const int r_lo = (int)((int64_t)wl * kFTile - j0l);
+    const int r_hi = (int)(p_len - j0l < kFTile ? p_len - j0l : kFTile);
     const int r_range = r_lo | (r_hi << 16);
     const uint32_t lds0 = lds_addr(lds);
     const uint32_t stride_bytes = (uint32_t)a.k_stride_token * 2u;
@@ -992,16 +1024,17 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     wk.c = phase_at(0, n_phases, a.n_kv_heads);
     wk.slot0 = 0;
     wk.dfirst = 0;
+    if (!EXTRA) { a.p_idx = 0; a.n_gp = 1; }
 
     // The body is unrolled four times so that the fragment ring slot (s % 4) and the buffer parity
     // (s % 2) are compile-time; the trip count is rounded up, surplus steps do no work but keep the
     // instruction stream uniform. The last probability pass (phase n_phases - 1) runs in step n_phases + 3.
     const int n_steps = (n_phases + kLag + 1 + 3) / 4 * 4;
     for (int s0 = 0; s0 < n_steps; s0 += 4) {
-        step<NB, GB, 0, 0, EXTRA>(a, kp, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 1, 1, EXTRA>(a, kp, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 2, 0, EXTRA>(a, kp, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 3, 1, EXTRA>(a, kp, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 0, 0, EXTRA>(a, kp, gt, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 1, 1, EXTRA>(a, kp, gt, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 2, 0, EXTRA>(a, kp, gt, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 3, 1, EXTRA>(a, kp, gt, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
     }
     vm_wait<0>();               // no direct-to-LDS load may outlive the workgroup
     lds_barrier();
@@ -1019,7 +1052,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
 // phase numbers start at 1, so zero normaliser entries are never taken as ready.
 __global__ void sp_fused_clear_kernel(uint64_t *p, size_t n, uint32_t *err)
 {
-    if (blockIdx.x == 0 && threadIdx.x == 0) *err = 0u;
+    if (err != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *err = 0u;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
@@ -1038,9 +1071,9 @@ void set_giveup(uint32_t spin_max, int32_t force_miss)
     g_force_miss.store(force_miss, std::memory_order_relaxed);
 }
 
-size_t workspace_bytes(int rows_pad, int n_wg)
+size_t workspace_bytes(int rows_pad, int n_wg, int n_prompts)
 {
-    return sp::align_up(sizeof(uint64_t) * ((size_t)kSlots * rows_pad * n_wg + (size_t)kSlots * rows_pad), 256);
+    return sp::align_up(sizeof(uint64_t) * ((size_t)kSlots * rows_pad * n_wg + (size_t)kSlots * rows_pad * n_prompts), 256);
 }
 
 bool fits_one_per_cu()
@@ -1051,10 +1084,14 @@ bool fits_one_per_cu()
     return n1 >= 1 && n2 >= 1;
 }
 
-sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, uint32_t *status_word, hipStream_t st)
+sp_status launch(FusedArgs a, const LayerPtrs &kp, const GroupTable *group, bool clear_status, void *ws,
+                 uint32_t *status_word, hipStream_t st)
 {
+    GroupTable gt;
+    std::memset(&gt, 0, sizeof gt);
+    if (group) gt = *group;
     uint64_t *base = static_cast<uint64_t *>(ws);
-    const size_t n_part = (size_t)kSlots * a.rows_pad * a.n_wg, n_lse = (size_t)kSlots * a.rows_pad;
+    const size_t n_part = (size_t)kSlots * a.rows_pad * a.n_wg, n_lse = (size_t)kSlots * a.rows_pad * (gt.n > 0 ? gt.n : 1);
     a.part = base;
     a.lse = base + n_part;
     a.err = status_word;
@@ -1062,32 +1099,32 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, void *ws, uint32_t *status_wo
     a.force_miss = g_force_miss.load(std::memory_order_relaxed);
     const size_t n_clear = n_part + n_lse;
     hipLaunchKernelGGL(sp_fused_clear_kernel, dim3((unsigned)((n_clear + 255) / 256 > 1024 ? 1024 : (n_clear + 255) / 256)),
-                       dim3(256), 0, st, base, n_clear, status_word);
+                       dim3(256), 0, st, base, n_clear, clear_status ? status_word : (uint32_t *)nullptr);
     SP_HIP_CHECK(hipGetLastError());
     // Every workgroup must be resident for the exchange to make progress: one workgroup fits per
     // compute unit (LDS), so the grid may not exceed the number of compute units. All waits in the
     // kernel are bounded; should residency fail (the device shared with other work), the call ends
     // with NaN scores and the status word set instead of hanging.
-    const bool extra = a.look != nullptr || a.block_table != nullptr;
+    const bool extra = a.look != nullptr || a.block_table != nullptr || gt.n > 0;
     const dim3 grid(a.n_wg), block(kFThreads);
     // the fixed-model instantiations apply when every folded constant equals the call's value
     const bool draft = !extra && a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
                        a.c == kScaleEighthLog2e && a.inv_c == 1.0f / kScaleEighthLog2e;
     if (draft && a.n_q == 16) {
-        if (a.n_wg == 256) hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 256>>), grid, block, 0, st, a, kp);
-        else hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 0>>), grid, block, 0, st, a, kp);
+        if (a.n_wg == 256) hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 256>>), grid, block, 0, st, a, kp, gt);
+        else hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 0>>), grid, block, 0, st, a, kp, gt);
     } else if (draft && a.n_q == 8) {
-        if (a.n_wg == 256) hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, Draft16x32x8<8, 256>>), grid, block, 0, st, a, kp);
-        else hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, Draft16x32x8<8, 0>>), grid, block, 0, st, a, kp);
+        if (a.n_wg == 256) hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, Draft16x32x8<8, 256>>), grid, block, 0, st, a, kp, gt);
+        else hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, Draft16x32x8<8, 0>>), grid, block, 0, st, a, kp, gt);
     } else if (a.n_nblk == 2 && a.n_gblk == 1) {
-        if (extra) hipLaunchKernelGGL((sp_fused_kernel<2, 1, true, AnyModel>), grid, block, 0, st, a, kp);
-        else hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, AnyModel>), grid, block, 0, st, a, kp);
+        if (extra) hipLaunchKernelGGL((sp_fused_kernel<2, 1, true, AnyModel>), grid, block, 0, st, a, kp, gt);
+        else hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, AnyModel>), grid, block, 0, st, a, kp, gt);
     } else if (a.n_nblk == 1 && a.n_gblk == 2) {
-        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 2, true, AnyModel>), grid, block, 0, st, a, kp);
-        else hipLaunchKernelGGL((sp_fused_kernel<1, 2, false, AnyModel>), grid, block, 0, st, a, kp);
+        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 2, true, AnyModel>), grid, block, 0, st, a, kp, gt);
+        else hipLaunchKernelGGL((sp_fused_kernel<1, 2, false, AnyModel>), grid, block, 0, st, a, kp, gt);
     } else if (a.n_nblk == 1 && a.n_gblk == 1) {
-        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 1, true, AnyModel>), grid, block, 0, st, a, kp);
-        else hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, AnyModel>), grid, block, 0, st, a, kp);
+        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 1, true, AnyModel>), grid, block, 0, st, a, kp, gt);
+        else hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, AnyModel>), grid, block, 0, st, a, kp, gt);
     } else {
         return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel: %d x %d row blocks", a.n_nblk, a.n_gblk);
     }

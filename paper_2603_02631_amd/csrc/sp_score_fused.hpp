@@ -10,6 +10,18 @@ constexpr int kTileKeys = 512;   // keys owned by one workgroup
 constexpr int kMaxRows = 64;     // padded query rows per kv head the kernel holds on chip
 constexpr int kSlots = 8;        // depth of the exchange ring
 constexpr int kMinWorkgroups = 64;
+constexpr int kMaxGroupPrompts = 32;   // prompts one launch can serve
+
+// Prompts of a ragged batch that share a launch: prompt i of the group is prompt `prompt[i]` of the
+// batch (its queries), owns keys [start[i], start[i] + len[i]) of the packed key arrays (len >= one
+// tile) and workgroups w0[i] .. w0[i+1]-1. n == 0: a single prompt described by FusedArgs::L.
+struct GroupTable {
+    int32_t n;
+    int32_t w0[kMaxGroupPrompts + 1];
+    int32_t prompt[kMaxGroupPrompts];
+    int64_t start[kMaxGroupPrompts];
+    int64_t len[kMaxGroupPrompts];
+};
 
 struct FusedArgs {
     const uint16_t *q;           // [Lyr][H][n_q][64]
@@ -27,20 +39,24 @@ struct FusedArgs {
     int64_t page_stride;
     float *scores;
     int32_t n_wg;
+    int32_t n_gp, p_idx;         // set in the kernel: prompts in the launch, this workgroup's prompt among them
     int32_t n_layers, n_q_heads, n_kv_heads, group, n_q;
     int32_t n_nblk, n_gblk, rows_pad;
     int32_t layer_agg;
     float c, inv_c, out_scale;
 };
 
-size_t workspace_bytes(int rows_pad, int n_wg);
+size_t workspace_bytes(int rows_pad, int n_wg, int n_prompts);
 
 // True when the device can hold one workgroup of the fused kernel per compute unit.
 bool fits_one_per_cu();
 
 // Enqueues the clear kernel and the fused kernel. `ws` must hold workspace_bytes(); `status_word`
 // (device) is cleared first and raised if the call gives up.
-sp_status launch(FusedArgs a, const sp_dev::LayerPtrs &kp, void *ws, uint32_t *status_word, hipStream_t st);
+// `group` (or null for one prompt) describes the prompts of the launch; the status word is cleared only
+// when clear_status is set (the first launch of a call).
+sp_status launch(FusedArgs a, const sp_dev::LayerPtrs &kp, const GroupTable *group, bool clear_status, void *ws,
+                 uint32_t *status_word, hipStream_t st);
 
 // Test hook: polls before a bounded wait gives up (default 2^20) and whether duty waves treat their
 // partials as never arriving; applies to launches that follow.

@@ -138,6 +138,51 @@ def test_score_batch_matches_oracle_per_prompt(layout):
                 np.testing.assert_allclose(got[sl], single, rtol=1e-6)
 
 
+FUSED_BATCHES = [
+    # name, Lyr, H, Hkv, d, n_q, prompt lengths  (every prompt empty or >= 512 tokens: one launch or several)
+    ("batch_one_launch", 2, 8, 2, 64, 8, [20000, 512, 700, 0, 15000, 9001]),
+    ("batch_nq16_two_row_blocks", 1, 8, 2, 64, 16, [12000, 24000, 513]),
+    ("batch_g8_two_gblocks", 1, 16, 2, 64, 8, [33000, 1024, 2047]),
+    ("batch_several_launches", 1, 4, 1, 64, 8, [70000, 65000, 60000, 3000, 1500]),
+    ("batch_single_prompt", 2, 8, 2, 64, 5, [40000]),
+]
+
+
+@pytest.mark.parametrize("case", FUSED_BATCHES, ids=[c[0] for c in FUSED_BATCHES])
+def test_score_batch_on_the_single_launch_kernel(case):
+    """Ragged batches whose prompts are all at least one 512-key tile long take the single-launch
+    kernel, several prompts to a launch: every prompt against the oracle run on that prompt alone, both
+    modes, both layouts, deterministic."""
+    import paper_2603_02631_amd as sp
+    from gpu_util import assert_scores_close, gpu_score_batch, make_desc
+    name, Lyr, H, Hkv, d, n_q, lens = case
+    lengths = np.array(lens, dtype=np.int64)
+    say(f"[score_batch-fused] {name} Lyr={Lyr} H={H} Hkv={Hkv} n_q={n_q} lengths={lens}")
+    w = dataclasses.replace(small_workload(name, Lyr, H, Hkv, d, n_q, 0, cfg_id=170 + FUSED_BATCHES.index(case), hh=(1, 1000)),
+                            batch=len(lengths))
+    hh = synth.heavy_hitter_positions(w, lengths)
+    q = synth.gen_q(w, len(lengths))
+    ks = [synth.gen_k_layer(w, l, q, lengths, hh) for l in range(w.n_layers)]
+    offsets = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    T = int(offsets[-1])
+    n_launch = sp.sp_score_batch_is_fused(make_desc(Lyr, H, Hkv, d, n_q, w.scale, 0, "HND", T), [int(v) for v in offsets])
+    assert n_launch >= (2 if "several" in name else 1)
+    got = None
+    for mode in (0, 1):
+        got = gpu_score_batch(q, ks, offsets, w.scale, mode)
+        for b, Lb in enumerate(lengths):
+            if Lb == 0:
+                continue
+            sl = slice(int(offsets[b]), int(offsets[b + 1]))
+            want = oracle.score(q[b], [np.ascontiguousarray(k[:, sl, :]) for k in ks], w.scale, mode)
+            assert_scores_close(got[sl], want)
+        say(f"  mode {mode}: ok")
+    again = gpu_score_batch(q, ks, offsets, w.scale, 1)
+    assert again.tobytes() == got.tobytes()
+    nhd = [np.ascontiguousarray(k.transpose(1, 0, 2)) for k in ks]
+    assert gpu_score_batch(q, nhd, offsets, w.scale, 1, layout="NHD").tobytes() == got.tobytes()
+
+
 def test_score_mid_size_config():
     """The 16-layer, 32/8-head, head_dim-64 shape at L = 8192 (second workload), full element-wise parity."""
     from gpu_util import assert_scores_close, gpu_score
