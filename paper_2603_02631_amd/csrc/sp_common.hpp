@@ -19,6 +19,9 @@ void clear_error();
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// ceil(n / d) for n >= 0, d > 0 without the overflow of n + d - 1
+inline int64_t ceil_div(int64_t n, int64_t d) { return n / d + (n % d != 0 ? 1 : 0); }
+
 }  // namespace sp
 
 // Evaluates a HIP call; on failure records the text and returns SP_ERR_DEVICE.

@@ -620,7 +620,11 @@ struct WsLayout {
 // Shapes the fused single-launch kernel can hold on chip (any L; the length test is separate).
 bool fused_shape_ok(const Plan &p) { return p.D == 64 && p.rows_pad <= sp_fused::kMaxRows; }
 
-int fused_workgroups(int64_t L) { return (int)((L + sp_fused::kTileKeys - 1) / sp_fused::kTileKeys); }
+int fused_workgroups(int64_t L)
+{
+    const int64_t n = sp::ceil_div(L, sp_fused::kTileKeys);
+    return n > 0x7fffffff ? 0x7fffffff : (int)n;
+}
 
 bool fused_applies(const Plan &p, int64_t L, int64_t k_stride_token);
 
@@ -669,7 +673,7 @@ bool plan_fused_batch(const Plan &p, const int64_t *offsets, int B, int64_t k_st
         const int64_t len = offsets[b + 1] - offsets[b];
         if (len == 0) continue;
         if (len < sp_fused::kTileKeys) return false;
-        const int64_t tiles = (len + sp_fused::kTileKeys - 1) / sp_fused::kTileKeys;
+        const int64_t tiles = sp::ceil_div(len, sp_fused::kTileKeys);
         if (tiles > cap) return false;
         order.emplace_back((int)tiles, b);
         total_tiles += tiles;
@@ -792,13 +796,13 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
         for (int b = 0; b < B; ++b) {
             const int64_t len = offsets_host[b + 1] - offsets_host[b];
             if (len < 0) return sp::fail(SP_ERR_INVALID_ARG, "offsets_host decreases at prompt %d", b);
-            n_tiles += (len + p.tile_keys - 1) / p.tile_keys;
+            n_tiles += sp::ceil_div(len, p.tile_keys);
         }
         total = offsets_host[B];
     } else {
         if (L_single < 0) return sp::fail(SP_ERR_INVALID_ARG, "L = %lld is negative", (long long)L_single);
         total = L_single;
-        n_tiles = (total + p.tile_keys - 1) / p.tile_keys;
+        n_tiles = sp::ceil_div(total, p.tile_keys);
         B = 1;
     }
     if (total == 0) return SP_OK;
@@ -922,7 +926,7 @@ extern "C" sp_status sp_score_workspace(const sp_score_desc *desc, int64_t total
     if (!bytes) return sp::fail(SP_ERR_INVALID_ARG, "bytes is null");
     if (total_tokens < 0 || n_prompts < 1 || n_prompts > kMaxPrompts)
         return sp::fail(SP_ERR_INVALID_ARG, "total_tokens must be >= 0 and n_prompts in 1..%d", kMaxPrompts);
-    const int64_t n_tiles = (total_tokens + p.tile_keys - 1) / p.tile_keys + n_prompts;
+    const int64_t n_tiles = sp::ceil_div(total_tokens, p.tile_keys) + n_prompts;
     *bytes = ws_layout(p, n_tiles, n_prompts).total;
     return SP_OK;
 }

@@ -445,7 +445,7 @@ extern "C" sp_status sp_select_workspace(int64_t L, int32_t chunk, size_t *bytes
 {
     if (!bytes) return sp::fail(SP_ERR_INVALID_ARG, "bytes is null");
     if (L < 1 || chunk < 1) return sp::fail(SP_ERR_INVALID_ARG, "L and chunk must be >= 1");
-    const int64_t C = (L + chunk - 1) / chunk;
+    const int64_t C = sp::ceil_div(L, chunk);
     *bytes = sp::align_up(sizeof(float) * (size_t)C, 256);
     return SP_OK;
 }
@@ -462,7 +462,7 @@ sp_status select_check(const float *scores_dev, int64_t L, int32_t pool_w, int32
     if (chunk < 1) return sp::fail(SP_ERR_INVALID_ARG, "chunk = %d must be >= 1", chunk);
     if (pool_w < 1 || pool_w % 2 == 0) return sp::fail(SP_ERR_INVALID_ARG, "pool_w = %d must be odd and >= 1", pool_w);
     if (pool_w > kMaxPool) return sp::fail(SP_ERR_UNSUPPORTED, "pool_w = %d (supported: <= %d)", pool_w, kMaxPool);
-    C = (L + chunk - 1) / chunk;
+    C = sp::ceil_div(L, chunk);
     if (C > (1 << 30)) return sp::fail(SP_ERR_UNSUPPORTED, "too many chunks (%lld)", (long long)C);
     if (k < 1 || k > C) return sp::fail(SP_ERR_INVALID_ARG, "k = %lld outside 1..%lld", (long long)k, (long long)C);
     return SP_OK;
@@ -555,7 +555,7 @@ extern "C" sp_status sp_select_budget_workspace(int64_t L, int32_t chunk, size_t
 {
     if (!bytes) return sp::fail(SP_ERR_INVALID_ARG, "bytes is null");
     if (L < 1 || chunk < 1) return sp::fail(SP_ERR_INVALID_ARG, "L and chunk must be >= 1");
-    const int64_t C = (L + chunk - 1) / chunk;
+    const int64_t C = sp::ceil_div(L, chunk);
     if (C > kMaxBudgetChunks)
         return sp::fail(SP_ERR_UNSUPPORTED, "%lld chunks (the budget search supports <= %d)", (long long)C, kMaxBudgetChunks);
     size_t a, b, c;
@@ -577,7 +577,7 @@ extern "C" sp_status sp_select_budget(const float *scores_dev, int64_t L, int32_
     if (pool_w > kMaxPool) return sp::fail(SP_ERR_UNSUPPORTED, "pool_w = %d (supported: <= %d)", pool_w, kMaxPool);
     if (budget < 0) return sp::fail(SP_ERR_INVALID_ARG, "budget = %lld is negative", (long long)budget);
     if (M >= (int64_t(1) << 31)) return sp::fail(SP_ERR_UNSUPPORTED, "M = %lld (supported: < 2^31)", (long long)M);
-    const int64_t C = (L + chunk - 1) / chunk;
+    const int64_t C = sp::ceil_div(L, chunk);
     if (C > kMaxBudgetChunks)
         return sp::fail(SP_ERR_UNSUPPORTED, "%lld chunks (the budget search supports <= %d)", (long long)C, kMaxBudgetChunks);
     size_t off_rank, off_hist, off_bnd;
