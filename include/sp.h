@@ -290,8 +290,10 @@ sp_status sp_select_budget(const float *scores_dev, int64_t L, int32_t pool_w,
  * draft_off_dev[L+1] and target_off_dev[M+1]. Draft span [a,b) covers
  * characters [draft_off[a], draft_off[b]); target token t is kept iff
  *      target_off[t] < draft_off[b]  and  target_off[t+1] > draft_off[a]
- * for some span. spans_dev holds *n_spans_dev ascending, disjoint spans (as
- * written by sp_select), at most max_spans.
+ * for some span. spans_dev is a buffer of max_spans entries whose first
+ * *n_spans_dev (at most max_spans) are ascending, disjoint spans, as written by
+ * sp_select; the kernels may read the entries after them (so all max_spans
+ * must be readable device memory) and do not use what they hold.
  *  - tspans_dev[max_spans][2]: kept target tokens as maximal ranges
  *    [begin, end), ascending, disjoint and non-adjacent (ranges that overlap or
  *    touch are merged); *n_tspans_dev of them are written;

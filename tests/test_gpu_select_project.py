@@ -128,6 +128,11 @@ def check_project(doff, toff, spans):
     ts2, m2, n2 = gpu_project(doff, toff, spans, want_mask=False, max_spans=max(1, spans.shape[0]) + 3)
     np.testing.assert_array_equal(ts2, o_ts)
     assert m2 is None and n2 == o_n
+    # a capacity beyond what the one-launch kernel holds in LDS takes the three-launch path
+    ts3, m3, n3 = gpu_project(doff, toff, spans, max_spans=1500)
+    np.testing.assert_array_equal(ts3, o_ts)
+    np.testing.assert_array_equal(m3, o_mask)
+    assert n3 == o_n
 
 
 def random_spans(rng, L, n_max):
@@ -170,6 +175,20 @@ def test_project_many_spans_and_special_tokenisations():
             d2[-1] = 1
         t2 = split_same_text(rng, int(d2[-1]), 3, allow_zero=True)
         check_project(d2, t2, random_spans(rng, Ls, 8))
+
+
+def test_project_long_prompt_coarse_index_strides():
+    say("[project] long prompts: coarse-index strides 2 .. 63 and beyond")
+    rng = np.random.default_rng(23)
+    for L, mean_len in ((6000, 3), (131072, 4), (131072, 6), (131072, 7)):
+        doff = offsets_from_lengths(rng.geometric(1.0 / mean_len, size=L))
+        toff = split_same_text(rng, int(doff[-1]), 5)
+        C = L // 32
+        sel = np.sort(rng.choice(C, size=min(C // 10, 400), replace=False)).astype(np.int64)
+        spans = oracle.merge(sel, 32, L)
+        say(f"  L={L} M={toff.size - 1} spans={spans.shape[0]}")
+        check_project(doff, toff, spans)
+        check_project(doff, toff, np.array([[0, 1], [L - 1, L]], dtype=np.int64))   # first and last token
 
 
 def test_project_workload_char_models():
