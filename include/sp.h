@@ -173,9 +173,12 @@ sp_status sp_score_fp8(const sp_score_desc *desc, const void *q_dev,
 
 /* Which implementation sp_score picks for this shape and length on the current
  * device: 1 = the single-launch kernel that keeps K on chip and reads it from
- * HBM once (long prompts of head_dim 64 whose query group fits 64 padded rows),
- * 0 = the three-kernel path, -1 = invalid or unsupported desc. Results are the
- * same either way (to rounding); this is for reporting. Host-only. */
+ * HBM once, 0 = the three-kernel path, -1 = invalid or unsupported desc. The
+ * single-launch kernel takes one workgroup per compute unit, each owning T keys:
+ * head_dim 64: T = 512, query groups of up to 64 padded rows, 64 to 256
+ * workgroups (about 32K to 128K tokens); head_dim 128: T = 256, up to 32 padded
+ * rows, 96 to 256 workgroups (about 24K to 64K tokens). Results are the same
+ * either way (to rounding); this is for reporting. Host-only. */
 int32_t sp_score_is_fused(const sp_score_desc *desc, int64_t L);
 
 /*
@@ -193,9 +196,10 @@ sp_status sp_score_batch(const sp_score_desc *desc, const void *q_dev,
                          size_t ws_bytes, void *hip_stream);
 
 /* How sp_score_batch runs this batch on the current device: n > 0 = on the
- * single-launch kernel in n launches (every prompt empty or at least 512 tokens
- * long and no longer than 512 tokens per compute unit; prompts share launches,
- * each with all its keys in one), 0 = the three-kernel path, -1 = invalid
+ * single-launch kernel in n launches (every prompt empty or at least T tokens
+ * long and no longer than T tokens per compute unit, T as above; at least 64
+ * workgroups in all; prompts share launches, each with all its keys in one),
+ * 0 = the three-kernel path, -1 = invalid
  * arguments. Same results either way (to rounding). Host-only. */
 int32_t sp_score_batch_is_fused(const sp_score_desc *desc,
                                 const int64_t *offsets_host, int32_t B);

@@ -618,11 +618,19 @@ struct WsLayout {
 };
 
 // Shapes the fused single-launch kernel can hold on chip (any L; the length test is separate).
-bool fused_shape_ok(const Plan &p) { return p.D == 64 && p.rows_pad <= sp_fused::kMaxRows; }
-
-int fused_workgroups(int64_t L)
+bool fused_shape_ok(const Plan &p)
 {
-    const int64_t n = sp::ceil_div(L, sp_fused::kTileKeys);
+    return p.D == 64 ? p.rows_pad <= sp_fused::kMaxRows : p.rows_pad <= sp_fused::kMaxRowsWide;
+}
+
+// Keys a workgroup of the fused kernel owns: 512 at head_dim 64, 256 at head_dim 128 (twice the tile of
+// the two-pass path), and the fewest workgroups it is used with.
+int fused_tile(const Plan &p) { return p.D == 64 ? sp_fused::kTileKeys : sp_fused::kTileKeys / 2; }
+int fused_min_workgroups(const Plan &p) { return p.D == 64 ? sp_fused::kMinWorkgroups : sp_fused::kMinWorkgroupsWide; }
+
+int fused_workgroups(const Plan &p, int64_t L)
+{
+    const int64_t n = sp::ceil_div(L, fused_tile(p));
     return n > 0x7fffffff ? 0x7fffffff : (int)n;
 }
 
@@ -649,8 +657,8 @@ bool fused_applies(const Plan &p, int64_t L, int64_t k_stride_token)
 {
     if (!fused_shape_ok(p)) return false;
     if (k_stride_token > (int64_t(1) << 20)) return false;       // lane offsets within a tile are 32-bit
-    const int n_wg = fused_workgroups(L);
-    return n_wg >= sp_fused::kMinWorkgroups && n_wg <= 256 && n_wg <= device_compute_units();
+    const int n_wg = fused_workgroups(p, L);
+    return n_wg >= fused_min_workgroups(p) && n_wg <= 256 && n_wg <= device_compute_units();
 }
 
 // A ragged batch on the single-launch kernel: the prompts are packed into launches of at most one
@@ -672,8 +680,8 @@ bool plan_fused_batch(const Plan &p, const int64_t *offsets, int B, int64_t k_st
     for (int b = 0; b < B; ++b) {
         const int64_t len = offsets[b + 1] - offsets[b];
         if (len == 0) continue;
-        if (len < sp_fused::kTileKeys) return false;
-        const int64_t tiles = sp::ceil_div(len, sp_fused::kTileKeys);
+        if (len < fused_tile(p)) return false;
+        const int64_t tiles = sp::ceil_div(len, fused_tile(p));
         if (tiles > cap) return false;
         order.emplace_back((int)tiles, b);
         total_tiles += tiles;
@@ -718,7 +726,7 @@ WsLayout ws_layout(const Plan &p, int64_t n_tiles, int n_prompts)
     w.look = off; off = sp::align_up(off + sizeof(float) * (size_t)p.n_phases * p.rows_pad, 256);
     w.fused = off;
     if (fused_shape_ok(p)) {
-        int64_t n_wg = n_tiles * p.tile_keys / sp_fused::kTileKeys + n_prompts;
+        int64_t n_wg = n_tiles * p.tile_keys / fused_tile(p) + n_prompts;
         if (n_wg > 1024) n_wg = 1024;
         off += sp_fused::workspace_bytes(p.rows_pad, (int)n_wg, std::min(n_prompts, sp_fused::kMaxGroupPrompts));
     }
@@ -859,11 +867,13 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
         return launch_all<128, 1, true>(p, a, kp, st);
     }
     if (!batch && fused_applies(p, total, desc->k_stride_token)) {
-        const int n_wg = fused_workgroups(total);
+        const int n_wg = fused_workgroups(p, total);
         {
             sp_fused::FusedArgs f;
             std::memset(&f, 0, sizeof f);
             f.q = a.q;
+            f.head_dim = p.D;
+            f.tile_keys = fused_tile(p);
             f.k_stride_token = a.k_stride_token;
             f.k_stride_head = a.k_stride_head;
             f.L = total;
@@ -887,6 +897,8 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
             sp_fused::FusedArgs f;
             std::memset(&f, 0, sizeof f);
             f.q = a.q;
+            f.head_dim = p.D;
+            f.tile_keys = fused_tile(p);
             f.k_stride_token = a.k_stride_token;
             f.k_stride_head = a.k_stride_head;
             f.L = 0;

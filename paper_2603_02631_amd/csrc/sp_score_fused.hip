@@ -74,6 +74,7 @@ constexpr uint32_t kPoisonTag = 0xffffffffu;   // normaliser entry of a duty tha
 // LDS map in bytes. Everything but the K transit ring sits below 64 KB, so that reads of it can
 // carry the buffer's place in the instruction's offset field.
 constexpr int kQTileBytes = kMaxRowsF * kD * 2;                    // one Q tile: 64 rows x 128 bytes
+constexpr int kWideHalf = 4096;                                    // head_dim 128: dims 64..127 of a Q tile's 32 rows sit here
 constexpr int kOffQ1 = 0;                                          // [2] Q of the statistics pass, by phase parity
 constexpr int kOffQ2 = kOffQ1 + 2 * kQTileBytes;                   // [2] Q of the probability pass
 constexpr int kWstatsBytes = kFWaves * kMaxRowsF * 8;              // (max, sum) of 64 rows from 8 waves
@@ -364,11 +365,29 @@ struct Acc {
 constexpr int kMidInstr = 2;              // of the four loads of sub-tile 0: issued right after the barrier ...
 constexpr int kProbInstr = kSubInstr - kMidInstr;     // ... and between the MFMA steps of the probability pass
 
-template <int NB, int GB, int PAR>
+template <int NB, int GB, int PAR, bool W>
 __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t cinit_ad,
                                           Acc<NB> &acc, const KIssue &ki, const uint32_t (&voff)[2])
 {
     static_assert(kProbInstr == 2 && (NB * GB == 1 || NB * GB == 2), "one load per row block, or one per step");
+    if constexpr (W) {
+        // head_dim 128: one chain of eight MFMA steps over both halves of the 32 keys' rows
+        static_assert(NB == 1 && GB == 1, "one block of 32 query rows");
+        bf16x8 q0[kKS], q1[kKS];
+        f32x16 d;
+        lift_q_and_seed<kOffQ2 + PAR * kQTileBytes>(lc, cinit_ad, q0, d);
+        lift_at<kOffQ2 + PAR * kQTileBytes + kWideHalf>(lc, q1);
+#pragma unroll
+        for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q0[t], kf[0][t], d, 0, 0, 0);
+        k_issue<1>(ki, voff, kMidInstr);
+#pragma unroll
+        for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q1[t], kf[1][t], d, 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc.mx[0][0][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[0][0][e]);
+        k_issue<1>(ki, voff, kMidInstr + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        return;
+    }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
@@ -395,11 +414,11 @@ __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const La
     }
 }
 
-template <int NB>
+template <int NB, int NSE>
 __device__ __forceinline__ void close_layer(Acc<NB> &acc, float c)
 {
 #pragma unroll
-    for (int s = 0; s < kNS; ++s) {
+    for (int s = 0; s < NSE; ++s) {
         float sum = 0.f;
 #pragma unroll
         for (int b = 0; b < NB; ++b)
@@ -491,7 +510,7 @@ __device__ __forceinline__ void store_row_stats(uint32_t ad, float m, float l, f
 template <int NBLK>
 constexpr int kLoadsBehindLse = kSubInstr - kSubInstr / (NBLK * kNS);
 
-template <int NBLK, int PAR>
+template <int NBLK, int PAR, bool W>
 __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t koff0,
                                            uint32_t koff1, uint32_t wstats_ad, int lo0, int hi0, int lane,
                                            const KIssue &ki, const uint32_t (&voff)[2], const uint64_t *lse_row,
@@ -499,6 +518,25 @@ __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], cons
 {
     constexpr int kPerStep = kSubInstr / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
     const int hf = lane >> 5;
+    if constexpr (W) {
+        // head_dim 128: the two sub-tiles are the two halves of the rows of this wave's 32 keys
+        static_assert(NBLK == 1, "one block of 32 query rows");
+        bf16x8 q0[kKS], q1[kKS];
+        lift_k_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, q0);
+        lift_at<kOffQ1 + PAR * kQTileBytes + kWideHalf>(lc, q1);
+        f32x16 d = logits32(kf[0], q0);
+#pragma unroll
+        for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][t], q1[t], d, 0, 0, 0);
+        k_issue<kPerStep>(ki, voff, 0);
+        if (lse_row != nullptr) stage_exchange_rows(xlse_ad, lse_row, look_row, rows_pad, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        float m = neg_inf(), l = 0.f;
+        fold_logits(d, m, l, c, lo0, hi0, hf);
+        store_row_stats(wstats_ad, m, l, c, hf);
+        k_issue<kPerStep>(ki, voff, kPerStep);
+        __builtin_amdgcn_sched_barrier(0);
+        return;
+    }
     const int lo1 = lo0 - 32, hi1 = hi0 - 32;      // this wave's keys lo0 <= key < hi0 (of 64) are the workgroup's
     bf16x8 qf[kKS];
     lift_k_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, qf);
@@ -644,7 +682,7 @@ struct Walk {
 // ones it needs.
 // EXTRA selects the variant that also serves paged keys (an upper bound on the tile's rows) and
 // lookahead keys in the normaliser; the plain variant carries none of their code or registers.
-template <int NB, int GB, int SLOT, int PAR, bool EXTRA>
+template <int NB, int GB, int SLOT, int PAR, bool EXTRA, bool W>
 __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, const GroupTable &gt, int s, int n_phases, Ring &ring,
                                      Acc<NB> &acc, const LaneConst &lc, Walk &wk, unsigned char *lds, uint32_t lds0,
                                      uint64_t wave_off, int r_range)
@@ -730,7 +768,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
     ki.base = kbase;
     ki.step_bytes = 8u * stride_bytes;
     if (lc.qoff >= 0) {       // padding rows of the Q tiles stay zero; the Q blocks of consecutive phases are contiguous
-        const uint32_t qblock = (uint32_t)(a.group * a.n_q * kD * 2);
+        const uint32_t qblock = (uint32_t)(a.group * a.n_q * kD * 2) * (W ? 2u : 1u);
         const char *q1src = reinterpret_cast<const char *>(a.q) + (uint32_t)min(s + 1, n_phases - 1) * qblock;
         const char *q2src = reinterpret_cast<const char *>(a.q) + (uint32_t)clampi(pl, 0, n_phases - 1) * qblock;
         dma_u<kOffQ1 + (1 - PAR) * kQTileBytes>((uint32_t)lc.qoff, q1src, lds0 + wave * 1024);
@@ -742,9 +780,9 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
     {
         if (do_prob) {
             const uint32_t cinit_ad = lds0 + kOffCinit + (1 - PAR) * (kMaxRowsF * 4) + ((uint32_t)(lane & 32) << 1);
-            prob_pass<NB, GB, 1 - PAR>(ring.kf[SLOT], lc, cinit_ad, acc, ki, voff);
+            prob_pass<NB, GB, 1 - PAR, W>(ring.kf[SLOT], lc, cinit_ad, acc, ki, voff);
             if (wk.c.kv == a.n_kv_heads - 1 && (a.layer_agg == SP_LAYER_MEAN || wk.c.layer == a.n_layers - 1))
-                close_layer<NB>(acc, a.c);
+                close_layer<NB, W ? 1 : kNS>(acc, a.c);
         } else {
             k_issue<kProbInstr>(ki, voff, kMidInstr);
         }
@@ -755,17 +793,18 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
     {
         KIssue ki;
         ki.lds_dst = lds0 + sub_slot_off(wave, slot_next, 1);
-        ki.base = kbase + (int64_t)32 * stride_bytes;
+        ki.base = kbase + (W ? (int64_t)(kD * 2) : (int64_t)32 * stride_bytes);     // W: the rows' second halves
         ki.step_bytes = 8u * stride_bytes;
         const uint64_t *lse_row = wave == kLseWave ? a.lse + ((size_t)(clampi(pl, 0, n_phases - 1) % kSlots) * a.n_gp + a.p_idx) * a.rows_pad : nullptr;
         const float *look_row = nullptr;
         if (EXTRA && a.look != nullptr) look_row = a.look + (size_t)clampi(pl, 0, n_phases - 1) * a.rows_pad;
         // r_range = r_lo | r_hi << 16 (r_hi = 512 without EXTRA): this wave's share of it
-        const int lo0 = (r_range & 0xffff) - wave * kNS * 32;
-        const int hi0 = EXTRA ? (r_range >> 16) - wave * kNS * 32 : kNS * 32;
+        constexpr int kWaveKeys = W ? 32 : kNS * 32;
+        const int lo0 = (r_range & 0xffff) - wave * kWaveKeys;
+        const int hi0 = EXTRA ? (r_range >> 16) - wave * kWaveKeys : kWaveKeys;
         if (do_stats) {
             const uint32_t wstats_ad = lds0 + kOffWstats + PAR * kWstatsBytes + wave * (kMaxRowsF * 8) + ((uint32_t)(lane & 31) << 3);
-            stats_pass<NB * GB, PAR>(a.c, ring.kf[SLOT], lc, sub_slot_off(wave, wk.slot0, 0),
+            stats_pass<NB * GB, PAR, W>(a.c, ring.kf[SLOT], lc, sub_slot_off(wave, wk.slot0, 0),
                                      sub_slot_off(wave, wk.slot0, 1), wstats_ad, lo0, hi0, lane, ki, voff, lse_row,
                                      look_row, a.rows_pad, lds0 + kOffXlse);
         } else {
@@ -917,9 +956,16 @@ __device__ __forceinline__ void fold_model_constants(FusedArgs &a)
     }
 }
 
-template <int NB, int GB, bool EXTRA, class M>
+// W: head_dim 128. A workgroup owns 256 keys, a wave 32; the two "sub-tiles" of a wave are the two
+// 64-element halves of its keys' rows (same transit ring, same fragment ring: kf[s][t] holds MFMA
+// k-step 4s + t), Q tiles hold 32 rows as two half-tiles, and a logit is one chain of eight MFMA steps.
+template <int NB, int GB, bool EXTRA, class M, bool W = false>
 __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, LayerPtrs kp, GroupTable gt)
 {
+    static_assert(!W || (NB == 1 && GB == 1 && !M::kFixed), "head_dim 128: one block of 32 query rows");
+    constexpr int kTile = W ? kFTile / 2 : kFTile;            // keys per workgroup
+    constexpr int kWaveKeys = kTile / kFWaves;
+    constexpr int kHeadDim = W ? 2 * kD : kD;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[kLdsBytes];
     fold_model_constants<M>(a);
 
@@ -943,17 +989,17 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
         p_start = gt.start[p];
         p_len = gt.len[p];
         wl = w - gt.w0[p];
-        a.q += (size_t)gt.prompt[p] * ((size_t)a.n_layers * a.n_q_heads * a.n_q * kD);
+        a.q += (size_t)gt.prompt[p] * ((size_t)a.n_layers * a.n_q_heads * a.n_q * kHeadDim);
         a.p_idx = p;
         a.n_gp = gt.n;
     } else {
         a.p_idx = 0;
         a.n_gp = 1;
     }
-    const int64_t j0l = (paged || (int64_t)(wl + 1) * kFTile <= p_len) ? (int64_t)wl * kFTile : p_len - kFTile;
+    const int64_t j0l = (paged || (int64_t)(wl + 1) * kTile <= p_len) ? (int64_t)wl * kTile : p_len - kTile;
     const int64_t j0 = p_start + j0l;         // first key of the tile in the layer's key array
-    const int r_lo = (int)((int64_t)wl * kFTile - j0l);
-    const int r_hi = (int)(p_len - j0l < kFTile ? p_len - j0l : kFTile);
+    const int r_lo = (int)((int64_t)wl * kTile - j0l);
+    const int r_hi = (int)(p_len - j0l < kTile ? p_len - j0l : kTile);
     const int r_range = r_lo | (r_hi << 16);
     const uint32_t lds0 = lds_addr(lds);
     const uint32_t stride_bytes = (uint32_t)a.k_stride_token * 2u;
@@ -977,11 +1023,12 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
         const uint32_t swz = (uint32_t)(lane >> 4);               // (row >> 1) & 7 of row = lane >> 3 in an even instruction
         lc.koff[0] = rowpart + (((uint32_t)(lane & 7) ^ swz) << 4);
         lc.koff[1] = rowpart + (((uint32_t)(lane & 7) ^ (swz | 4u)) << 4);
-        const int row = wave * 8 + (lane >> 3);
+        // a wave's slice of a Q tile: 8 rows (W: of one half-tile, waves 4..7 take the second halves)
+        const int row = (W ? (wave & 3) : wave) * 8 + (lane >> 3);
         int g, n;
         lc.qoff = -1;
         if (row < a.rows_pad && row_valid<NB>(a, row, g, n))
-            lc.qoff = ((g * a.n_q + n) * kD + (((lane & 7) ^ ((row >> 1) & 7)) << 3)) * 2;
+            lc.qoff = ((g * a.n_q + n) * kHeadDim + (W ? (wave >> 2) * kD : 0) + (((lane & 7) ^ ((row >> 1) & 7)) << 3)) * 2;
     }
 
     Ring ring;
@@ -997,11 +1044,11 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
 
     // byte offset of this wave's first key within a (layer, kv head): uniform, kept in scalar registers
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    uint64_t wave_off = (uint64_t)(j0 + wave_u * 64) * (uint64_t)a.k_stride_token * 2u;
+    uint64_t wave_off = (uint64_t)(j0 + wave_u * kWaveKeys) * (uint64_t)a.k_stride_token * 2u;
     if (paged) {
         const int64_t page = j0 / a.page_tokens;
         wave_off = ((uint64_t)a.block_table[page] * (uint64_t)a.page_stride +
-                    (uint64_t)(j0 - page * a.page_tokens + wave_u * 64) * (uint64_t)a.k_stride_token) * 2u;
+                    (uint64_t)(j0 - page * a.page_tokens + wave_u * kWaveKeys) * (uint64_t)a.k_stride_token) * 2u;
     }
     wave_off = (uint64_t)uniform32((uint32_t)wave_off) | ((uint64_t)uniform32((uint32_t)(wave_off >> 32)) << 32);
 
@@ -1011,7 +1058,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     for (int s2 = 0; s2 < kNS; ++s2) {
         KIssue ki;
         ki.lds_dst = lds0 + sub_slot_off(wave_u, 0, s2);
-        ki.base = reinterpret_cast<const char *>(kp.p[0]) + wave_off + (uint64_t)(s2 * 32) * stride_bytes;
+        ki.base = reinterpret_cast<const char *>(kp.p[0]) + wave_off + (W ? (uint64_t)(s2 * kD * 2) : (uint64_t)(s2 * 32) * stride_bytes);
         ki.step_bytes = 8u * stride_bytes;
         k_issue<kSubInstr>(ki, lc.koff, 0);
     }
@@ -1031,19 +1078,19 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     // instruction stream uniform. The last probability pass (phase n_phases - 1) runs in step n_phases + 3.
     const int n_steps = (n_phases + kLag + 1 + 3) / 4 * 4;
     for (int s0 = 0; s0 < n_steps; s0 += 4) {
-        step<NB, GB, 0, 0, EXTRA>(a, kp, gt, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 1, 1, EXTRA>(a, kp, gt, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 2, 0, EXTRA>(a, kp, gt, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 3, 1, EXTRA>(a, kp, gt, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 0, 0, EXTRA, W>(a, kp, gt, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 1, 1, EXTRA, W>(a, kp, gt, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 2, 0, EXTRA, W>(a, kp, gt, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 3, 1, EXTRA, W>(a, kp, gt, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
     }
     vm_wait<0>();               // no direct-to-LDS load may outlive the workgroup
     lds_barrier();
     // the call has failed if any workgroup raised the status word; this workgroup's own failures are in it
     const bool failed = __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
 #pragma unroll
-    for (int s = 0; s < kNS; ++s) {
+    for (int s = 0; s < kWaveKeys / 32; ++s) {
         const float both = acc.total[s] + __shfl_xor(acc.total[s], 32);
-        const int key = (wave * kNS + s) * 32 + col;
+        const int key = wave * kWaveKeys + s * 32 + col;
         if (hf == 0 && key >= r_lo && key < r_hi) a.scores[j0 + key] = failed ? __uint_as_float(0x7fc00000u) : both * a.out_scale;   // quiet NaN marks a failed call
     }
 }
@@ -1090,6 +1137,22 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, const GroupTable *group, bool
     GroupTable gt;
     std::memset(&gt, 0, sizeof gt);
     if (group) gt = *group;
+    // The kernel places workgroup w of a prompt at key w * tile: the grid must be exactly the prompts' tiles
+    // (a surplus workgroup of a paged prompt would look up a page the table does not have).
+    const int64_t tile = a.tile_keys;
+    if (!(a.head_dim == kD && tile == kFTile) && !(a.head_dim == 2 * kD && tile == kFTile / 2))
+        return sp::fail(SP_ERR_INVALID_ARG, "fused score kernel: head_dim %d with %d keys per workgroup", a.head_dim, a.tile_keys);
+    if (gt.n == 0) {
+        if (a.L < tile || sp::ceil_div(a.L, tile) != a.n_wg)
+            return sp::fail(SP_ERR_INVALID_ARG, "fused score kernel: %d workgroups for %lld keys", a.n_wg, (long long)a.L);
+    } else {
+        if (gt.n < 0 || gt.n > sp_fused::kMaxGroupPrompts || gt.w0[0] != 0 || gt.w0[gt.n] != a.n_wg)
+            return sp::fail(SP_ERR_INVALID_ARG, "fused score kernel: group table does not cover %d workgroups", a.n_wg);
+        for (int i = 0; i < gt.n; ++i)
+            if (gt.len[i] < tile || sp::ceil_div(gt.len[i], tile) != gt.w0[i + 1] - gt.w0[i])
+                return sp::fail(SP_ERR_INVALID_ARG, "fused score kernel: prompt %d of the group: %d workgroups for %lld keys", i,
+                                gt.w0[i + 1] - gt.w0[i], (long long)gt.len[i]);
+    }
     uint64_t *base = static_cast<uint64_t *>(ws);
     const size_t n_part = (size_t)kSlots * a.rows_pad * a.n_wg, n_lse = (size_t)kSlots * a.rows_pad * (gt.n > 0 ? gt.n : 1);
     a.part = base;
@@ -1107,8 +1170,16 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, const GroupTable *group, bool
     // with NaN scores and the status word set instead of hanging.
     const bool extra = a.look != nullptr || a.block_table != nullptr || gt.n > 0;
     const dim3 grid(a.n_wg), block(kFThreads);
+    if (a.head_dim == 2 * kD) {
+        if (a.n_nblk != 1 || a.n_gblk != 1)
+            return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel, head_dim 128: %d x %d row blocks", a.n_nblk, a.n_gblk);
+        if (extra) hipLaunchKernelGGL((sp_fused_kernel<1, 1, true, AnyModel, true>), grid, block, 0, st, a, kp, gt);
+        else hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, AnyModel, true>), grid, block, 0, st, a, kp, gt);
+        SP_HIP_CHECK(hipGetLastError());
+        return SP_OK;
+    }
     // the fixed-model instantiations apply when every folded constant equals the call's value
-    const bool draft = !extra && a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
+    const bool draft = !extra && a.head_dim == kD && a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
                        a.c == kScaleEighthLog2e && a.inv_c == 1.0f / kScaleEighthLog2e;
     if (draft && a.n_q == 16) {
         if (a.n_wg == 256) hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 256>>), grid, block, 0, st, a, kp, gt);

@@ -6,10 +6,12 @@
 
 namespace sp_fused {
 
-constexpr int kTileKeys = 512;   // keys owned by one workgroup
+constexpr int kTileKeys = 512;   // keys owned by one workgroup at head_dim 64; 256 at head_dim 128
+constexpr int kMaxRowsWide = 32; // head_dim 128: padded query rows per kv head
 constexpr int kMaxRows = 64;     // padded query rows per kv head the kernel holds on chip
 constexpr int kSlots = 8;        // depth of the exchange ring
-constexpr int kMinWorkgroups = 64;
+constexpr int kMinWorkgroups = 64;       // head_dim 64: shorter prompts are faster on the two-pass path
+constexpr int kMinWorkgroupsWide = 96;   // head_dim 128 (measured crossover near 24K tokens)
 constexpr int kMaxGroupPrompts = 32;   // prompts one launch can serve
 
 // Prompts of a ragged batch that share a launch: prompt i of the group is prompt `prompt[i]` of the
@@ -24,7 +26,9 @@ struct GroupTable {
 };
 
 struct FusedArgs {
-    const uint16_t *q;           // [Lyr][H][n_q][64]
+    const uint16_t *q;           // [Lyr][H][n_q][head_dim]
+    int32_t head_dim;            // 64 or 128
+    int32_t tile_keys;           // keys per workgroup: 512 at head_dim 64, 256 at head_dim 128
     int64_t k_stride_token, k_stride_head;
     int64_t L;
     uint64_t *part;              // [kSlots][n_wg][rows_pad]  (max, sum exp) partials, parity in bit 63

@@ -145,12 +145,14 @@ FUSED_BATCHES = [
     ("batch_g8_two_gblocks", 1, 16, 2, 64, 8, [33000, 1024, 2047]),
     ("batch_several_launches", 1, 4, 1, 64, 8, [70000, 65000, 60000, 3000, 1500]),
     ("batch_single_prompt", 2, 8, 2, 64, 5, [40000]),
+    ("batch_d128_one_launch", 2, 4, 2, 128, 8, [9000, 256, 300, 0, 7000, 4001]),
+    ("batch_d128_several_launches", 1, 4, 2, 128, 8, [40000, 33000, 30000, 1500]),
 ]
 
 
 @pytest.mark.parametrize("case", FUSED_BATCHES, ids=[c[0] for c in FUSED_BATCHES])
 def test_score_batch_on_the_single_launch_kernel(case):
-    """Ragged batches whose prompts are all at least one 512-key tile long take the single-launch
+    """Ragged batches whose prompts are all at least one tile (512 keys; 256 at head_dim 128) long take the single-launch
     kernel, several prompts to a launch: every prompt against the oracle run on that prompt alone, both
     modes, both layouts, deterministic."""
     import paper_2603_02631_amd as sp
@@ -196,7 +198,8 @@ def test_score_mid_size_config():
         say(f"  mode {mode}: max rel err {np.max(np.abs(got - want) / want):.2e}")
 
 
-# Long single prompts of head_dim 64 take the single-launch kernel that keeps K on chip.
+# Long single prompts take the single-launch kernel that keeps K on chip (head_dim 64: up to 64 padded
+# query rows and 128K tokens; head_dim 128: up to 32 rows and 64K tokens).
 FUSED_SHAPES = [
     # name, Lyr, H, Hkv, d, n_q, L
     ("fused_g4_nq16_tail", 2, 8, 2, 64, 16, 40000),       # 79 workgroups, 64-key tail
@@ -210,7 +213,29 @@ FUSED_SHAPES = [
     ("fused_draft_model_nq8", 16, 32, 8, 64, 8, 33000),
     ("fused_draft_model_nq16", 16, 32, 8, 64, 16, 32768 + 513),
     ("fused_draft_model_nq8_full_grid", 16, 32, 8, 64, 8, 131072 - 100),     # 256 workgroups, ragged last tile
+    # head_dim 128 (up to 32 padded query rows): 256 keys per workgroup, from 96 workgroups up
+    ("fused_d128_g2_nq8", 3, 4, 2, 128, 8, 25000),                           # 98 workgroups, 168-key tail
+    ("fused_d128_g4_nq8_rows32", 2, 8, 2, 128, 8, 24576 + 1),                # 1-key tail
+    ("fused_d128_g2_nq5_padding", 2, 4, 2, 128, 5, 26000),
+    ("fused_d128_g3_nq8_padding", 2, 6, 2, 128, 8, 25500),
+    ("fused_d128_full_grid", 2, 4, 2, 128, 8, 65536 - 100),                  # 256 workgroups, ragged last tile
+    ("fused_d128_28_phases", 7, 8, 4, 128, 8, 24576),
+    ("fused_d128_40k", 2, 4, 2, 128, 8, 40000),
 ]
+
+
+def test_which_prompts_take_the_single_launch_kernel():
+    """The lengths at which sp_score changes kernels (sp_score_is_fused): head_dim 64 from 64 workgroups of
+    512 keys up to 256; head_dim 128 from 96 workgroups of 256 keys up to 256, and only with at most 32
+    padded query rows."""
+    import paper_2603_02631_amd as sp
+    from gpu_util import make_desc
+    def fused(d, G, n_q, L):
+        return sp.sp_score_is_fused(make_desc(2, 2 * G, 2, d, n_q, 0.1, 0, "HND", L), L)
+    assert [fused(64, 4, 16, L) for L in (63 * 512, 63 * 512 + 1, 131072, 131073)] == [0, 1, 1, 0]
+    assert [fused(128, 2, 8, L) for L in (95 * 256, 95 * 256 + 1, 65536, 65537)] == [0, 1, 1, 0]
+    assert fused(128, 4, 8, 40000) == 1 and fused(128, 4, 16, 40000) == 0 and fused(128, 8, 8, 40000) == 0
+    assert fused(64, 8, 16, 40000) == 0          # 128 padded rows
 
 
 @pytest.mark.parametrize("shape", FUSED_SHAPES, ids=[s[0] for s in FUSED_SHAPES])
@@ -276,6 +301,7 @@ LOOK_SHAPES = [
     ("look_nq1_d64", 2, 4, 2, 64, 1, 300),
     ("look_fused_g4_nq16", 3, 8, 2, 64, 16, 33000),
     ("look_fused_g3_nq5_padding", 2, 6, 2, 64, 5, 35000),
+    ("look_fused_d128_g2_nq8", 2, 4, 2, 128, 8, 25000),
 ]
 
 
@@ -315,6 +341,9 @@ PAGED_SHAPES = [
     ("paged_fused_4k_ragged_tail", 3, 8, 2, 64, 16, 33000 + 77, 4096, "HND"),
     ("paged_fused_4k_whole_pages", 2, 8, 2, 64, 8, 8 * 4096, 4096, "HND"),
     ("paged_fused_512_nhd", 2, 6, 2, 64, 5, 35000, 512, "NHD"),
+    ("paged_fused_d128_2k_ragged_tail", 2, 4, 2, 128, 8, 25000 + 77, 2048, "HND"),
+    ("paged_fused_d128_512_nhd", 2, 4, 2, 128, 5, 24600, 512, "NHD"),
+    ("paged_fused_d128_40k_4k_pages", 1, 4, 2, 128, 8, 40000 + 5, 4096, "HND"),
 ]
 
 
