@@ -35,8 +35,8 @@ ROTATE_BYTES = 2 << 30          # K buffers are rotated over at least this much 
 # It is reported only while the kernel sources are the ones the counters were taken on.
 TRAFFIC = {
     "workload": "long-128k",
-    "sources_sha256": None,
-    "fetch_bytes": 1090789.5 * 2048,      # FETCH_SIZE 1090789.5 per dispatch; the 1 GiB copy reads 524307 -> 2 KiB per count
+    "sources_sha256": "25bded116cec0d2ec540fa77c2555f0b6b170e65972f9b96283c840cc0f920ab",
+    "fetch_bytes": 1090816.0 * 2048,      # FETCH_SIZE 1090816.0 per dispatch; the 1 GiB copy reads 524320 -> 2 KiB per count
     "write_bytes": 16960.0 * 1024,        # WRITE_SIZE 16960.0 per dispatch; the 1 GiB copy writes 1048576 -> 1 KiB per count
 }
 KERNEL_SOURCES = ["sp_score_fused.hip", "sp_score_fused.hpp", "sp_score_dev.hpp"]     # the dominant kernel and its headers
@@ -172,6 +172,11 @@ def main() -> int:
     else:
         fused = 0 if fp8 else sp.sp_score_is_fused(desc, T)
     calls = [0]
+    # ragged batch: the prompts' select / project chains (one-workgroup kernels) are independent of each other
+    # and go round robin onto a few streams of default priority, so that they overlap
+    side = [torch.cuda.Stream(device=dev) for _ in range(min(4, B))] if ragged else []
+    scored = torch.cuda.Event()
+    side_done = [torch.cuda.Event() for _ in side]
 
     def step(ev=None):
         # two events per step bracket the score call on its stream; the rest of the step follows from the wall clock
@@ -187,11 +192,19 @@ def main() -> int:
             sp.sp_score(desc, qd, k_dev, T, scores, ws1, stream=stream)
         if ev is not None:
             ev[1].record(stream)
-        for p in per:
+        if side:
+            scored.record(stream)
+            for sd in side:
+                sd.wait_event(scored)
+        for i, p in enumerate(per):
+            st = side[i % len(side)] if side else stream
             sp.sp_select(p["scores"], p["L"], w.pool, w.chunk, p["k"], p["sel"], p["spans"], p["n_spans"], None,
-                         p["ws"], stream=stream)
+                         p["ws"], stream=st)
             sp.sp_project(p["dd"], p["L"], p["td"], p["M"], p["spans"], p["n_spans"], p["k"], p["tsp"], p["n_t"],
-                          p["mask"], p["n_kept"], stream=stream)
+                          p["mask"], p["n_kept"], stream=st)
+        for sd, e in zip(side, side_done):     # the next step's score call overwrites the scores: it waits for all of them
+            e.record(sd)
+            stream.wait_event(e)
 
     def timed(n):
         events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n)]
