@@ -1179,9 +1179,15 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, const GroupTable *group, bool
         return SP_OK;
     }
     // the fixed-model instantiations apply when every folded constant equals the call's value
-    const bool draft = !extra && a.head_dim == kD && a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
-                       a.c == kScaleEighthLog2e && a.inv_c == 1.0f / kScaleEighthLog2e;
-    if (draft && a.n_q == 16) {
+    const bool draft_shape = a.head_dim == kD && a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
+                             a.c == kScaleEighthLog2e && a.inv_c == 1.0f / kScaleEighthLog2e;
+    const bool draft = !extra && draft_shape;
+    const bool draft_batch = draft_shape && gt.n > 0 && a.look == nullptr && a.block_table == nullptr;    // several prompts a launch
+    if (draft_batch && a.n_q == 16) {
+        hipLaunchKernelGGL((sp_fused_kernel<2, 1, true, Draft16x32x8<16, 0>>), grid, block, 0, st, a, kp, gt);
+    } else if (draft_batch && a.n_q == 8) {
+        hipLaunchKernelGGL((sp_fused_kernel<1, 1, true, Draft16x32x8<8, 0>>), grid, block, 0, st, a, kp, gt);
+    } else if (draft && a.n_q == 16) {
         if (a.n_wg == 256) hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 256>>), grid, block, 0, st, a, kp, gt);
         else hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 0>>), grid, block, 0, st, a, kp, gt);
     } else if (draft && a.n_q == 8) {

@@ -146,6 +146,9 @@ FUSED_BATCHES = [
     ("batch_several_launches", 1, 4, 1, 64, 8, [70000, 65000, 60000, 3000, 1500]),
     ("batch_single_prompt", 2, 8, 2, 64, 5, [40000]),
     ("batch_d128_one_launch", 2, 4, 2, 128, 8, [9000, 256, 300, 0, 7000, 4001]),
+    # the kernel instantiations with a fixed model shape (16 layers, 32 / 8 heads) for several prompts a launch
+    ("batch_draft_model_nq16", 16, 32, 8, 64, 16, [20000, 13000, 600]),
+    ("batch_draft_model_nq8", 16, 32, 8, 64, 8, [15000, 18000, 512, 0, 1000]),
     ("batch_d128_several_launches", 1, 4, 2, 128, 8, [40000, 33000, 30000, 1500]),
 ]
 
