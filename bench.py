@@ -35,7 +35,7 @@ ROTATE_BYTES = 2 << 30          # K buffers are rotated over at least this much 
 # It is reported only while the kernel sources are the ones the counters were taken on.
 TRAFFIC = {
     "workload": "long-128k",
-    "sources_sha256": "25bded116cec0d2ec540fa77c2555f0b6b170e65972f9b96283c840cc0f920ab",
+    "sources_sha256": "0258a3351a97b772383b9428347f33e6582f9caec1baf7dbdde7f8adad796a0c",
     "fetch_bytes": 1090816.0 * 2048,      # FETCH_SIZE 1090816.0 per dispatch; the 1 GiB copy reads 524320 -> 2 KiB per count
     "write_bytes": 16960.0 * 1024,        # WRITE_SIZE 16960.0 per dispatch; the 1 GiB copy writes 1048576 -> 1 KiB per count
 }
@@ -82,8 +82,9 @@ def main() -> int:
                     help="fp8: the keys quantised to E4M3 codes with one scale per layer and kv head, scored by "
                          "sp_score_fp8 (a line of its own beside the bf16 one, never instead of it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-graph", action="store_true",
-                    help="batches: launch sp_select / sp_project call by call instead of replaying them from a HIP graph")
+    ap.add_argument("--batch-post", default="batch", choices=["batch", "graph", "eager"],
+                    help="ragged batch: sp_select_batch + sp_project_batch (three launches for all prompts), or "
+                         "sp_select + sp_project per prompt replayed from a HIP graph / launched call by call")
     ap.add_argument("--cpu-sample-layers", type=int, default=0,
                     help="layers the CPU oracle is timed on with all cores (0 = all layers of the workload)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -197,6 +198,25 @@ def main() -> int:
             main.wait_event(e)
 
     graph = [None]
+    batch_post = None
+    if ragged and args.batch_post == "batch":
+        # all prompts in three launches: packed inputs and outputs
+        kept_host = [0]
+        for p in per:
+            kept_host.append(kept_host[-1] + p["k"])
+        moff_host = [0]
+        for p in per:
+            moff_host.append(moff_host[-1] + p["M"])
+        K = kept_host[-1]
+        i64 = dict(dtype=torch.int64, device=dev)
+        batch_post = dict(
+            kept_host=kept_host, moff_host=moff_host, kept_dev=torch.tensor(kept_host, **i64),
+            moff_dev=torch.tensor(moff_host, **i64), dd=torch.cat([p["dd"] for p in per]), td=torch.cat([p["td"] for p in per]),
+            sel=torch.empty(K, dtype=torch.int32, device=dev), spans=torch.empty((K, 2), **i64),
+            n_spans=torch.zeros(B, dtype=torch.int32, device=dev), tsp=torch.empty((K, 2), **i64),
+            n_t=torch.zeros(B, dtype=torch.int32, device=dev), mask=torch.empty(moff_host[-1], dtype=torch.uint8, device=dev),
+            n_kept=torch.zeros(B, **i64),
+            ws=torch.empty(sp.sp_select_batch_workspace(T, B, w.chunk), dtype=torch.uint8, device=dev))
 
     def step(ev=None):
         # two events per step bracket the score call on its stream; the rest of the step follows from the wall clock
@@ -212,7 +232,14 @@ def main() -> int:
             sp.sp_score(desc, qd, k_dev, T, scores, ws1, stream=stream)
         if ev is not None:
             ev[1].record(stream)
-        if graph[0] is not None:
+        if batch_post is not None:
+            bp = batch_post
+            sp.sp_select_batch(scores, off_host, off_dev, w.pool, w.chunk, bp["kept_host"], bp["kept_dev"], bp["sel"],
+                               bp["spans"], bp["n_spans"], None, bp["ws"], stream=stream)
+            sp.sp_project_batch(bp["dd"], off_host, off_dev, bp["td"], bp["moff_host"], bp["moff_dev"], bp["spans"],
+                                bp["n_spans"], bp["kept_host"], bp["kept_dev"], bp["tsp"], bp["n_t"], bp["mask"],
+                                bp["n_kept"], stream=stream)
+        elif graph[0] is not None:
             graph[0].replay()
         else:
             enqueue_select_project(stream)
@@ -271,7 +298,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del a_src, a_dst
     torch.cuda.synchronize()
-    if not args.no_graph and len(per) > 1:     # one prompt: three launches, eager is as fast (0.034 vs 0.041 ms)
+    if ragged and args.batch_post == "graph":
         graph[0] = build_graph()
         time.sleep(1.0)          # the first calls below are meant to follow an idle period
     first_wall, first_score = timed(args.first_calls) if args.first_calls > 0 else (None, np.zeros(0))
@@ -291,7 +318,20 @@ def main() -> int:
     if status != 0 or not bool(torch.isfinite(scores).all()):
         print(f"bench.py: invalid scores after the timed steps (status word {status})", file=sys.stderr)
         return 4
-    n_kept = sum(int(p["n_kept"].item()) for p in per)
+    if batch_post is not None:
+        # the batch calls against the per-prompt calls on the same scores: identical results
+        torch.cuda.synchronize()
+        got = (batch_post["n_kept"].cpu().numpy().copy(), batch_post["mask"].cpu().numpy().copy())
+        enqueue_select_project(stream)
+        torch.cuda.synchronize()
+        want_kept = np.array([int(p["n_kept"].item()) for p in per])
+        want_mask = np.concatenate([p["mask"].cpu().numpy() for p in per])
+        if not (np.array_equal(got[0], want_kept) and np.array_equal(got[1], want_mask)):
+            print("bench.py: sp_select_batch / sp_project_batch differ from the per-prompt calls", file=sys.stderr)
+            return 4
+        n_kept = int(got[0].sum())
+    else:
+        n_kept = sum(int(p["n_kept"].item()) for p in per)
 
     # ---- streaming-read probe over the same K buffers: the achievable rate on this device ----
     sink = torch.zeros(1, dtype=torch.int64, device=dev)
@@ -321,7 +361,8 @@ def main() -> int:
            "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "n_q": w.n_q, "pool": w.pool, "chunk": w.chunk,
            "keep": f"{w.keep_num}/{w.keep_den}", "layer_agg": args.layer_agg, "k_layout": "HND", "k_dtype": args.k_dtype,
            "k_rotating_copies": n_rot, "score_path": "single-launch" if fused == 1 else "three-kernel",
-           "select_project_launch": "hip graph" if graph[0] is not None else "eager"}
+           "select_project_launch": ("batch calls" if batch_post is not None else
+                                     "hip graph" if graph[0] is not None else "per prompt")}
     if ragged:
         cfg.update({"prompts": B, "total_tokens": T, "min_len": int(lengths.min()), "max_len": int(lengths.max())})
     else:

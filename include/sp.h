@@ -236,6 +236,34 @@ sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_w,
                     void *hip_stream);
 
 /*
+ * sp_select for a ragged batch of B prompts in two launches (Algorithm 1, the
+ * same four steps, each prompt on its own: pooling windows and chunks never
+ * cross a prompt's end). scores_dev is packed as sp_score_batch leaves it:
+ * prompt b owns [offsets[b], offsets[b+1]). kept_off holds the prefix sums of the
+ * prompts' chunk counts to keep, kept_off[0] = 0: prompt b keeps
+ * k_b = kept_off[b+1] - kept_off[b] chunks, 1 <= k_b <= ceil(L_b / chunk), or 0
+ * for an empty prompt (the caller fills it with sp_keep_count). offsets and
+ * kept_off are each given twice with the same B+1 values, in host and in device
+ * memory. Outputs, packed by kept_off:
+ *  - sel_chunks_dev[kept_off[B]]: prompt b's k_b kept chunk indices (relative to
+ *    the prompt), ascending, from kept_off[b] on;
+ *  - spans_dev[kept_off[B]][2]: its spans as token ranges relative to the prompt,
+ *    from kept_off[b] on; n_spans_dev[b] of them are written;
+ *  - chunk_scores_dev: optional; prompt b's chunk scores start at
+ *    offsets[b] / chunk + b (so total / chunk + B + 1 floats in all).
+ * Workspace: sp_select_batch_workspace(offsets[B], B, chunk). 1 <= B <= 4096.
+ */
+sp_status sp_select_batch_workspace(int64_t total_tokens, int32_t B, int32_t chunk,
+                                    size_t *bytes);
+sp_status sp_select_batch(const float *scores_dev, const int64_t *offsets_host,
+                          const int64_t *offsets_dev, int32_t B, int32_t pool_w,
+                          int32_t chunk, const int64_t *kept_off_host,
+                          const int64_t *kept_off_dev, int32_t *sel_chunks_dev,
+                          int64_t *spans_dev, int32_t *n_spans_dev,
+                          float *chunk_scores_dev, void *ws_dev, size_t ws_bytes,
+                          void *hip_stream);
+
+/*
  * sp_select for callers that cannot allocate device memory or pass a workspace:
  * code recorded into a HIP graph, tight serving loops, harnesses that forbid
  * hipMalloc. Same arguments, kernels and results as sp_select, without ws_dev /
@@ -311,6 +339,29 @@ sp_status sp_project(const int64_t *draft_off_dev, int64_t L,
                      int32_t max_spans, int64_t *tspans_dev,
                      int32_t *n_tspans_dev, uint8_t *keep_mask_dev,
                      int64_t *n_kept_dev, void *hip_stream);
+
+/*
+ * sp_project for a ragged batch in one launch (Algorithm 1, the same mapping,
+ * each prompt on its own text). Packed inputs: prompt b's L_b + 1 draft offsets
+ * start at draft_off_dev[offsets[b] + b], its M_b + 1 target offsets at
+ * target_off_dev[moffsets[b] + b] (moffsets = prefix sums of the prompts' target
+ * token counts), its spans at spans_dev[kept_off[b]] with n_spans_dev[b] of them
+ * valid, as sp_select_batch writes them. Packed outputs: prompt b's target ranges
+ * (relative to its own target tokens) from tspans_dev[kept_off[b]] on,
+ * n_tspans_dev[b] of them; its mask bytes at keep_mask_dev[moffsets[b]] (optional);
+ * n_kept_dev[b]. offsets, moffsets and kept_off are each given in host and in
+ * device memory with the same B+1 values, first value 0. A prompt may have at
+ * most 1024 spans and fewer than 258048 target tokens (SP_ERR_UNSUPPORTED
+ * otherwise: call sp_project for it). 1 <= B <= 4096.
+ */
+sp_status sp_project_batch(const int64_t *draft_off_dev, const int64_t *offsets_host,
+                           const int64_t *offsets_dev, const int64_t *target_off_dev,
+                           const int64_t *moffsets_host, const int64_t *moffsets_dev,
+                           int32_t B, const int64_t *spans_dev,
+                           const int32_t *n_spans_dev, const int64_t *kept_off_host,
+                           const int64_t *kept_off_dev, int64_t *tspans_dev,
+                           int32_t *n_tspans_dev, uint8_t *keep_mask_dev,
+                           int64_t *n_kept_dev, void *hip_stream);
 
 /* Bytes of workspace sp_assemble needs for up to max_spans kept ranges. */
 sp_status sp_assemble_workspace(int32_t max_spans, size_t *bytes);

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     sp_keep_count,
     sp_last_error,
     sp_project,
+    sp_project_batch,
     sp_score,
     sp_score_batch,
     sp_score_batch_is_fused,
@@ -28,6 +29,8 @@ from .binding import (  # noqa: F401
     sp_score_is_fused,
     sp_score_workspace,
     sp_select,
+    sp_select_batch,
+    sp_select_batch_workspace,
     sp_select_budget,
     sp_select_static,
     sp_select_budget_workspace,

@@ -21,7 +21,8 @@ _LIB_PATH = os.path.join(_PKG_DIR, "libsp_amd.so")
 
 EXPORTS = (
     "sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_fp8", "sp_score_is_fused", "sp_score_batch", "sp_score_batch_is_fused", "sp_keep_count", "sp_select_workspace",
-    "sp_select", "sp_select_static", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble", "sp_last_error", "sp_version",
+    "sp_select", "sp_select_static", "sp_select_batch_workspace", "sp_select_batch", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_project_batch",
+    "sp_assemble_workspace", "sp_assemble", "sp_last_error", "sp_version",
     "sp_debug_fused_giveup", "sp_hbm_read_probe",
 )
 
@@ -83,6 +84,10 @@ def load_library():
     lib.sp_select_workspace.argtypes = [c.c_int64, c.c_int32, c.POINTER(c.c_size_t)]
     lib.sp_select.argtypes = [P, c.c_int64, c.c_int32, c.c_int32, c.c_int64, P, P, P, P, P, c.c_size_t, P]
     lib.sp_select_static.argtypes = [P, c.c_int64, c.c_int32, c.c_int32, c.c_int64, P, P, P, P, P]
+    I64P = c.POINTER(c.c_int64)
+    lib.sp_select_batch_workspace.argtypes = [c.c_int64, c.c_int32, c.c_int32, c.POINTER(c.c_size_t)]
+    lib.sp_select_batch.argtypes = [P, I64P, P, c.c_int32, c.c_int32, c.c_int32, I64P, P, P, P, P, P, P, c.c_size_t, P]
+    lib.sp_project_batch.argtypes = [P, I64P, P, P, I64P, P, c.c_int32, P, P, I64P, P, P, P, P, P, P]
     lib.sp_select_budget_workspace.argtypes = [c.c_int64, c.c_int32, c.POINTER(c.c_size_t)]
     lib.sp_select_budget.argtypes = [P, c.c_int64, c.c_int32, c.c_int32, P, P, c.c_int64, c.c_int64, P, P, P, P, P, P,
                                      P, c.c_size_t, P]
@@ -96,7 +101,8 @@ def load_library():
     lib.sp_last_error.restype = c.c_char_p
     lib.sp_version.restype = c.c_char_p
     for name in ("sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_fp8", "sp_score_is_fused", "sp_score_batch", "sp_select_workspace", "sp_select",
-                 "sp_select_static", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_assemble_workspace", "sp_assemble"):
+                 "sp_select_static", "sp_select_batch_workspace", "sp_select_batch", "sp_select_budget_workspace", "sp_select_budget", "sp_project",
+                 "sp_project_batch", "sp_assemble_workspace", "sp_assemble"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -282,6 +288,47 @@ def sp_select_static(scores, L: int, pool_w: int, chunk: int, k: int, sel_chunks
                                            _ptr(sel_chunks, "sel_chunks", 4 * kk), _ptr(spans, "spans", 16 * kk),
                                            _ptr(n_spans, "n_spans", 4), _ptr(chunk_scores, "chunk_scores", 4 * C),
                                            _stream(stream)))
+
+
+def _host_i64(values: Sequence[int]):
+    return (ctypes.c_int64 * len(values))(*[int(v) for v in values])
+
+
+def sp_select_batch_workspace(total_tokens: int, B: int, chunk: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().sp_select_batch_workspace(total_tokens, B, chunk, ctypes.byref(n)))
+    return int(n.value)
+
+
+def sp_select_batch(scores, offsets_host: Sequence[int], offsets_dev, pool_w: int, chunk: int,
+                    kept_off_host: Sequence[int], kept_off_dev, sel_chunks, spans, n_spans, chunk_scores, ws,
+                    ws_bytes: Optional[int] = None, stream=None) -> None:
+    B = len(offsets_host) - 1
+    if len(kept_off_host) != B + 1:
+        raise SpError(1, f"kept_off_host has {len(kept_off_host)} entries, offsets_host {B + 1}")
+    total, kept = max(int(offsets_host[-1]), 0), max(int(kept_off_host[-1]), 0)
+    n_cs = total // chunk + B + 1 if chunk > 0 else 0
+    _check(load_library().sp_select_batch(
+        _ptr(scores, "scores", 4 * total), _host_i64(offsets_host), _ptr(offsets_dev, "offsets_dev", 8 * (B + 1)), B,
+        pool_w, chunk, _host_i64(kept_off_host), _ptr(kept_off_dev, "kept_off_dev", 8 * (B + 1)),
+        _ptr(sel_chunks, "sel_chunks", 4 * kept), _ptr(spans, "spans", 16 * kept), _ptr(n_spans, "n_spans", 4 * B),
+        _ptr(chunk_scores, "chunk_scores", 4 * n_cs), _ptr(ws, "ws"), _ws_bytes(ws, ws_bytes), _stream(stream)))
+
+
+def sp_project_batch(draft_off, offsets_host: Sequence[int], offsets_dev, target_off, moffsets_host: Sequence[int],
+                     moffsets_dev, spans, n_spans, kept_off_host: Sequence[int], kept_off_dev, tspans, n_tspans,
+                     keep_mask, n_kept, stream=None) -> None:
+    B = len(offsets_host) - 1
+    if len(moffsets_host) != B + 1 or len(kept_off_host) != B + 1:
+        raise SpError(1, "offsets_host, moffsets_host and kept_off_host must have the same length")
+    total, m_total, kept = max(int(offsets_host[-1]), 0), max(int(moffsets_host[-1]), 0), max(int(kept_off_host[-1]), 0)
+    _check(load_library().sp_project_batch(
+        _ptr(draft_off, "draft_off", 8 * (total + B)), _host_i64(offsets_host),
+        _ptr(offsets_dev, "offsets_dev", 8 * (B + 1)), _ptr(target_off, "target_off", 8 * (m_total + B)),
+        _host_i64(moffsets_host), _ptr(moffsets_dev, "moffsets_dev", 8 * (B + 1)), B, _ptr(spans, "spans", 16 * kept),
+        _ptr(n_spans, "n_spans", 4 * B), _host_i64(kept_off_host), _ptr(kept_off_dev, "kept_off_dev", 8 * (B + 1)),
+        _ptr(tspans, "tspans", 16 * kept), _ptr(n_tspans, "n_tspans", 4 * B), _ptr(keep_mask, "keep_mask", m_total),
+        _ptr(n_kept, "n_kept", 8 * B), _stream(stream)))
 
 
 def sp_select_budget_workspace(L: int, chunk: int) -> int:

@@ -32,6 +32,8 @@
 //                            merged ranges, writes the 0/1 keep mask.
 #include "sp_common.hpp"
 
+#include <algorithm>
+
 namespace {
 
 constexpr int kThreads = 256;
@@ -252,7 +254,7 @@ __device__ __forceinline__ int64_t read_lane64(int64_t v, int l)
 }
 
 // Requires max_spans <= kOneSpans (one scan segment: kOneSpans == kOneThreads) and M < 2^31.
-__global__ __launch_bounds__(kOneThreads) void sp_project_one_kernel(
+__device__ __forceinline__ void project_one_body(
     const int64_t *__restrict__ draft_off, int64_t L, const int64_t *__restrict__ target_off, int M,
     const int64_t *__restrict__ spans, const int32_t *__restrict__ n_spans_p, int max_spans, int stride,
     int n_coarse, int64_t *__restrict__ tspans, int32_t *__restrict__ n_tspans, int64_t *__restrict__ n_kept,
@@ -409,6 +411,47 @@ __global__ __launch_bounds__(kOneThreads) void sp_project_one_kernel(
     }
 }
 
+__global__ __launch_bounds__(kOneThreads) void sp_project_one_kernel(
+    const int64_t *__restrict__ draft_off, int64_t L, const int64_t *__restrict__ target_off, int M,
+    const int64_t *__restrict__ spans, const int32_t *__restrict__ n_spans_p, int max_spans, int stride,
+    int n_coarse, int64_t *__restrict__ tspans, int32_t *__restrict__ n_tspans, int64_t *__restrict__ n_kept,
+    uint8_t *__restrict__ mask)
+{
+    project_one_body(draft_off, L, target_off, M, spans, n_spans_p, max_spans, stride, n_coarse, tspans, n_tspans, n_kept,
+                     mask);
+}
+
+// Ragged batch: prompt b = blockIdx.y. Its L_b + 1 draft offsets start at off[b] + b of the packed array,
+// its M_b + 1 target offsets at moff[b] + b, its spans and target ranges (k_b of each at most) at
+// kept_off[b], its mask bytes at moff[b]. Workgroup 0 of a prompt finds its ranges, the others its mask.
+__global__ __launch_bounds__(kOneThreads) void sp_project_batch_kernel(
+    const int64_t *__restrict__ draft_off, const int64_t *__restrict__ off, const int64_t *__restrict__ target_off,
+    const int64_t *__restrict__ moff, const int64_t *__restrict__ spans, const int32_t *__restrict__ n_spans,
+    const int64_t *__restrict__ kept_off, int64_t *__restrict__ tspans, int32_t *__restrict__ n_tspans,
+    int64_t *__restrict__ n_kept, uint8_t *__restrict__ mask)
+{
+    const int b = blockIdx.y;
+    const int64_t o = off[b], L = off[b + 1] - o, mo = moff[b];
+    const int M = (int)(moff[b + 1] - mo);
+    const int64_t k0 = kept_off[b];
+    const int max_spans = (int)(kept_off[b + 1] - k0);
+    if (blockIdx.x > 0 && ((int64_t)blockIdx.x - 1) * (kOneThreads * kMaskPerThread) >= M) return;   // past this prompt's mask
+    if (L < 1 || M < 1 || max_spans < 1) {           // nothing kept (uniform: no barrier is skipped by part of a workgroup)
+        if (blockIdx.x == 0 && threadIdx.x == 0) { n_tspans[b] = 0; n_kept[b] = 0; }
+        if (blockIdx.x > 0 && mask)
+            for (int k = 0; k < kMaskPerThread; ++k) {
+                const int64_t t = ((int64_t)blockIdx.x - 1) * (kOneThreads * kMaskPerThread) + (int64_t)k * kOneThreads + threadIdx.x;
+                if (t < M) mask[mo + t] = 0;
+            }
+        return;
+    }
+    if (blockIdx.x > 0 && !mask) return;
+    const int stride = (M + kCoarse) / kCoarse;          // ceil((M + 1) / kCoarse)
+    const int n_coarse = (M + stride) / stride;          // ceil((M + 1) / stride)
+    project_one_body(draft_off + o + b, L, target_off + mo + b, M, spans + 2 * k0, n_spans + b, max_spans, stride,
+                     n_coarse, tspans + 2 * k0, n_tspans + b, n_kept + b, mask ? mask + mo : nullptr);
+}
+
 }  // namespace
 
 extern "C" sp_status sp_project(const int64_t *draft_off_dev, int64_t L, const int64_t *target_off_dev, int64_t M,
@@ -423,7 +466,7 @@ extern "C" sp_status sp_project(const int64_t *draft_off_dev, int64_t L, const i
         return sp::fail(SP_ERR_INVALID_ARG, "max_spans = %d outside 1..2^24", max_spans);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     // one launch when the spans fit its LDS and one stride of the coarse index fits a wave-wide probe
-    const int64_t stride = sp::ceil_div(M + 1, kCoarse);
+    const int64_t stride = M / kCoarse + 1;          // ceil((M + 1) / kCoarse)
     if (max_spans <= kOneSpans && stride <= 63) {
         const int n_coarse = (int)sp::ceil_div(M + 1, stride);
         const int64_t mask_groups = keep_mask_dev ? sp::ceil_div(M, (int64_t)kOneThreads * kMaskPerThread) : 0;
@@ -446,5 +489,40 @@ extern "C" sp_status sp_project(const int64_t *draft_off_dev, int64_t L, const i
                            (const int32_t *)n_tspans_dev, M, keep_mask_dev);
         SP_HIP_CHECK(hipGetLastError());
     }
+    return SP_OK;
+}
+
+extern "C" sp_status sp_project_batch(const int64_t *draft_off_dev, const int64_t *offsets_host,
+                                      const int64_t *offsets_dev, const int64_t *target_off_dev,
+                                      const int64_t *moffsets_host, const int64_t *moffsets_dev, int32_t B,
+                                      const int64_t *spans_dev, const int32_t *n_spans_dev,
+                                      const int64_t *kept_off_host, const int64_t *kept_off_dev, int64_t *tspans_dev,
+                                      int32_t *n_tspans_dev, uint8_t *keep_mask_dev, int64_t *n_kept_dev,
+                                      void *hip_stream)
+{
+    if (!draft_off_dev || !offsets_host || !offsets_dev || !target_off_dev || !moffsets_host || !moffsets_dev ||
+        !spans_dev || !n_spans_dev || !kept_off_host || !kept_off_dev || !tspans_dev || !n_tspans_dev || !n_kept_dev)
+        return sp::fail(SP_ERR_INVALID_ARG, "only keep_mask_dev may be null");
+    if (B < 1 || B > 4096) return sp::fail(SP_ERR_INVALID_ARG, "B = %d (supported: 1..4096)", B);
+    if (offsets_host[0] != 0 || moffsets_host[0] != 0 || kept_off_host[0] != 0)
+        return sp::fail(SP_ERR_INVALID_ARG, "offsets_host[0], moffsets_host[0] and kept_off_host[0] must be 0");
+    int64_t max_m = 0;
+    for (int b = 0; b < B; ++b) {
+        const int64_t len = offsets_host[b + 1] - offsets_host[b], m = moffsets_host[b + 1] - moffsets_host[b],
+                      k = kept_off_host[b + 1] - kept_off_host[b];
+        if (len < 0 || m < 0 || k < 0) return sp::fail(SP_ERR_INVALID_ARG, "offsets decrease at prompt %d", b);
+        if (k > kOneSpans)
+            return sp::fail(SP_ERR_UNSUPPORTED, "prompt %d: %lld spans (the batch call supports <= %d a prompt; use sp_project)",
+                            b, (long long)k, kOneSpans);
+        if (m >= (int64_t)63 * kCoarse)
+            return sp::fail(SP_ERR_UNSUPPORTED, "prompt %d: %lld target tokens (the batch call supports < %d a prompt; use sp_project)",
+                            b, (long long)m, 63 * kCoarse);
+        max_m = std::max(max_m, m);
+    }
+    const int64_t mask_groups = keep_mask_dev ? sp::ceil_div(max_m, (int64_t)kOneThreads * kMaskPerThread) : 0;
+    hipLaunchKernelGGL(sp_project_batch_kernel, dim3((unsigned)(1 + mask_groups), (unsigned)B), dim3(kOneThreads), 0,
+                       static_cast<hipStream_t>(hip_stream), draft_off_dev, offsets_dev, target_off_dev, moffsets_dev,
+                       spans_dev, n_spans_dev, kept_off_dev, tspans_dev, n_tspans_dev, n_kept_dev, keep_mask_dev);
+    SP_HIP_CHECK(hipGetLastError());
     return SP_OK;
 }

@@ -42,6 +42,13 @@
 // poison entry that fails every workgroup reading it, and every workgroup
 // reads the status word before it stores its scores (once any workgroup has
 // passed that point all exchanged data is out, so none can fail after it).
+//
+// Variants of the same loop: head_dim 128 (256 keys per workgroup, a wave's two
+// sub-tiles are the two halves of its 32 keys' rows: see the kernel's template
+// flag W), paged keys and lookahead keys in the normaliser (flag EXTRA), and
+// launches that carry several prompts of a ragged batch (a table of prompts,
+// also under EXTRA: each prompt has its own workgroups, duty blocks and row of
+// normalisers).
 #include "sp_score_fused.hpp"
 
 #include <atomic>

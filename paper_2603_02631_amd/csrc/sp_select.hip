@@ -38,6 +38,7 @@
 //   sp_topk_kernel        as above, reading k from device memory.
 #include "sp_common.hpp"
 
+#include <algorithm>
 #include <atomic>
 
 namespace {
@@ -48,14 +49,10 @@ constexpr int kMaxPool = 129;                // halo (w-1)/2 <= 64 fits the stag
 constexpr int kSegLds = kSeg + kMaxPool - 1; // staged floats per wave
 constexpr int kTopkThreads = 1024;
 
-__global__ __launch_bounds__(kChunkThreads) void sp_chunk_kernel(const float *__restrict__ scores, int64_t L,
-                                                                 int pool_w, int chunk, int64_t n_chunks,
-                                                                 float *__restrict__ cs_ws,
-                                                                 float *__restrict__ cs_out,
-                                                                 const int64_t *__restrict__ draft_off,
-                                                                 int64_t *__restrict__ bnd,
-                                                                 int32_t *__restrict__ rank,
-                                                                 int32_t *__restrict__ hist)
+__device__ __forceinline__ void chunk_body(const float *__restrict__ scores, int64_t L, int pool_w, int chunk,
+                                           int64_t n_chunks, float *__restrict__ cs_ws, float *__restrict__ cs_out,
+                                           const int64_t *__restrict__ draft_off, int64_t *__restrict__ bnd,
+                                           int32_t *__restrict__ rank, int32_t *__restrict__ hist)
 {
     __shared__ float stage[kChunkThreads / 64][kSegLds + 3];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -108,6 +105,37 @@ __global__ __launch_bounds__(kChunkThreads) void sp_chunk_kernel(const float *__
     }
 }
 
+__global__ __launch_bounds__(kChunkThreads) void sp_chunk_kernel(const float *__restrict__ scores, int64_t L,
+                                                                 int pool_w, int chunk, int64_t n_chunks,
+                                                                 float *__restrict__ cs_ws,
+                                                                 float *__restrict__ cs_out,
+                                                                 const int64_t *__restrict__ draft_off,
+                                                                 int64_t *__restrict__ bnd,
+                                                                 int32_t *__restrict__ rank,
+                                                                 int32_t *__restrict__ hist)
+{
+    chunk_body(scores, L, pool_w, chunk, n_chunks, cs_ws, cs_out, draft_off, bnd, rank, hist);
+}
+
+// Ragged batch: prompt b = blockIdx.y owns scores [off[b], off[b+1]) and the chunk-score slots from
+// off[b] / chunk + b on (distinct prompts' slots cannot overlap: a prompt has at most
+// off[b+1] / chunk - off[b] / chunk + 1 chunks).
+__device__ __forceinline__ int64_t batch_chunk_slot(int64_t off_b, int b, int chunk) { return off_b / chunk + b; }
+
+__global__ __launch_bounds__(kChunkThreads) void sp_chunk_batch_kernel(const float *__restrict__ scores,
+                                                                       const int64_t *__restrict__ off, int pool_w,
+                                                                       int chunk, float *__restrict__ cs_ws,
+                                                                       float *__restrict__ cs_out)
+{
+    const int b = blockIdx.y;
+    const int64_t o = off[b], L = off[b + 1] - o;
+    const int64_t n_chunks = (L + chunk - 1) / chunk;
+    if ((int64_t)blockIdx.x * (kChunkThreads / 64) >= n_chunks) return;        // also: empty prompt
+    const int64_t slot = batch_chunk_slot(o, b, chunk);
+    chunk_body(scores + o, L, pool_w, chunk, n_chunks, cs_ws + slot, cs_out ? cs_out + slot : nullptr, nullptr, nullptr,
+               nullptr, nullptr);
+}
+
 // fp32 -> uint32 whose unsigned order is the float order (-0 mapped onto +0 first).
 __device__ __forceinline__ uint32_t order_key(float v)
 {
@@ -142,11 +170,9 @@ __device__ __forceinline__ int block_scan_incl(int v, int *wave_tot /*[16]*/, in
 // R > 0: the keys of up to R * 1024 chunks are read once and kept in registers (every pass over the
 // chunk scores would otherwise pay a trip to memory); R = 0: any number of chunks, re-read per pass.
 template <int R>
-__global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__restrict__ cs, int64_t n_chunks,
-                                                               int64_t k, const int64_t *__restrict__ k_dev,
-                                                               int chunk, int64_t L, int32_t *sel,
-                                                               int64_t *__restrict__ spans,
-                                                               int32_t *__restrict__ n_spans)
+__device__ __forceinline__ void topk_body(const float *__restrict__ cs, int64_t n_chunks, int64_t k,
+                                          const int64_t *__restrict__ k_dev, int chunk, int64_t L, int32_t *sel,
+                                          int64_t *__restrict__ spans, int32_t *__restrict__ n_spans)
 {
     __shared__ int hist[256];
     if (k_dev) {                             // k chosen on the device (budget search); always within 1..n_chunks
@@ -275,6 +301,38 @@ __global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__re
         span_base += tot;
     }
     if (tid == 0) *n_spans = (int32_t)span_base;
+}
+
+template <int R>
+__global__ __launch_bounds__(kTopkThreads) void sp_topk_kernel(const float *__restrict__ cs, int64_t n_chunks,
+                                                               int64_t k, const int64_t *__restrict__ k_dev,
+                                                               int chunk, int64_t L, int32_t *sel,
+                                                               int64_t *__restrict__ spans,
+                                                               int32_t *__restrict__ n_spans)
+{
+    topk_body<R>(cs, n_chunks, k, k_dev, chunk, L, sel, spans, n_spans);
+}
+
+// Ragged batch: one workgroup per prompt; prompt b keeps k_b = kept_off[b+1] - kept_off[b] chunks and
+// writes its indices and spans from kept_off[b] on. An empty prompt keeps nothing.
+template <int R>
+__global__ __launch_bounds__(kTopkThreads) void sp_topk_batch_kernel(const float *__restrict__ cs,
+                                                                     const int64_t *__restrict__ off,
+                                                                     const int64_t *__restrict__ kept_off, int chunk,
+                                                                     int32_t *sel, int64_t *__restrict__ spans,
+                                                                     int32_t *__restrict__ n_spans)
+{
+    const int b = blockIdx.x;
+    const int64_t o = off[b], L = off[b + 1] - o;
+    const int64_t n_chunks = (L + chunk - 1) / chunk;
+    const int64_t k0 = kept_off[b];
+    int64_t k = kept_off[b + 1] - k0;
+    if (n_chunks == 0 || k < 1) {            // uniform
+        if (threadIdx.x == 0) n_spans[b] = 0;
+        return;
+    }
+    k = k > n_chunks ? n_chunks : k;
+    topk_body<R>(cs + batch_chunk_slot(o, b, chunk), n_chunks, k, nullptr, chunk, L, sel + k0, spans + 2 * k0, n_spans + b);
 }
 
 // ---------------------------------------------------------------------------
@@ -498,6 +556,80 @@ extern "C" sp_status sp_select(const float *scores_dev, int64_t L, int32_t pool_
     if (ws_bytes < need) return sp::fail(SP_ERR_WORKSPACE, "workspace too small: %zu < %zu", ws_bytes, need);
     return select_launch(scores_dev, L, pool_w, chunk, k, C, sel_chunks_dev, spans_dev, n_spans_dev, chunk_scores_dev,
                          static_cast<float *>(ws_dev), static_cast<hipStream_t>(hip_stream));
+}
+
+// ---------------------------------------------------------------------------
+// sp_select for a ragged batch: two launches for all prompts.
+// ---------------------------------------------------------------------------
+namespace {
+constexpr int kMaxBatchPrompts = 4096;
+
+size_t select_batch_ws(int64_t total, int32_t B, int32_t chunk)
+{
+    return sp::align_up(sizeof(float) * (size_t)(total / chunk + B + 1), 256);
+}
+}  // namespace
+
+extern "C" sp_status sp_select_batch_workspace(int64_t total_tokens, int32_t B, int32_t chunk, size_t *bytes)
+{
+    if (!bytes) return sp::fail(SP_ERR_INVALID_ARG, "bytes is null");
+    if (total_tokens < 0 || chunk < 1 || B < 1 || B > kMaxBatchPrompts)
+        return sp::fail(SP_ERR_INVALID_ARG, "total_tokens >= 0, chunk >= 1 and B in 1..%d are required", kMaxBatchPrompts);
+    if (total_tokens / chunk > (int64_t(1) << 42))       // 4096 prompts of 2^30 chunks: what sp_select_batch accepts at most
+        return sp::fail(SP_ERR_UNSUPPORTED, "too many chunks (%lld)", (long long)(total_tokens / chunk));
+    *bytes = select_batch_ws(total_tokens, B, chunk);
+    return SP_OK;
+}
+
+extern "C" sp_status sp_select_batch(const float *scores_dev, const int64_t *offsets_host, const int64_t *offsets_dev,
+                                     int32_t B, int32_t pool_w, int32_t chunk, const int64_t *kept_off_host,
+                                     const int64_t *kept_off_dev, int32_t *sel_chunks_dev, int64_t *spans_dev,
+                                     int32_t *n_spans_dev, float *chunk_scores_dev, void *ws_dev, size_t ws_bytes,
+                                     void *hip_stream)
+{
+    if (!scores_dev || !offsets_host || !offsets_dev || !kept_off_host || !kept_off_dev || !sel_chunks_dev || !spans_dev ||
+        !n_spans_dev)
+        return sp::fail(SP_ERR_INVALID_ARG, "only chunk_scores_dev may be null");
+    if (B < 1 || B > kMaxBatchPrompts) return sp::fail(SP_ERR_INVALID_ARG, "B = %d (supported: 1..%d)", B, kMaxBatchPrompts);
+    if (chunk < 1) return sp::fail(SP_ERR_INVALID_ARG, "chunk = %d must be >= 1", chunk);
+    if (pool_w < 1 || pool_w % 2 == 0) return sp::fail(SP_ERR_INVALID_ARG, "pool_w = %d must be odd and >= 1", pool_w);
+    if (pool_w > kMaxPool) return sp::fail(SP_ERR_UNSUPPORTED, "pool_w = %d (supported: <= %d)", pool_w, kMaxPool);
+    if (offsets_host[0] != 0 || kept_off_host[0] != 0)
+        return sp::fail(SP_ERR_INVALID_ARG, "offsets_host[0] and kept_off_host[0] must be 0");
+    int64_t max_chunks = 0;
+    for (int b = 0; b < B; ++b) {
+        const int64_t len = offsets_host[b + 1] - offsets_host[b], k = kept_off_host[b + 1] - kept_off_host[b];
+        if (len < 0) return sp::fail(SP_ERR_INVALID_ARG, "offsets_host decreases at prompt %d", b);
+        const int64_t C = sp::ceil_div(len, chunk);
+        if (C > (1 << 30)) return sp::fail(SP_ERR_UNSUPPORTED, "too many chunks (%lld) in prompt %d", (long long)C, b);
+        if (len == 0 ? k != 0 : (k < 1 || k > C))
+            return sp::fail(SP_ERR_INVALID_ARG, "prompt %d keeps %lld chunks of %lld (1..C, or 0 of an empty prompt)", b,
+                            (long long)k, (long long)C);
+        max_chunks = std::max(max_chunks, C);
+    }
+    const size_t need = select_batch_ws(offsets_host[B], B, chunk);
+    if (!ws_dev) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is null (%zu bytes needed)", need);
+    if ((uintptr_t)ws_dev % 256 != 0) return sp::fail(SP_ERR_WORKSPACE, "ws_dev is not 256-byte aligned");
+    if (ws_bytes < need) return sp::fail(SP_ERR_WORKSPACE, "workspace too small: %zu < %zu", ws_bytes, need);
+    if (max_chunks == 0) max_chunks = 1;     // all prompts empty: the top-k launch still writes n_spans = 0
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    float *cs = static_cast<float *>(ws_dev);
+    const int waves_per_block = kChunkThreads / 64;
+    hipLaunchKernelGGL(sp_chunk_batch_kernel, dim3((unsigned)sp::ceil_div(max_chunks, waves_per_block), (unsigned)B),
+                       dim3(kChunkThreads), 0, st, scores_dev, offsets_dev, (int)pool_w, (int)chunk, cs, chunk_scores_dev);
+    SP_HIP_CHECK(hipGetLastError());
+    const dim3 grid((unsigned)B), block(kTopkThreads);
+    if (max_chunks <= 2 * kTopkThreads)
+        hipLaunchKernelGGL((sp_topk_batch_kernel<2>), grid, block, 0, st, cs, offsets_dev, kept_off_dev, (int)chunk,
+                           sel_chunks_dev, spans_dev, n_spans_dev);
+    else if (max_chunks <= 8 * kTopkThreads)
+        hipLaunchKernelGGL((sp_topk_batch_kernel<8>), grid, block, 0, st, cs, offsets_dev, kept_off_dev, (int)chunk,
+                           sel_chunks_dev, spans_dev, n_spans_dev);
+    else
+        hipLaunchKernelGGL((sp_topk_batch_kernel<0>), grid, block, 0, st, cs, offsets_dev, kept_off_dev, (int)chunk,
+                           sel_chunks_dev, spans_dev, n_spans_dev);
+    SP_HIP_CHECK(hipGetLastError());
+    return SP_OK;
 }
 
 // ---------------------------------------------------------------------------

@@ -124,6 +124,18 @@ int main()
         EXPECT(sp_assemble_workspace(0, &n) == SP_ERR_INVALID_ARG);
         EXPECT(sp_assemble(p32, 100, p64, p32, 10, nullptr, 3, 50, p32, p32, nullptr, p64, fake, n, nullptr) == SP_ERR_INVALID_ARG);
         EXPECT(sp_assemble(p32, 100, p64, p32, 10, p32, 2000, 50, p32, p32, nullptr, p64, fake, n, nullptr) == SP_ERR_INVALID_ARG);
+        // ragged-batch select / project: host arrays are walked before anything else happens
+        const int64_t off[4] = {0, 400, 400, 1000}, moff[4] = {0, 450, 450, 1100}, kept[4] = {0, 3, 3, 7};
+        const int64_t bad_kept[4] = {0, 14, 14, 18}, huge_off[2] = {0, INT64_MAX}, many[2] = {0, 1025}, one[2] = {0, 1};
+        float *scores = static_cast<float *>(fake);
+        EXPECT(sp_select_batch_workspace(1000, 3, 32, &n) == SP_OK && n % 256 == 0);
+        EXPECT(sp_select_batch_workspace(INT64_MAX, 4096, 1, &n) == SP_ERR_UNSUPPORTED);
+        EXPECT(sp_select_batch(scores, off, p64, 3, 13, 32, bad_kept, p64, p32, p64, p32, nullptr, fake, n, nullptr) == SP_ERR_INVALID_ARG);
+        EXPECT(sp_select_batch(scores, huge_off, p64, 1, 13, 1, one, p64, p32, p64, p32, nullptr, fake, n, nullptr) == SP_ERR_UNSUPPORTED);
+        EXPECT(sp_select_batch(scores, off, p64, 3, 13, 32, kept, p64, p32, p64, p32, nullptr, fake, 8, nullptr) == SP_ERR_WORKSPACE);
+        EXPECT(sp_project_batch(p64, off, p64, p64, moff, p64, 3, p64, p32, bad_kept, nullptr, p64, p32, nullptr, p64, nullptr) == SP_ERR_INVALID_ARG);
+        EXPECT(sp_project_batch(p64, huge_off, p64, p64, huge_off, p64, 1, p64, p32, one, p64, p64, p32, nullptr, p64, nullptr) == SP_ERR_UNSUPPORTED);
+        EXPECT(sp_project_batch(p64, off, p64, p64, moff, p64, 1, p64, p32, many, p64, p64, p32, nullptr, p64, nullptr) == SP_ERR_UNSUPPORTED);
         EXPECT(sp_hbm_read_probe(nullptr, 1024, static_cast<uint64_t *>(fake), nullptr) == SP_ERR_INVALID_ARG);
         EXPECT(sp_hbm_read_probe(fake, 24, static_cast<uint64_t *>(fake), nullptr) == SP_ERR_INVALID_ARG);
     }

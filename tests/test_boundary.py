@@ -190,6 +190,53 @@ def test_select_static_argument_errors():
         assert e.value.status == status, kw
 
 
+def test_select_batch_argument_errors():
+    fake = 0x1000
+    n = sp.sp_select_batch_workspace(1000, 3, 32)
+    assert n >= 4 * (1000 // 32 + 3 + 1) and n % 256 == 0
+    for args in [(-1, 3, 32), (1000, 0, 32), (1000, 4097, 32), (1000, 3, 0)]:
+        with pytest.raises(sp.SpError) as e:
+            sp.sp_select_batch_workspace(*args)
+        assert e.value.status == 1
+
+    def call(off=(0, 400, 400, 1000), kept=(0, 3, 3, 7), pool=13, chunk=32, scores=fake, offd=fake, keptd=fake, sel=fake,
+             spans=fake, ns=fake, ws=fake, wsb=n):
+        sp.sp_select_batch(scores, list(off), offd, pool, chunk, list(kept), keptd, sel, spans, ns, None, ws, wsb, stream=0)
+
+    for kw, status in [(dict(scores=None), 1), (dict(offd=None), 1), (dict(keptd=None), 1), (dict(sel=None), 1),
+                       (dict(spans=None), 1), (dict(ns=None), 1), (dict(pool=12), 1), (dict(pool=131), 2),
+                       (dict(chunk=0), 1), (dict(off=(1, 400, 400, 1000)), 1), (dict(off=(0, 400, 300, 1000)), 1),
+                       (dict(kept=(1, 3, 3, 7)), 1),
+                       (dict(kept=(0, 3, 4, 7)), 1),            # an empty prompt keeps nothing
+                       (dict(kept=(0, 0, 0, 7)), 1),            # a prompt with tokens keeps at least one chunk
+                       (dict(kept=(0, 14, 14, 18)), 1),         # more than the 13 chunks of 400 tokens
+                       (dict(ws=None, wsb=0), 3), (dict(wsb=8), 3), (dict(ws=fake + 8), 3)]:
+        with pytest.raises(sp.SpError) as e:
+            call(**kw)
+        assert e.value.status == status, (kw, e.value)
+    with pytest.raises(sp.SpError):
+        sp.sp_select_batch(fake, [0, 10], fake, 13, 32, [0, 1, 2], fake, fake, fake, fake, None, fake, n, stream=0)
+
+
+def test_project_batch_argument_errors():
+    fake = 0x1000
+
+    def call(off=(0, 400, 400, 1000), moff=(0, 450, 450, 1100), kept=(0, 3, 3, 7), doff=fake, offd=fake, toff=fake,
+             moffd=fake, spans=fake, ns=fake, keptd=fake, tsp=fake, nt=fake, nk=fake):
+        sp.sp_project_batch(doff, list(off), offd, toff, list(moff), moffd, spans, ns, list(kept), keptd, tsp, nt, None, nk,
+                            stream=0)
+
+    for kw, status in [(dict(doff=None), 1), (dict(offd=None), 1), (dict(toff=None), 1), (dict(moffd=None), 1),
+                       (dict(spans=None), 1), (dict(ns=None), 1), (dict(keptd=None), 1), (dict(tsp=None), 1),
+                       (dict(nt=None), 1), (dict(nk=None), 1), (dict(off=(1, 400, 400, 1000)), 1),
+                       (dict(moff=(0, 450, 440, 1100)), 1), (dict(kept=(0, 3, 2, 7)), 1),
+                       (dict(kept=(0, 1025, 1025, 1030)), 2),                   # more spans than one launch holds
+                       (dict(moff=(0, 258048, 258048, 258100)), 2)]:            # more target tokens than a wave-wide probe covers
+        with pytest.raises(sp.SpError) as e:
+            call(**kw)
+        assert e.value.status == status, (kw, e.value)
+
+
 def test_project_argument_errors():
     fake = 0x1000
 

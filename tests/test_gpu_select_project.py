@@ -201,3 +201,104 @@ def test_project_workload_char_models():
         k = oracle.keep_count(C, w.keep_num, w.keep_den)
         sel = np.sort(rng.choice(C, size=k, replace=False)).astype(np.int64)
         check_project(doff, toff, oracle.merge(sel, w.chunk, w.L))
+
+
+BATCHES = [
+    # name, prompt lengths, pool, chunk, keep
+    ("batch_mixed", [1000, 0, 1, 31, 5000, 40000, 33, 0], 13, 32, (20, 100)),
+    ("batch_many_chunks", [70000, 300, 9000], 13, 16, (15, 100)),        # 4375 chunks: eight key segments per thread
+    ("batch_keys_reread", [40000, 12], 13, 4, (10, 100)),                # 10000 chunks: keys re-read per pass
+    ("batch_single_prompt", [12345], 5, 64, (25, 100)),
+    ("batch_all_empty", [0, 0, 0], 13, 32, (20, 100)),
+    ("batch_wide_pool_short_prompts", [5, 200, 64, 129], 129, 32, (50, 100)),
+]
+
+
+@pytest.mark.parametrize("case", BATCHES, ids=[c[0] for c in BATCHES])
+def test_select_and_project_batch_match_the_per_prompt_calls_and_the_oracle(case):
+    """sp_select_batch / sp_project_batch on packed ragged inputs: every prompt bit-identical to
+    sp_select / sp_project on that prompt alone (same kernels' arithmetic), selection exact against the
+    oracle's top-k on the GPU's chunk scores, projection exact against the oracle; nothing written
+    outside a prompt's share of the packed outputs."""
+    import torch
+    import paper_2603_02631_amd as sp
+    from gpu_util import DEV, gpu_select, workspace
+    name, lens, pool_w, chunk, keep = case
+    say(f"[select/project batch] {name} lengths={lens} pool={pool_w} chunk={chunk} keep={keep}")
+    B = len(lens)
+    rng = np.random.default_rng(500 + BATCHES.index(case))
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    T = int(off[-1])
+    scores = rng.random(max(T, 1)).astype(np.float32) ** 4
+    ks = [int(sp.sp_keep_count((L + chunk - 1) // chunk, *keep)) if L > 0 else 0 for L in lens]
+    kept = np.concatenate([[0], np.cumsum(ks)]).astype(np.int64)
+    K = int(kept[-1])
+    doffs, toffs = [], []
+    for L in lens:
+        d = offsets_from_lengths(rng.integers(1, 9, size=L)) if L > 0 else np.zeros(1, np.int64)
+        t = split_same_text(rng, int(d[-1]), 7) if L > 0 else np.zeros(1, np.int64)
+        doffs.append(d)
+        toffs.append(t)
+    Ms = [t.size - 1 for t in toffs]
+    moff = np.concatenate([[0], np.cumsum(Ms)]).astype(np.int64)
+    MT = int(moff[-1])
+
+    def dev(a, dt):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=dt)).to(DEV)
+    sd, off_d, kept_d, moff_d = dev(scores, np.float32), dev(off, np.int64), dev(kept, np.int64), dev(moff, np.int64)
+    dd, td = dev(np.concatenate(doffs), np.int64), dev(np.concatenate(toffs), np.int64)
+    sel = torch.full((max(K, 1),), -1, dtype=torch.int32, device=DEV)
+    spans = torch.full((max(K, 1), 2), -1, dtype=torch.int64, device=DEV)
+    n_spans = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+    n_cs = T // chunk + B + 1
+    cs = torch.full((n_cs,), float("nan"), dtype=torch.float32, device=DEV)
+    ws = workspace(sp.sp_select_batch_workspace(T, B, chunk))
+    sp.sp_select_batch(sd, [int(v) for v in off], off_d, pool_w, chunk, [int(v) for v in kept], kept_d, sel, spans,
+                       n_spans, cs, ws)
+    tsp = torch.full((max(K, 1), 2), -1, dtype=torch.int64, device=DEV)
+    n_t = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+    n_kept = torch.full((B,), -1, dtype=torch.int64, device=DEV)
+    mask = torch.full((max(MT, 1),), 7, dtype=torch.uint8, device=DEV)
+    sp.sp_project_batch(dd, [int(v) for v in off], off_d, td, [int(v) for v in moff], moff_d, spans, n_spans,
+                        [int(v) for v in kept], kept_d, tsp, n_t, mask, n_kept)
+    torch.cuda.synchronize()
+    sel, spans, n_spans, cs = sel.cpu().numpy(), spans.cpu().numpy(), n_spans.cpu().numpy(), cs.cpu().numpy()
+    tsp, n_t, n_kept, mask = tsp.cpu().numpy(), n_t.cpu().numpy(), n_kept.cpu().numpy(), mask.cpu().numpy()
+    for b, L in enumerate(lens):
+        k0, k1 = int(kept[b]), int(kept[b + 1])
+        if L == 0:
+            assert n_spans[b] == 0 and n_t[b] == 0 and n_kept[b] == 0
+            continue
+        s_sel, s_spans, s_cs = gpu_select(scores[off[b]:off[b + 1]], pool_w, chunk, ks[b])
+        C = (L + chunk - 1) // chunk
+        slot = int(off[b]) // chunk + b
+        assert cs[slot:slot + C].tobytes() == s_cs.tobytes()
+        np.testing.assert_array_equal(sel[k0:k1], s_sel)
+        ns = int(n_spans[b])
+        np.testing.assert_array_equal(spans[k0:k0 + ns], s_spans)
+        assert (spans[k0 + ns:k1] == -1).all()
+        exact = oracle.topk(s_cs.astype(np.float64), ks[b])
+        np.testing.assert_array_equal(sel[k0:k1].astype(np.int64), exact)
+        np.testing.assert_array_equal(spans[k0:k0 + ns], oracle.merge(exact, chunk, L))
+        o_ts, o_mask, o_n = oracle.project(doffs[b], toffs[b], spans[k0:k0 + ns])
+        nt = int(n_t[b])
+        np.testing.assert_array_equal(tsp[k0:k0 + nt], o_ts)
+        assert (tsp[k0 + nt:k1] == -1).all()
+        np.testing.assert_array_equal(mask[moff[b]:moff[b + 1]], o_mask)
+        assert n_kept[b] == o_n
+    if K:
+        assert (sel[K:] == -1).all()
+    # without the optional outputs: same selections
+    sel2 = torch.full((max(K, 1),), -1, dtype=torch.int32, device=DEV)
+    spans2 = torch.full((max(K, 1), 2), -1, dtype=torch.int64, device=DEV)
+    n_spans2 = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+    sp.sp_select_batch(sd, [int(v) for v in off], off_d, pool_w, chunk, [int(v) for v in kept], kept_d, sel2, spans2,
+                       n_spans2, None, ws)
+    n_kept2 = torch.full((B,), -1, dtype=torch.int64, device=DEV)
+    tsp2 = torch.full((max(K, 1), 2), -1, dtype=torch.int64, device=DEV)
+    n_t2 = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+    sp.sp_project_batch(dd, [int(v) for v in off], off_d, td, [int(v) for v in moff], moff_d, spans2, n_spans2,
+                        [int(v) for v in kept], kept_d, tsp2, n_t2, None, n_kept2)
+    torch.cuda.synchronize()
+    assert sel2.cpu().numpy().tobytes() == sel.tobytes() and spans2.cpu().numpy().tobytes() == spans.tobytes()
+    assert tsp2.cpu().numpy().tobytes() == tsp.tobytes() and n_kept2.cpu().numpy().tobytes() == n_kept.tobytes()
