@@ -173,7 +173,7 @@ def main() -> int:
     if ragged:
         fused = 1 if sp.sp_score_batch_is_fused(desc, off_host) > 0 else 0
     else:
-        fused = 0 if fp8 else sp.sp_score_is_fused(desc, T)
+        fused = sp.sp_score_fp8_is_fused(desc, T) if fp8 else sp.sp_score_is_fused(desc, T)
     calls = [0]
     # ragged batch: the prompts' select / project chains (one-workgroup kernels) are independent of each other
     # and go round robin onto a few streams of default priority, so that they overlap

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     sp_score_batch,
     sp_score_batch_is_fused,
     sp_score_fp8,
+    sp_score_fp8_is_fused,
     sp_score_look,
     sp_score_paged,
     sp_score_is_fused,

@@ -20,7 +20,7 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG_DIR, "libsp_amd.so")
 
 EXPORTS = (
-    "sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_fp8", "sp_score_is_fused", "sp_score_batch", "sp_score_batch_is_fused", "sp_keep_count", "sp_select_workspace",
+    "sp_score_workspace", "sp_score", "sp_score_look", "sp_score_paged", "sp_score_fp8", "sp_score_is_fused", "sp_score_fp8_is_fused", "sp_score_batch", "sp_score_batch_is_fused", "sp_keep_count", "sp_select_workspace",
     "sp_select", "sp_select_static", "sp_select_batch_workspace", "sp_select_batch", "sp_select_budget_workspace", "sp_select_budget", "sp_project", "sp_project_batch",
     "sp_assemble_workspace", "sp_assemble", "sp_last_error", "sp_version",
     "sp_debug_fused_giveup", "sp_hbm_read_probe",
@@ -79,6 +79,8 @@ def load_library():
     lib.sp_score_batch_is_fused.restype = c.c_int32
     lib.sp_score_is_fused.argtypes = [D, c.c_int64]
     lib.sp_score_is_fused.restype = c.c_int32
+    lib.sp_score_fp8_is_fused.argtypes = [D, c.c_int64]
+    lib.sp_score_fp8_is_fused.restype = c.c_int32
     lib.sp_keep_count.argtypes = [c.c_int64, c.c_int64, c.c_int64]
     lib.sp_keep_count.restype = c.c_int64
     lib.sp_select_workspace.argtypes = [c.c_int64, c.c_int32, c.POINTER(c.c_size_t)]
@@ -182,6 +184,10 @@ def sp_score_workspace(desc: ScoreDesc, total_tokens: int, n_prompts: int = 1) -
 
 def sp_score_is_fused(desc: ScoreDesc, L: int) -> int:
     return int(load_library().sp_score_is_fused(ctypes.byref(desc), L))
+
+
+def sp_score_fp8_is_fused(desc: ScoreDesc, L: int) -> int:
+    return int(load_library().sp_score_fp8_is_fused(ctypes.byref(desc), L))
 
 
 def sp_score_batch_is_fused(desc: ScoreDesc, offsets_host: Sequence[int]) -> int:

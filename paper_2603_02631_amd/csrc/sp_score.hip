@@ -138,23 +138,6 @@ __device__ __forceinline__ void stage_q(u32x4 *qs, const ScoreArgs &a, int promp
     }
 }
 
-// Eight E4M3 codes (two dwords) -> eight bf16 (every E4M3 value is exact in bf16: the upper half of
-// its float image).
-__device__ __forceinline__ u32x4 e4m3x8_to_bf16x8(uint2 c)
-{
-    typedef __attribute__((ext_vector_type(2))) float f32x2;
-    u32x4 r;
-    const uint32_t w[2] = {c.x, c.y};
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);     // codes 0, 1 of the dword
-        const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);      // codes 2, 3
-        r[2 * i] = __builtin_amdgcn_perm(__float_as_uint(lo.y), __float_as_uint(lo.x), 0x07060302u);
-        r[2 * i + 1] = __builtin_amdgcn_perm(__float_as_uint(hi.y), __float_as_uint(hi.x), 0x07060302u);
-    }
-    return r;
-}
-
 // The same staging for 8-bit keys: kb8 addresses bytes, strides are in elements (= bytes).
 template <int D, int NS>
 __device__ __forceinline__ void stage_k_fp8(u32x4 *ks, const uint8_t *kb8, int64_t stride_token, int64_t j0,
@@ -174,7 +157,7 @@ __device__ __forceinline__ void stage_k_fp8(u32x4 *ks, const uint8_t *kb8, int64
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         const int idx = tid + i * kThreads;
-        ks[lds_slot<D>(idx / CH, idx % CH)] = e4m3x8_to_bf16x8(v[i]);
+        ks[lds_slot<D>(idx / CH, idx % CH)] = e4m3x8_to_bf16x8(v[i].x, v[i].y);
     }
 }
 
@@ -661,6 +644,14 @@ bool fused_applies(const Plan &p, int64_t L, int64_t k_stride_token)
     return n_wg >= fused_min_workgroups(p) && n_wg <= 256 && n_wg <= device_compute_units();
 }
 
+// 8-bit keys: the single-launch kernel has a head_dim 64 variant for them (rows of 64 codes fetched in 16-byte
+// pieces: strides in multiples of 16 elements).
+bool fused_applies_fp8(const Plan &p, const sp_score_desc *desc, int64_t L)
+{
+    return p.D == 64 && desc->k_stride_token % 16 == 0 && desc->k_stride_head % 16 == 0 &&
+           fused_applies(p, L, desc->k_stride_token);
+}
+
 // A ragged batch on the single-launch kernel: the prompts are packed into launches of at most one
 // workgroup per compute unit (first fit, longest first), each prompt with all its 512-key tiles in one
 // launch. Applies when every prompt is empty or at least one tile long and fits a launch, the batch has
@@ -862,7 +853,9 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
         SP_HIP_CHECK(hipGetLastError());
         a.look = look;
     }
-    if (opt.kscale) {            // 8-bit keys take the three-kernel path
+    // 8-bit keys outside the single-launch kernel's variant for them take the three-kernel path
+    const bool fp8_fused = opt.kscale && !batch && fused_applies_fp8(p, desc, total);
+    if (opt.kscale && !fp8_fused) {
         if (p.D == 64) return launch_all<64, 2, true>(p, a, kp, st);
         return launch_all<128, 1, true>(p, a, kp, st);
     }
@@ -877,6 +870,7 @@ sp_status score_impl(const sp_score_desc *desc, const void *q_dev, const void *c
             f.k_stride_token = a.k_stride_token;
             f.k_stride_head = a.k_stride_head;
             f.L = total;
+            f.kscale = opt.kscale;
             f.look = a.look;
             f.block_table = a.block_table;
             f.page_tokens = a.page_tokens;
@@ -953,6 +947,13 @@ extern "C" int32_t sp_score_is_fused(const sp_score_desc *desc, int64_t L)
     Plan p;
     if (make_plan(desc, p) != SP_OK) return -1;
     return fused_applies(p, L, desc->k_stride_token) ? 1 : 0;
+}
+
+extern "C" int32_t sp_score_fp8_is_fused(const sp_score_desc *desc, int64_t L)
+{
+    Plan p;
+    if (make_plan(desc, p) != SP_OK) return -1;
+    return fused_applies_fp8(p, desc, L) ? 1 : 0;
 }
 
 extern "C" int32_t sp_score_batch_is_fused(const sp_score_desc *desc, const int64_t *offsets_host, int32_t B)

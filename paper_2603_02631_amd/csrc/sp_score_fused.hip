@@ -138,6 +138,7 @@ struct Ring {
 // address arithmetic of every load and lift.
 struct LaneConst {
     uint32_t ld[kKS];       // LDS byte address of this lane's fragment chunk t in a tile at LDS offset 0
+    uint32_t ld8[kKS];      // the same in a sub-tile of 8-bit keys (rows of 64 bytes, 8 bytes per chunk)
     uint32_t koff[2];       // byte offset of this lane's chunk in an even / odd tile-load instruction (full tiles)
     int32_t qoff;           // byte offset of this lane's chunk of its wave's Q slice in a (layer, kv head) block; < 0: padding
 };
@@ -225,6 +226,46 @@ __device__ __forceinline__ void lift_k_and_q(const LaneConst &lc, uint32_t koff0
         kf[0][t] = __builtin_bit_cast(bf16x8, r[t]);
         kf[1][t] = __builtin_bit_cast(bf16x8, r[4 + t]);
         qf[t] = __builtin_bit_cast(bf16x8, r[8 + t]);
+    }
+}
+
+// 8-bit keys: both 32-key sub-tiles of a K tile (rows of 64 codes; this lane's eight codes of k-step t
+// are one 8-byte read) and one 32-row Q block in one round trip to LDS, the codes widened to bf16.
+template <int QOFF>
+__device__ __forceinline__ void lift_k8_and_q(const LaneConst &lc, uint32_t koff0, uint32_t koff1,
+                                              bf16x8 (&kf)[kNS][kKS], bf16x8 (&qf)[kKS])
+{
+    static_assert(kKS == 4 && kNS == 2 && QOFF >= 0 && QOFF < 65536, "layout of the asm block");
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+    u32x2 r[8];
+    u32x4 q[4];
+    uint32_t a0[kKS], a1[kKS];
+#pragma unroll
+    for (int t = 0; t < kKS; ++t) { a0[t] = lc.ld8[t] + koff0; a1[t] = lc.ld8[t] + koff1; }
+    __asm__ volatile(
+        "ds_read_b64 %0, %12\n\t"
+        "ds_read_b64 %1, %13\n\t"
+        "ds_read_b64 %2, %14\n\t"
+        "ds_read_b64 %3, %15\n\t"
+        "ds_read_b128 %8, %20 offset:%24\n\t"
+        "ds_read_b128 %9, %21 offset:%24\n\t"
+        "ds_read_b128 %10, %22 offset:%24\n\t"
+        "ds_read_b128 %11, %23 offset:%24\n\t"
+        "ds_read_b64 %4, %16\n\t"
+        "ds_read_b64 %5, %17\n\t"
+        "ds_read_b64 %6, %18\n\t"
+        "ds_read_b64 %7, %19\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7]),
+          "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2]), "=&v"(q[3])
+        : "v"(a0[0]), "v"(a0[1]), "v"(a0[2]), "v"(a0[3]), "v"(a1[0]), "v"(a1[1]), "v"(a1[2]), "v"(a1[3]),
+          "v"(lc.ld[0]), "v"(lc.ld[1]), "v"(lc.ld[2]), "v"(lc.ld[3]), "i"(QOFF)
+        : "memory");
+#pragma unroll
+    for (int t = 0; t < kKS; ++t) {
+        kf[0][t] = __builtin_bit_cast(bf16x8, e4m3x8_to_bf16x8(r[t].x, r[t].y));
+        kf[1][t] = __builtin_bit_cast(bf16x8, e4m3x8_to_bf16x8(r[4 + t].x, r[4 + t].y));
+        qf[t] = __builtin_bit_cast(bf16x8, q[t]);
     }
 }
 
@@ -369,14 +410,17 @@ struct Acc {
 };
 
 // ---- probability pass of one phase from the fragment ring; tile loads are issued between the MFMA steps ----
-constexpr int kMidInstr = 2;              // of the four loads of sub-tile 0: issued right after the barrier ...
-constexpr int kProbInstr = kSubInstr - kMidInstr;     // ... and between the MFMA steps of the probability pass
+// Of the four loads of sub-tile 0 two are issued right after the barrier and two between the MFMA steps of
+// the probability pass (8-bit keys: two loads a sub-tile, one and one).
 
-template <int NB, int GB, int PAR, bool W>
+// F8: logits are in units of the phase's key scale `ks`; a phase's head maximum is brought to common
+// units before it meets other phases'. One tile load instead of two (half the bytes per sub-tile).
+template <int NB, int GB, int PAR, bool W, bool F8>
 __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t cinit_ad,
-                                          Acc<NB> &acc, const KIssue &ki, const uint32_t (&voff)[2])
+                                          Acc<NB> &acc, const KIssue &ki, const uint32_t (&voff)[2], float ks)
 {
-    static_assert(kProbInstr == 2 && (NB * GB == 1 || NB * GB == 2), "one load per row block, or one per step");
+    static_assert(NB * GB == 1 || NB * GB == 2, "one load per row block, or one per step");
+    constexpr int kMid = F8 ? 1 : 2;
     if constexpr (W) {
         // head_dim 128: one chain of eight MFMA steps over both halves of the 32 keys' rows
         static_assert(NB == 1 && GB == 1, "one block of 32 query rows");
@@ -386,12 +430,12 @@ __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const La
         lift_at<kOffQ2 + PAR * kQTileBytes + kWideHalf>(lc, q1);
 #pragma unroll
         for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q0[t], kf[0][t], d, 0, 0, 0);
-        k_issue<1>(ki, voff, kMidInstr);
+        k_issue<1>(ki, voff, kMid);
 #pragma unroll
         for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q1[t], kf[1][t], d, 0, 0, 0);
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc.mx[0][0][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[0][0][e]);
-        k_issue<1>(ki, voff, kMidInstr + 1);
+        k_issue<1>(ki, voff, kMid + 1);
         __builtin_amdgcn_sched_barrier(0);
         return;
     }
@@ -411,10 +455,13 @@ __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const La
                 for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t], kf[s][t], d, 0, 0, 0);
                 // d[r]: group head r/4, lookahead row 8*nb + 4*hf + r%4, key (wave*2+s)*32 + col
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    acc.mx[s][nb][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[s][nb][e]);
-                if (NB * GB == 1) k_issue<1>(ki, voff, kMidInstr + s);
-                else if (s == kNS - 1) k_issue<1>(ki, voff, kMidInstr + blk);
+                for (int e = 0; e < 4; ++e) {
+                    if (F8) acc.mx[s][nb][e] = fmaxf(acc.mx[s][nb][e], fmaxf(max3(d[e], d[4 + e], d[8 + e]), d[12 + e]) * ks);
+                    else acc.mx[s][nb][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[s][nb][e]);
+                }
+                if (F8) { if (blk == 0 && s == 0) k_issue<1>(ki, voff, kMid); }
+                else if (NB * GB == 1) k_issue<1>(ki, voff, kMid + s);
+                else if (s == kNS - 1) k_issue<1>(ki, voff, kMid + blk);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -514,16 +561,18 @@ __device__ __forceinline__ void store_row_stats(uint32_t ad, float m, float l, f
 // tile load is issued after each of the four steps (with one row block: two per step). On the
 // normaliser wave (lse_row != nullptr) the request for the normalisers follows the first step: late
 // enough for the duty workgroups' stores to be visible, early enough to land before the barrier.
-template <int NBLK>
-constexpr int kLoadsBehindLse = kSubInstr - kSubInstr / (NBLK * kNS);
+template <int NBLK, bool F8>
+constexpr int kLoadsBehindLse = F8 ? 1 : kSubInstr - kSubInstr / (NBLK * kNS);
 
-template <int NBLK, int PAR, bool W>
+template <int NBLK, int PAR, bool W, bool F8>
 __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], const LaneConst &lc, uint32_t koff0,
                                            uint32_t koff1, uint32_t wstats_ad, int lo0, int hi0, int lane,
                                            const KIssue &ki, const uint32_t (&voff)[2], const uint64_t *lse_row,
                                            const float *look_row, int rows_pad, uint32_t xlse_ad)
 {
-    constexpr int kPerStep = kSubInstr / (NBLK * kNS);   // tile-load instructions issued after each MFMA step
+    // tile-load instructions issued after each MFMA step (8-bit keys: two in all, after the first two steps)
+    constexpr int kPerStep = F8 ? 1 : kSubInstr / (NBLK * kNS);
+    constexpr int kLate = F8 ? 0 : kPerStep;             // after the third and fourth step
     const int hf = lane >> 5;
     if constexpr (W) {
         // head_dim 128: the two sub-tiles are the two halves of the rows of this wave's 32 keys
@@ -546,7 +595,8 @@ __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], cons
     }
     const int lo1 = lo0 - 32, hi1 = hi0 - 32;      // this wave's keys lo0 <= key < hi0 (of 64) are the workgroup's
     bf16x8 qf[kKS];
-    lift_k_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, qf);
+    if (F8) lift_k8_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, qf);
+    else lift_k_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, qf);
     f32x16 da = logits32(kf[0], qf);
     f32x16 db = logits32(kf[1], qf);
     float m = neg_inf(), l = 0.f;
@@ -566,11 +616,11 @@ __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], cons
         db = logits32(kf[1], qf);
         m = neg_inf(); l = 0.f;
         fold_logits(da, m, l, c, lo0, hi0, hf);
-        k_issue<kPerStep>(ki, voff, 2 * kPerStep);
+        k_issue<kLate>(ki, voff, 2 * kPerStep);
         __builtin_amdgcn_sched_barrier(0);
         fold_logits(db, m, l, c, lo1, hi1, hf);
         store_row_stats(wstats_ad + 256, m, l, c, hf);
-        k_issue<kPerStep>(ki, voff, 3 * kPerStep);
+        k_issue<kLate>(ki, voff, 3 * kPerStep);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -689,7 +739,7 @@ struct Walk {
 // ones it needs.
 // EXTRA selects the variant that also serves paged keys (an upper bound on the tile's rows) and
 // lookahead keys in the normaliser; the plain variant carries none of their code or registers.
-template <int NB, int GB, int SLOT, int PAR, bool EXTRA, bool W>
+template <int NB, int GB, int SLOT, int PAR, bool EXTRA, bool W, bool F8>
 __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, const GroupTable &gt, int s, int n_phases, Ring &ring,
                                      Acc<NB> &acc, const LaneConst &lc, Walk &wk, unsigned char *lds, uint32_t lds0,
                                      uint64_t wave_off, int r_range)
@@ -705,7 +755,15 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
     const int pd = s - 2;                 // phase whose duty rows are combined in this step
     const int pl = s - kLag;              // phase whose normalisers are fetched in this step
     const bool do_stats = s < n_phases, do_prob = pc >= 0 && pc < n_phases;
-    const uint32_t stride_bytes = (uint32_t)a.k_stride_token * 2u;
+    constexpr int kSI = F8 ? kSubInstr / 2 : kSubInstr;     // tile-load instructions per sub-tile
+    constexpr int kMid = F8 ? 1 : 2;                        // of them, for sub-tile 0: issued right after the barrier
+    constexpr uint32_t kElem = F8 ? 1u : 2u;                // bytes per key element
+    const uint32_t stride_bytes = (uint32_t)a.k_stride_token * kElem;
+    // 8-bit keys: the exponent's scale of a phase is c times that phase's key scale
+    const float c_stats = F8 ? a.c * a.kscale[clampi(s, 0, n_phases - 1)] : a.c;
+    const float c_pub = F8 ? a.c * a.kscale[clampi(pp, 0, n_phases - 1)] : a.c;
+    const float c_duty = F8 ? a.c * a.kscale[clampi(pd, 0, n_phases - 1)] : a.c;
+    const float ks_prob = F8 ? a.kscale[clampi(pc, 0, n_phases - 1)] : 1.f;
     // Duty blocks of a phase: kDutyRows consecutive rows of one prompt (launches over several prompts have
     // blocks_per_prompt of them for each); block i goes to workgroup dfirst + i. src_w0 / src_n: the
     // workgroups whose partials the block combines (its prompt's), lse_idx: the prompt's row of normalisers.
@@ -752,7 +810,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
             for (int i = 1; i < kFWaves; ++i) m = fmaxf(m, pm[i]);
             float l = 0.f;
 #pragma unroll
-            for (int i = 0; i < kFWaves; ++i) l += pl8[i] * fast_exp2((pm[i] - m) * a.c);
+            for (int i = 0; i < kFWaves; ++i) l += pl8[i] * fast_exp2((pm[i] - m) * c_pub);
             if (lane < a.rows_pad) {
                 const uint64_t bits = (uint64_t)__float_as_uint(m) | ((uint64_t)__float_as_uint(l) << 32) |
                                       ((uint64_t)((pp / kSlots) & 1) << 63);
@@ -773,7 +831,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
     KIssue ki;
     ki.lds_dst = lds0 + sub_slot_off(wave, slot_next, 0);
     ki.base = kbase;
-    ki.step_bytes = 8u * stride_bytes;
+    ki.step_bytes = (F8 ? 16u : 8u) * stride_bytes;
     if (lc.qoff >= 0) {       // padding rows of the Q tiles stay zero; the Q blocks of consecutive phases are contiguous
         const uint32_t qblock = (uint32_t)(a.group * a.n_q * kD * 2) * (W ? 2u : 1u);
         const char *q1src = reinterpret_cast<const char *>(a.q) + (uint32_t)min(s + 1, n_phases - 1) * qblock;
@@ -781,27 +839,27 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
         dma_u<kOffQ1 + (1 - PAR) * kQTileBytes>((uint32_t)lc.qoff, q1src, lds0 + wave * 1024);
         dma_u<kOffQ2 + PAR * kQTileBytes>((uint32_t)lc.qoff, q2src, lds0 + wave * 1024);
     }
-    k_issue<kMidInstr>(ki, voff, 0);
+    k_issue<kMid>(ki, voff, 0);
 
     // ---- probability pass of phase pc; sub-tile 0 of K(s+1) ----
     {
         if (do_prob) {
             const uint32_t cinit_ad = lds0 + kOffCinit + (1 - PAR) * (kMaxRowsF * 4) + ((uint32_t)(lane & 32) << 1);
-            prob_pass<NB, GB, 1 - PAR, W>(ring.kf[SLOT], lc, cinit_ad, acc, ki, voff);
+            prob_pass<NB, GB, 1 - PAR, W, F8>(ring.kf[SLOT], lc, cinit_ad, acc, ki, voff, ks_prob);
             if (wk.c.kv == a.n_kv_heads - 1 && (a.layer_agg == SP_LAYER_MEAN || wk.c.layer == a.n_layers - 1))
                 close_layer<NB, W ? 1 : kNS>(acc, a.c);
         } else {
-            k_issue<kProbInstr>(ki, voff, kMidInstr);
+            k_issue<kSI - kMid>(ki, voff, kMid);
         }
     }
 
     // ---- lift K(s), statistics pass of phase s; sub-tile 1 of K(s+1) ----
-    vm_wait<kSubInstr>();                 // behind sub-tile 1 of K(s): at least the 4 loads of the prob part
+    vm_wait<kSI>();                       // behind sub-tile 1 of K(s): at least the loads of sub-tile 0 of K(s+1)
     {
         KIssue ki;
         ki.lds_dst = lds0 + sub_slot_off(wave, slot_next, 1);
         ki.base = kbase + (W ? (int64_t)(kD * 2) : (int64_t)32 * stride_bytes);     // W: the rows' second halves
-        ki.step_bytes = 8u * stride_bytes;
+        ki.step_bytes = (F8 ? 16u : 8u) * stride_bytes;
         const uint64_t *lse_row = wave == kLseWave ? a.lse + ((size_t)(clampi(pl, 0, n_phases - 1) % kSlots) * a.n_gp + a.p_idx) * a.rows_pad : nullptr;
         const float *look_row = nullptr;
         if (EXTRA && a.look != nullptr) look_row = a.look + (size_t)clampi(pl, 0, n_phases - 1) * a.rows_pad;
@@ -811,17 +869,17 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
         const int hi0 = EXTRA ? (r_range >> 16) - wave * kWaveKeys : kWaveKeys;
         if (do_stats) {
             const uint32_t wstats_ad = lds0 + kOffWstats + PAR * kWstatsBytes + wave * (kMaxRowsF * 8) + ((uint32_t)(lane & 31) << 3);
-            stats_pass<NB * GB, PAR, W>(a.c, ring.kf[SLOT], lc, sub_slot_off(wave, wk.slot0, 0),
+            stats_pass<NB * GB, PAR, W, F8>(c_stats, ring.kf[SLOT], lc, sub_slot_off(wave, wk.slot0, 0),
                                      sub_slot_off(wave, wk.slot0, 1), wstats_ad, lo0, hi0, lane, ki, voff, lse_row,
                                      look_row, a.rows_pad, lds0 + kOffXlse);
         } else {
             if (lse_row != nullptr) stage_exchange_rows(lds0 + kOffXlse, lse_row, look_row, a.rows_pad, lane);
-            k_issue<kSubInstr>(ki, voff, 0);
+            k_issue<kSI>(ki, voff, 0);
         }
     }
 
     // ---- pre-barrier: exchange data in, seeds out ----
-    if (wave == kLseWave) vm_wait<kLoadsBehindLse<NB * GB>>(); else vm_wait<2 * kSubInstr>();
+    if (wave == kLseWave) vm_wait<kLoadsBehindLse<NB * GB, F8>>(); else vm_wait<2 * kSI>();
     int *fail = reinterpret_cast<int *>(lds + kOffFail);
     if (wave == kDutyWave) {
         if (duty_blk >= 0) {
@@ -864,9 +922,9 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
                     m = wave_max(m);
                     float l = 0.f;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) l += pl4[q] * fast_exp2((pm[q] - m) * a.c);
+                    for (int q = 0; q < 4; ++q) l += pl4[q] * fast_exp2((pm[q] - m) * c_duty);
                     l = wave_sum(l);
-                    const float v = -(m + fast_log2(l) * a.inv_c);
+                    const float v = -(m + fast_log2(l) * (F8 ? 1.0f / c_duty : a.inv_c));
                     if (lane == r) mine = v;
                 }
                 // a duty that could not be completed (now or because the workgroup has failed before)
@@ -912,7 +970,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
             ++wk.k.layer;
             wk.kptr = reinterpret_cast<const char *>(kp.p[wk.k.layer]) + wave_off;
         } else {
-            wk.kptr += (uint64_t)a.k_stride_head * 2u;
+            wk.kptr += (uint64_t)a.k_stride_head * kElem;
         }
     }
     phase_advance(wk.c, s - 3, n_phases, a.n_kv_heads);
@@ -966,10 +1024,15 @@ __device__ __forceinline__ void fold_model_constants(FusedArgs &a)
 // W: head_dim 128. A workgroup owns 256 keys, a wave 32; the two "sub-tiles" of a wave are the two
 // 64-element halves of its keys' rows (same transit ring, same fragment ring: kf[s][t] holds MFMA
 // k-step 4s + t), Q tiles hold 32 rows as two half-tiles, and a logit is one chain of eight MFMA steps.
-template <int NB, int GB, bool EXTRA, class M, bool W = false>
+// F8: 8-bit keys (head_dim 64): rows of 64 codes, sub-tiles of 2 KB fetched by two instructions of 16 rows,
+// widened to bf16 at the lift; every phase has its own key scale.
+template <int NB, int GB, bool EXTRA, class M, bool W = false, bool F8 = false>
 __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, LayerPtrs kp, GroupTable gt)
 {
     static_assert(!W || (NB == 1 && GB == 1 && !M::kFixed), "head_dim 128: one block of 32 query rows");
+    static_assert(!F8 || (!W && !EXTRA), "8-bit keys: plain head_dim 64 variant only");
+    constexpr int kSI = F8 ? kSubInstr / 2 : kSubInstr;
+    constexpr uint32_t kElem = F8 ? 1u : 2u;
     constexpr int kTile = W ? kFTile / 2 : kFTile;            // keys per workgroup
     constexpr int kWaveKeys = kTile / kFWaves;
     constexpr int kHeadDim = W ? 2 * kD : kD;
@@ -1009,7 +1072,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     const int r_hi = (int)(p_len - j0l < kTile ? p_len - j0l : kTile);
     const int r_range = r_lo | (r_hi << 16);
     const uint32_t lds0 = lds_addr(lds);
-    const uint32_t stride_bytes = (uint32_t)a.k_stride_token * 2u;
+    const uint32_t stride_bytes = (uint32_t)a.k_stride_token * kElem;
 
     // zero the Q tiles (their padding rows are never loaded), seed the accumulator seeds with -inf
     {
@@ -1025,11 +1088,19 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     LaneConst lc;
 #pragma unroll
     for (int t = 0; t < kKS; ++t) lc.ld[t] = lds0 + 16u * (uint32_t)lds_slot<kD>(col, 2 * t + hf);
+    // 8-bit sub-tile: row r at 64 r, its four 16-byte chunks XOR-swizzled by (r >> 2) & 3 (eight-byte reads of
+    // 64 lanes then spread over all banks twice, which is what 512 bytes need anyway)
+#pragma unroll
+    for (int t = 0; t < kKS; ++t) lc.ld8[t] = lds0 + 64u * (uint32_t)col + ((((uint32_t)t ^ ((uint32_t)col >> 2)) & 3u) << 4) + 8u * (uint32_t)hf;
     {
-        const uint32_t rowpart = (uint32_t)(lane >> 3) * stride_bytes;
+        uint32_t rowpart = (uint32_t)(lane >> 3) * stride_bytes;
         const uint32_t swz = (uint32_t)(lane >> 4);               // (row >> 1) & 7 of row = lane >> 3 in an even instruction
         lc.koff[0] = rowpart + (((uint32_t)(lane & 7) ^ swz) << 4);
         lc.koff[1] = rowpart + (((uint32_t)(lane & 7) ^ (swz | 4u)) << 4);
+        if (F8) {       // an instruction moves 16 rows of 64 bytes: row lane >> 2, chunk (lane & 3) ^ ((row >> 2) & 3)
+            rowpart = (uint32_t)(lane >> 2) * stride_bytes;
+            lc.koff[0] = lc.koff[1] = rowpart + ((((uint32_t)lane & 3u) ^ (((uint32_t)lane >> 4) & 3u)) << 4);
+        }
         // a wave's slice of a Q tile: 8 rows (W: of one half-tile, waves 4..7 take the second halves)
         const int row = (W ? (wave & 3) : wave) * 8 + (lane >> 3);
         int g, n;
@@ -1051,7 +1122,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
 
     // byte offset of this wave's first key within a (layer, kv head): uniform, kept in scalar registers
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    uint64_t wave_off = (uint64_t)(j0 + wave_u * kWaveKeys) * (uint64_t)a.k_stride_token * 2u;
+    uint64_t wave_off = (uint64_t)(j0 + wave_u * kWaveKeys) * (uint64_t)a.k_stride_token * kElem;
     if (paged) {
         const int64_t page = j0 / a.page_tokens;
         wave_off = ((uint64_t)a.block_table[page] * (uint64_t)a.page_stride +
@@ -1066,15 +1137,15 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
         KIssue ki;
         ki.lds_dst = lds0 + sub_slot_off(wave_u, 0, s2);
         ki.base = reinterpret_cast<const char *>(kp.p[0]) + wave_off + (W ? (uint64_t)(s2 * kD * 2) : (uint64_t)(s2 * 32) * stride_bytes);
-        ki.step_bytes = 8u * stride_bytes;
-        k_issue<kSubInstr>(ki, lc.koff, 0);
+        ki.step_bytes = (F8 ? 16u : 8u) * stride_bytes;
+        k_issue<kSI>(ki, lc.koff, 0);
     }
     vm_wait<0>();
     lds_barrier();
 
     Walk wk;
     wk.k = phase_at(1, n_phases, a.n_kv_heads);
-    wk.kptr = reinterpret_cast<const char *>(kp.p[wk.k.layer]) + (uint64_t)wk.k.kv * (uint64_t)a.k_stride_head * 2u + wave_off;
+    wk.kptr = reinterpret_cast<const char *>(kp.p[wk.k.layer]) + (uint64_t)wk.k.kv * (uint64_t)a.k_stride_head * kElem + wave_off;
     wk.c = phase_at(0, n_phases, a.n_kv_heads);
     wk.slot0 = 0;
     wk.dfirst = 0;
@@ -1085,10 +1156,10 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     // instruction stream uniform. The last probability pass (phase n_phases - 1) runs in step n_phases + 3.
     const int n_steps = (n_phases + kLag + 1 + 3) / 4 * 4;
     for (int s0 = 0; s0 < n_steps; s0 += 4) {
-        step<NB, GB, 0, 0, EXTRA, W>(a, kp, gt, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 1, 1, EXTRA, W>(a, kp, gt, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 2, 0, EXTRA, W>(a, kp, gt, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
-        step<NB, GB, 3, 1, EXTRA, W>(a, kp, gt, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 0, 0, EXTRA, W, F8>(a, kp, gt, s0 + 0, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 1, 1, EXTRA, W, F8>(a, kp, gt, s0 + 1, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 2, 0, EXTRA, W, F8>(a, kp, gt, s0 + 2, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
+        step<NB, GB, 3, 1, EXTRA, W, F8>(a, kp, gt, s0 + 3, n_phases, ring, acc, lc, wk, lds, lds0, wave_off, r_range);
     }
     vm_wait<0>();               // no direct-to-LDS load may outlive the workgroup
     lds_barrier();
@@ -1177,6 +1248,21 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, const GroupTable *group, bool
     // with NaN scores and the status word set instead of hanging.
     const bool extra = a.look != nullptr || a.block_table != nullptr || gt.n > 0;
     const dim3 grid(a.n_wg), block(kFThreads);
+    if (a.kscale != nullptr) {              // 8-bit keys
+        if (a.head_dim != kD || extra)
+            return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel, 8-bit keys: head_dim 64, one prompt, contiguous keys only");
+        const bool draft8 = a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
+                            a.c == kScaleEighthLog2e && a.inv_c == 1.0f / kScaleEighthLog2e;
+        if (draft8 && a.n_q == 16 && a.n_wg == 256) hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 256>, false, true>), grid, block, 0, st, a, kp, gt);
+        else if (draft8 && a.n_q == 16) hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 0>, false, true>), grid, block, 0, st, a, kp, gt);
+        else if (draft8 && a.n_q == 8) hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, Draft16x32x8<8, 0>, false, true>), grid, block, 0, st, a, kp, gt);
+        else if (a.n_nblk == 2 && a.n_gblk == 1) hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, AnyModel, false, true>), grid, block, 0, st, a, kp, gt);
+        else if (a.n_nblk == 1 && a.n_gblk == 2) hipLaunchKernelGGL((sp_fused_kernel<1, 2, false, AnyModel, false, true>), grid, block, 0, st, a, kp, gt);
+        else if (a.n_nblk == 1 && a.n_gblk == 1) hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, AnyModel, false, true>), grid, block, 0, st, a, kp, gt);
+        else return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel: %d x %d row blocks", a.n_nblk, a.n_gblk);
+        SP_HIP_CHECK(hipGetLastError());
+        return SP_OK;
+    }
     if (a.head_dim == 2 * kD) {
         if (a.n_nblk != 1 || a.n_gblk != 1)
             return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel, head_dim 128: %d x %d row blocks", a.n_nblk, a.n_gblk);
@@ -1186,7 +1272,7 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, const GroupTable *group, bool
         return SP_OK;
     }
     // the fixed-model instantiations apply when every folded constant equals the call's value
-    const bool draft_shape = a.head_dim == kD && a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
+    const bool draft_shape = a.kscale == nullptr && a.head_dim == kD && a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
                              a.c == kScaleEighthLog2e && a.inv_c == 1.0f / kScaleEighthLog2e;
     const bool draft = !extra && draft_shape;
     const bool draft_batch = draft_shape && gt.n > 0 && a.look == nullptr && a.block_table == nullptr;    // several prompts a launch

@@ -36,6 +36,7 @@ struct FusedArgs {
     uint32_t *err;               // the call's status word: raised by any workgroup whose bounded wait gave up
     uint32_t spin_max;           // polls before a wait gives up
     int32_t force_miss;          // test hook: duty waves treat their partials as never arriving
+    const float *kscale;         // 8-bit keys (E4M3 codes): [n_phases] scale of each (layer, kv head); null: bf16 keys
     const float *look;           // [n_phases][rows_pad] log-sum-exp of each row over its visible lookahead keys
                                  // (raw-logit units, -inf for none), or null: prompt keys only
     const int32_t *block_table;  // paged keys: token j of a layer sits in page block_table[j / page_tokens] of that

@@ -28,13 +28,26 @@ FP8_SHAPES = [
     ("fp8_one_key", 2, 4, 2, 64, 8, 1),
     ("fp8_g4_nq8_d64_long", 2, 8, 2, 64, 8, 40000),          # past the length where bf16 keys take the single-launch kernel
     ("fp8_layer_split_d128", 3, 2, 1, 128, 4, 70001),
+    # head_dim 64 at the lengths of the single-launch kernel: its variant for 8-bit keys
+    ("fp8_fused_g4_nq16_tail", 2, 8, 2, 64, 16, 40000 + 64),
+    ("fp8_fused_g8_nq8_two_gblocks", 1, 16, 2, 64, 8, 34000),
+    ("fp8_fused_g3_nq5_padding", 2, 6, 2, 64, 5, 35000),
+    ("fp8_fused_20_phases", 5, 8, 4, 64, 16, 33000),
+    ("fp8_fused_full_grid", 1, 4, 1, 64, 8, 131072 - 100),
+    # the instantiations with a fixed model shape (16 layers, 32 / 8 heads)
+    ("fp8_fused_draft_model_nq8", 16, 32, 8, 64, 8, 33000),
+    ("fp8_fused_draft_model_nq16", 16, 32, 8, 64, 16, 32768 + 513),
+    ("fp8_fused_draft_model_nq16_full_grid", 16, 32, 8, 64, 16, 131072 - 100),
 ]
 
 
 @pytest.mark.parametrize("shape", FP8_SHAPES, ids=[s[0] for s in FP8_SHAPES])
 def test_score_fp8_matches_oracle(shape):
-    from gpu_util import assert_scores_close, gpu_score_fp8
+    import paper_2603_02631_amd as sp
+    from gpu_util import assert_scores_close, gpu_score_fp8, make_desc
     name, Lyr, H, Hkv, d, n_q, L = shape
+    fused = sp.sp_score_fp8_is_fused(make_desc(Lyr, H, Hkv, d, n_q, 0.125, 0, "HND", L), L)
+    assert fused == (1 if ("fused" in name or name == "fp8_g4_nq8_d64_long") else 0)
     say(f"[score-fp8] {name} Lyr={Lyr} H={H} Hkv={Hkv} d={d} n_q={n_q} L={L}")
     w = synth.Workload(name, 300 + FP8_SHAPES.index(shape), Lyr, H, Hkv, d, n_q, L, hh_frac_num=1, hh_frac_den=100)
     inp = synth.make_score_inputs(w)
