@@ -180,8 +180,8 @@ sp_status sp_score_fp8(const sp_score_desc *desc, const void *q_dev,
  * rows, 96 to 256 workgroups (about 24K to 64K tokens). Results are the same
  * either way (to rounding); this is for reporting. Host-only. */
 int32_t sp_score_is_fused(const sp_score_desc *desc, int64_t L);
-/* The same for sp_score_fp8: its single-launch variant exists for head_dim 64 with
- * key strides that are multiples of 16 elements, at the lengths above. */
+/* The same for sp_score_fp8: its single-launch variants need key strides that are
+ * multiples of 16 elements; shapes and lengths as above. */
 int32_t sp_score_fp8_is_fused(const sp_score_desc *desc, int64_t L);
 
 /*

@@ -644,12 +644,11 @@ bool fused_applies(const Plan &p, int64_t L, int64_t k_stride_token)
     return n_wg >= fused_min_workgroups(p) && n_wg <= 256 && n_wg <= device_compute_units();
 }
 
-// 8-bit keys: the single-launch kernel has a head_dim 64 variant for them (rows of 64 codes fetched in 16-byte
-// pieces: strides in multiples of 16 elements).
+// 8-bit keys: the single-launch kernel's variants for them fetch the codes in 16-byte pieces (strides in
+// multiples of 16 elements).
 bool fused_applies_fp8(const Plan &p, const sp_score_desc *desc, int64_t L)
 {
-    return p.D == 64 && desc->k_stride_token % 16 == 0 && desc->k_stride_head % 16 == 0 &&
-           fused_applies(p, L, desc->k_stride_token);
+    return desc->k_stride_token % 16 == 0 && desc->k_stride_head % 16 == 0 && fused_applies(p, L, desc->k_stride_token);
 }
 
 // A ragged batch on the single-launch kernel: the prompts are packed into launches of at most one

@@ -434,8 +434,11 @@ __device__ __forceinline__ void prob_pass(const bf16x8 (&kf)[kNS][kKS], const La
 #pragma unroll
         for (int t = 0; t < kKS; ++t) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q1[t], kf[1][t], d, 0, 0, 0);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc.mx[0][0][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[0][0][e]);
-        k_issue<1>(ki, voff, kMid + 1);
+        for (int e = 0; e < 4; ++e) {
+            if (F8) acc.mx[0][0][e] = fmaxf(acc.mx[0][0][e], fmaxf(max3(d[e], d[4 + e], d[8 + e]), d[12 + e]) * ks);
+            else acc.mx[0][0][e] = max3(max3(d[e], d[4 + e], d[8 + e]), d[12 + e], acc.mx[0][0][e]);
+        }
+        if (!F8) k_issue<1>(ki, voff, kMid + 1);
         __builtin_amdgcn_sched_barrier(0);
         return;
     }
@@ -578,7 +581,8 @@ __device__ __forceinline__ void stats_pass(float c, bf16x8 (&kf)[kNS][kKS], cons
         // head_dim 128: the two sub-tiles are the two halves of the rows of this wave's 32 keys
         static_assert(NBLK == 1, "one block of 32 query rows");
         bf16x8 q0[kKS], q1[kKS];
-        lift_k_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, q0);
+        if (F8) lift_k8_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, q0);
+        else lift_k_and_q<kOffQ1 + PAR * kQTileBytes>(lc, koff0, koff1, kf, q0);
         lift_at<kOffQ1 + PAR * kQTileBytes + kWideHalf>(lc, q1);
         f32x16 d = logits32(kf[0], q0);
 #pragma unroll
@@ -858,7 +862,7 @@ __device__ __forceinline__ void step(const FusedArgs &a, const LayerPtrs &kp, co
     {
         KIssue ki;
         ki.lds_dst = lds0 + sub_slot_off(wave, slot_next, 1);
-        ki.base = kbase + (W ? (int64_t)(kD * 2) : (int64_t)32 * stride_bytes);     // W: the rows' second halves
+        ki.base = kbase + (W ? (int64_t)(kD * kElem) : (int64_t)32 * stride_bytes);     // W: the rows' second halves
         ki.step_bytes = (F8 ? 16u : 8u) * stride_bytes;
         const uint64_t *lse_row = wave == kLseWave ? a.lse + ((size_t)(clampi(pl, 0, n_phases - 1) % kSlots) * a.n_gp + a.p_idx) * a.rows_pad : nullptr;
         const float *look_row = nullptr;
@@ -1030,7 +1034,7 @@ template <int NB, int GB, bool EXTRA, class M, bool W = false, bool F8 = false>
 __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, LayerPtrs kp, GroupTable gt)
 {
     static_assert(!W || (NB == 1 && GB == 1 && !M::kFixed), "head_dim 128: one block of 32 query rows");
-    static_assert(!F8 || (!W && !EXTRA), "8-bit keys: plain head_dim 64 variant only");
+    static_assert(!F8 || !EXTRA, "8-bit keys: plain variants only");
     constexpr int kSI = F8 ? kSubInstr / 2 : kSubInstr;
     constexpr uint32_t kElem = F8 ? 1u : 2u;
     constexpr int kTile = W ? kFTile / 2 : kFTile;            // keys per workgroup
@@ -1136,7 +1140,7 @@ __global__ __launch_bounds__(kFThreads, 2) void sp_fused_kernel(FusedArgs a, Lay
     for (int s2 = 0; s2 < kNS; ++s2) {
         KIssue ki;
         ki.lds_dst = lds0 + sub_slot_off(wave_u, 0, s2);
-        ki.base = reinterpret_cast<const char *>(kp.p[0]) + wave_off + (W ? (uint64_t)(s2 * kD * 2) : (uint64_t)(s2 * 32) * stride_bytes);
+        ki.base = reinterpret_cast<const char *>(kp.p[0]) + wave_off + (W ? (uint64_t)(s2 * kD * kElem) : (uint64_t)(s2 * 32) * stride_bytes);
         ki.step_bytes = (F8 ? 16u : 8u) * stride_bytes;
         k_issue<kSI>(ki, lc.koff, 0);
     }
@@ -1249,8 +1253,14 @@ sp_status launch(FusedArgs a, const LayerPtrs &kp, const GroupTable *group, bool
     const bool extra = a.look != nullptr || a.block_table != nullptr || gt.n > 0;
     const dim3 grid(a.n_wg), block(kFThreads);
     if (a.kscale != nullptr) {              // 8-bit keys
-        if (a.head_dim != kD || extra)
-            return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel, 8-bit keys: head_dim 64, one prompt, contiguous keys only");
+        if (extra) return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel, 8-bit keys: one prompt, contiguous keys only");
+        if (a.head_dim == 2 * kD) {
+            if (a.n_nblk != 1 || a.n_gblk != 1)
+                return sp::fail(SP_ERR_UNSUPPORTED, "fused score kernel, head_dim 128: %d x %d row blocks", a.n_nblk, a.n_gblk);
+            hipLaunchKernelGGL((sp_fused_kernel<1, 1, false, AnyModel, true, true>), grid, block, 0, st, a, kp, gt);
+            SP_HIP_CHECK(hipGetLastError());
+            return SP_OK;
+        }
         const bool draft8 = a.n_layers == 16 && a.n_q_heads == 32 && a.n_kv_heads == 8 && a.k_stride_token == kD &&
                             a.c == kScaleEighthLog2e && a.inv_c == 1.0f / kScaleEighthLog2e;
         if (draft8 && a.n_q == 16 && a.n_wg == 256) hipLaunchKernelGGL((sp_fused_kernel<2, 1, false, Draft16x32x8<16, 256>, false, true>), grid, block, 0, st, a, kp, gt);

@@ -34,6 +34,10 @@ FP8_SHAPES = [
     ("fp8_fused_g3_nq5_padding", 2, 6, 2, 64, 5, 35000),
     ("fp8_fused_20_phases", 5, 8, 4, 64, 16, 33000),
     ("fp8_fused_full_grid", 1, 4, 1, 64, 8, 131072 - 100),
+    # head_dim 128 on the single-launch kernel
+    ("fp8_fused_d128_g2_nq8", 3, 4, 2, 128, 8, 25000),
+    ("fp8_fused_d128_g4_nq5_tail", 2, 8, 2, 128, 5, 24576 + 1),
+    ("fp8_fused_d128_full_grid", 1, 4, 2, 128, 8, 65536 - 100),
     # the instantiations with a fixed model shape (16 layers, 32 / 8 heads)
     ("fp8_fused_draft_model_nq8", 16, 32, 8, 64, 8, 33000),
     ("fp8_fused_draft_model_nq16", 16, 32, 8, 64, 16, 32768 + 513),
