@@ -206,7 +206,8 @@ constexpr int kOneWaves = kOneThreads / 64;
 constexpr int kOneSpans = 1024;              // spans the single launch holds in LDS
 static_assert(kOneSpans == kOneThreads, "the merge scan takes one span per thread");
 constexpr int kCoarse = 4096;                // entries of the coarse index
-constexpr int kMaskPerThread = 2;            // target tokens per thread of a mask workgroup
+constexpr int kMaskPerThread = 2;            // target tokens per thread of a mask workgroup: one prompt (more, smaller workgroups) ...
+constexpr int kMaskPerThreadBatch = 8;       // ... a ragged batch (measured: 14.8 vs 17.5 µs and 19.6 vs 30.4 µs)
 
 struct OneSmem {
     int64_t coarse[kCoarse];                 // target_off[i * stride]
@@ -254,6 +255,7 @@ __device__ __forceinline__ int64_t read_lane64(int64_t v, int l)
 }
 
 // Requires max_spans <= kOneSpans (one scan segment: kOneSpans == kOneThreads) and M < 2^31.
+template <int kMaskPerThread>
 __device__ __forceinline__ void project_one_body(
     const int64_t *__restrict__ draft_off, int64_t L, const int64_t *__restrict__ target_off, int M,
     const int64_t *__restrict__ spans, const int32_t *__restrict__ n_spans_p, int max_spans, int stride,
@@ -417,8 +419,8 @@ __global__ __launch_bounds__(kOneThreads) void sp_project_one_kernel(
     int n_coarse, int64_t *__restrict__ tspans, int32_t *__restrict__ n_tspans, int64_t *__restrict__ n_kept,
     uint8_t *__restrict__ mask)
 {
-    project_one_body(draft_off, L, target_off, M, spans, n_spans_p, max_spans, stride, n_coarse, tspans, n_tspans, n_kept,
-                     mask);
+    project_one_body<kMaskPerThread>(draft_off, L, target_off, M, spans, n_spans_p, max_spans, stride, n_coarse, tspans,
+                                     n_tspans, n_kept, mask);
 }
 
 // Ragged batch: prompt b = blockIdx.y. Its L_b + 1 draft offsets start at off[b] + b of the packed array,
@@ -435,12 +437,12 @@ __global__ __launch_bounds__(kOneThreads) void sp_project_batch_kernel(
     const int M = (int)(moff[b + 1] - mo);
     const int64_t k0 = kept_off[b];
     const int max_spans = (int)(kept_off[b + 1] - k0);
-    if (blockIdx.x > 0 && ((int64_t)blockIdx.x - 1) * (kOneThreads * kMaskPerThread) >= M) return;   // past this prompt's mask
+    if (blockIdx.x > 0 && ((int64_t)blockIdx.x - 1) * (kOneThreads * kMaskPerThreadBatch) >= M) return;   // past this prompt's mask
     if (L < 1 || M < 1 || max_spans < 1) {           // nothing kept (uniform: no barrier is skipped by part of a workgroup)
         if (blockIdx.x == 0 && threadIdx.x == 0) { n_tspans[b] = 0; n_kept[b] = 0; }
         if (blockIdx.x > 0 && mask)
-            for (int k = 0; k < kMaskPerThread; ++k) {
-                const int64_t t = ((int64_t)blockIdx.x - 1) * (kOneThreads * kMaskPerThread) + (int64_t)k * kOneThreads + threadIdx.x;
+            for (int k = 0; k < kMaskPerThreadBatch; ++k) {
+                const int64_t t = ((int64_t)blockIdx.x - 1) * (kOneThreads * kMaskPerThreadBatch) + (int64_t)k * kOneThreads + threadIdx.x;
                 if (t < M) mask[mo + t] = 0;
             }
         return;
@@ -448,7 +450,7 @@ __global__ __launch_bounds__(kOneThreads) void sp_project_batch_kernel(
     if (blockIdx.x > 0 && !mask) return;
     const int stride = (M + kCoarse) / kCoarse;          // ceil((M + 1) / kCoarse)
     const int n_coarse = (M + stride) / stride;          // ceil((M + 1) / stride)
-    project_one_body(draft_off + o + b, L, target_off + mo + b, M, spans + 2 * k0, n_spans + b, max_spans, stride,
+    project_one_body<kMaskPerThreadBatch>(draft_off + o + b, L, target_off + mo + b, M, spans + 2 * k0, n_spans + b, max_spans, stride,
                      n_coarse, tspans + 2 * k0, n_tspans + b, n_kept + b, mask ? mask + mo : nullptr);
 }
 
@@ -519,7 +521,7 @@ extern "C" sp_status sp_project_batch(const int64_t *draft_off_dev, const int64_
                             b, (long long)m, 63 * kCoarse);
         max_m = std::max(max_m, m);
     }
-    const int64_t mask_groups = keep_mask_dev ? sp::ceil_div(max_m, (int64_t)kOneThreads * kMaskPerThread) : 0;
+    const int64_t mask_groups = keep_mask_dev ? sp::ceil_div(max_m, (int64_t)kOneThreads * kMaskPerThreadBatch) : 0;
     hipLaunchKernelGGL(sp_project_batch_kernel, dim3((unsigned)(1 + mask_groups), (unsigned)B), dim3(kOneThreads), 0,
                        static_cast<hipStream_t>(hip_stream), draft_off_dev, offsets_dev, target_off_dev, moffsets_dev,
                        spans_dev, n_spans_dev, kept_off_dev, tspans_dev, n_tspans_dev, n_kept_dev, keep_mask_dev);
