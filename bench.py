@@ -35,8 +35,8 @@ ROTATE_BYTES = 2 << 30          # K buffers are rotated over at least this much 
 # It is reported only while the kernel sources are the ones the counters were taken on.
 TRAFFIC = {
     "workload": "long-128k",
-    "sources_sha256": "0258a3351a97b772383b9428347f33e6582f9caec1baf7dbdde7f8adad796a0c",
-    "fetch_bytes": 1090816.0 * 2048,      # FETCH_SIZE 1090816.0 per dispatch; the 1 GiB copy reads 524320 -> 2 KiB per count
+    "sources_sha256": "971240212852ba369836edad355ea8676dc7853e40188034fee0d7762d77563b",
+    "fetch_bytes": 1090799.0 * 2048,      # FETCH_SIZE 1090799.0 per dispatch; the 1 GiB copy reads 524314 -> 2 KiB per count
     "write_bytes": 16960.0 * 1024,        # WRITE_SIZE 16960.0 per dispatch; the 1 GiB copy writes 1048576 -> 1 KiB per count
 }
 KERNEL_SOURCES = ["sp_score_fused.hip", "sp_score_fused.hpp", "sp_score_dev.hpp"]     # the dominant kernel and its headers
