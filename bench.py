@@ -95,7 +95,7 @@ def main() -> int:
         print(kernel_sources_sha256())
         return 0
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+        print("bench.py: this library runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
         return 2
 
