@@ -163,8 +163,10 @@ sp_status sp_score_paged(const sp_score_desc *desc, const void *q_dev,
  * read: the key vector of (l, kv, j) is kscale[l][kv] * E4M3(code), and the
  * scores are those of sp_score on exactly these dequantised keys (the queries
  * stay bf16; products are exact, sums are fp32). NaN codes are the caller's to
- * avoid. Contiguous keys of one prompt only; three-kernel path (see
- * sp_score_is_fused), same workspace size as sp_score.
+ * avoid. Contiguous keys of one prompt only; same workspace size and the same
+ * choice between the two implementations as sp_score (sp_score_fp8_is_fused;
+ * the single-launch kernel fetches codes in 16-byte pieces and so needs both
+ * strides to be multiples of 16), same status word and failure behaviour.
  */
 sp_status sp_score_fp8(const sp_score_desc *desc, const void *q_dev,
                        const void *const *k8_layers_host, const float *kscale_dev,
